@@ -1,0 +1,182 @@
+/*
+ * gs.h -- C ABI of the MI355X (gfx950) per-layer optimizer step.
+ *
+ * The step is the one GreedySnake's vertical schedule produces once per layer
+ * (arxiv 2512.17570): the layer's k micro-batch gradients are accumulated in full precision
+ * (Sec. 2.1 "Gradient accumulation"; Sec. 3.4), the global L2 norm of the accumulated
+ * gradient is reduced for clipping (Sec. 2.1 "Pipelined optimizer step"), and an element-wise
+ * Adam(W) update is applied to the three full-precision states of every weight -- master
+ * parameter, momentum, variance (Sec. 2.2) -- after which the master parameter is converted
+ * to low precision to refresh the working parameter (Sec. 2.2, step (4) of the optimizer
+ * figure).  Because the update is element-wise it may be applied to any contiguous range:
+ * in full, split into an immediate part and a deferred part (delay ratio alpha, Sec. 4.4),
+ * or chunk by chunk over states that live in host memory (Sec. 2.2 chunk loop; Sec. 4.3).
+ *
+ * Conventions for every entry point
+ *   - Plain C types only.  "device" pointers are HIP device addresses, "host" pointers are
+ *     ordinary process addresses, "pinned host" pointers come from gs_pinned_alloc (or any
+ *     hipHostMalloc).  `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *   - bf16 tensors are arrays of uint16_t holding the upper half of an IEEE binary32.
+ *   - Element indices are int64_t.  Ranges are half-open [begin,end); begin == end is a
+ *     no-op that returns GS_OK.  begin/end need no alignment.  Every array argument is
+ *     indexed by the same absolute element index i in [begin,end); element 0 of each array
+ *     must be 16-byte aligned and the arrays must hold at least `end` elements.  Only
+ *     elements in [begin,end) are read or written.
+ *   - The caller owns all tensors and workspaces.  Pointer tables (`grads`) are host arrays
+ *     copied by value at call time; they may be freed as soon as the call returns.
+ *   - All device work is enqueued on `stream` and the call returns without waiting.
+ *   - Every argument is validated before the first HIP call; a rejected call has touched
+ *     nothing.  Functions return a gs_status; nothing throws or aborts.
+ *   - Results do not depend on how a range is partitioned: applying the step to [a,b) and
+ *     then to [b,c) gives bit-identical p, m, v, w to applying it to [a,c) (Sec. 6.5 requires
+ *     results that are reproducible across partition ratios).
+ */
+#ifndef GS_H
+#define GS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GS_OK = 0,
+    GS_ERR_INVALID_ARG = -1, /* null pointer, bad range, k out of [1,GS_MAX_K], bad hyper-parameter, misalignment */
+    GS_ERR_WORKSPACE = -2,   /* workspace missing or smaller than gs_sqnorm_workspace_bytes() */
+    GS_ERR_HIP = -3,         /* a HIP runtime call failed; see gs_last_hip_error() */
+    GS_ERR_NOMEM = -4        /* host or device allocation failed */
+} gs_status;
+
+/* Largest number of micro-batch gradient buffers one call accepts. */
+#define GS_MAX_K 32
+
+/*
+ * Hyper-parameters of one AdamW step.  The paper names the optimizer (Adam, three fp32
+ * states per weight, Sec. 2.2) but prints no arithmetic; the update implemented is
+ *     g  = c * sum_j grad_j                         (fp32 sum, j ascending, no 1/k)
+ *     m' = beta1*m + (1-beta1)*g
+ *     v' = beta2*v + (1-beta2)*g*g
+ *     p' = p*(1 - lr*weight_decay) - (lr/(1-beta1^t)) * m' / (sqrt(v')/sqrt(1-beta2^t) + eps)
+ *     w  = bf16_round_to_nearest_even(p')
+ * with t = step.  Requirements: lr >= 0, 0 <= beta1 < 1, 0 <= beta2 < 1, eps >= 0,
+ * weight_decay >= 0, all finite; step >= 1.  max_grad_norm <= 0 disables clipping.
+ * Both halves of a split step use the same hparams (same t).
+ */
+typedef struct {
+    float lr;
+    float beta1;
+    float beta2;
+    float eps;
+    float weight_decay;
+    float max_grad_norm;
+    int32_t step;
+} gs_adamw_hparams;
+
+/* ------------------------------------------------------------------------------------------
+ * Gradient norm (Sec. 2.1: clipping needs the global L2 norm over all gradients, so the
+ * optimizer waits for it).
+ * ------------------------------------------------------------------------------------------ */
+
+/* Bytes of device workspace gs_grad_sqnorm needs; a constant independent of n and k. */
+size_t gs_sqnorm_workspace_bytes(void);
+
+/*
+ * S = sum over i in [begin,end) of a_i^2, where a_i = sum_{j<k} float(grads[j][i]) is the
+ * fp32 accumulation of the k bf16 micro-batch gradients (j ascending).  Squares and the
+ * reduction are carried in fp64.  The result is deterministic for given arguments.
+ *   grads        host array of k device pointers (bf16, each >= end elements)
+ *   d_sqnorm     device double; receives S (accumulate == 0) or *d_sqnorm + S (accumulate != 0),
+ *                so a caller can build the global norm over several layers or ranges
+ *   d_workspace  device buffer of at least gs_sqnorm_workspace_bytes() bytes, 8-byte aligned;
+ *                contents need no initialisation and are clobbered.  Calls that share a
+ *                workspace must be ordered on one stream.
+ * begin == end writes 0 (or leaves *d_sqnorm unchanged when accumulating).
+ */
+gs_status gs_grad_sqnorm(const uint16_t *const *grads, int k, int64_t begin, int64_t end,
+                         double *d_sqnorm, int accumulate,
+                         void *d_workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Fused accumulate + clip + AdamW + bf16 emit (Sec. 2.1 gradient accumulation in full
+ * precision; Sec. 2.2 optimizer step over a parameter chunk; Sec. 4.4 partial update of
+ * (1-alpha) / alpha of a layer).
+ * ------------------------------------------------------------------------------------------ */
+
+/*
+ * Applies the update documented at gs_adamw_hparams to every element of [begin,end).
+ *   p, m, v   device fp32, updated in place
+ *   w_bf16    device bf16, written (never read)
+ *   grads     host array of k device pointers to bf16 gradient buffers, read only.  The fp32
+ *             sum of the k buffers lives in registers only; no accumulation buffer exists.
+ *   d_sqnorm  device double holding the TOTAL squared gradient norm (all layers / ranges that
+ *             are clipped together), as produced by gs_grad_sqnorm; read on the device when
+ *             the kernel runs, so no host synchronisation is needed between the two calls.
+ *             The clip coefficient is c = min(1, max_grad_norm / (sqrt(S) + 1e-6)).
+ *             NULL, or hp->max_grad_norm <= 0, means c = 1.
+ * Non-finite gradients propagate by IEEE rules into the states they touch; a NaN norm gives
+ * c = 1 and an infinite norm c = 0.  Callers that want to skip such a step read *d_sqnorm.
+ * Weight-decay exclusion (biases, LayerNorm) is done by calling per range with
+ * weight_decay = 0.
+ */
+gs_status gs_accum_adamw(float *p, float *m, float *v, uint16_t *w_bf16,
+                         const uint16_t *const *grads, int k, int64_t begin, int64_t end,
+                         const gs_adamw_hparams *hp, const double *d_sqnorm, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Streamed step for states that live in pinned host memory (Sec. 2.2: for each parameter
+ * chunk, load gradients + master parameters + optimizer states, step, write back; Sec. 4.3
+ * the five optimizer-step stages of the backward pipeline -- here the slow link is
+ * host<->device PCIe instead of SSD<->host).
+ * ------------------------------------------------------------------------------------------ */
+
+typedef struct gs_stream_ctx gs_stream_ctx;
+
+/*
+ * Creates a context that owns one H2D copy stream, one compute stream, one D2H copy stream,
+ * `slots` (>= 2) staging slots of 3 x chunk_elems fp32 in device memory, and the events that
+ * order them.  chunk_elems >= 1.  Returns GS_ERR_NOMEM if the slots cannot be allocated.
+ */
+gs_status gs_stream_ctx_create(gs_stream_ctx **out, int64_t chunk_elems, int slots);
+gs_status gs_stream_ctx_destroy(gs_stream_ctx *ctx); /* waits for pending work, frees everything */
+
+/*
+ * Applies the same update as gs_accum_adamw to all n elements of a layer whose p, m, v are in
+ * PINNED host memory, chunk by chunk: chunk c is copied host->slot on the H2D stream, updated
+ * by the fused kernel on the compute stream (gradients and w are device-resident and indexed
+ * by absolute element), and copied slot->host on the D2H stream; chunk c+1's upload and chunk
+ * c-1's download overlap chunk c's kernel.  Results are bit-identical to gs_accum_adamw on a
+ * device copy of the same states, for every chunk size.
+ *   h_p, h_m, h_v   pinned host fp32, n elements each, updated in place
+ *   d_w_bf16        device bf16, n elements, written
+ *   d_grads         host array of k device pointers (bf16, n elements each)
+ *   d_sqnorm        as for gs_accum_adamw (device double or NULL)
+ *   producer_stream stream on which the gradients and *d_sqnorm were produced; work already
+ *                   enqueued there is waited for before the first kernel (NULL = null stream)
+ * The call enqueues everything and returns; host buffers must stay untouched until
+ * gs_stream_ctx_sync.  Several layers may be enqueued back to back on one context.
+ */
+gs_status gs_stream_layer_step(gs_stream_ctx *ctx, float *h_p, float *h_m, float *h_v,
+                               uint16_t *d_w_bf16, const uint16_t *const *d_grads, int k, int64_t n,
+                               const gs_adamw_hparams *hp, const double *d_sqnorm,
+                               void *producer_stream);
+
+/* Blocks until everything enqueued on the context has finished (including the downloads). */
+gs_status gs_stream_ctx_sync(gs_stream_ctx *ctx);
+
+/* Page-locked host memory without power-of-two padding (Sec. 5 notes that a framework's
+ * pinned allocator may round each buffer up to a power of two; host-resident optimizer
+ * states of tens of GB cannot afford that).  Returns NULL on failure. */
+void *gs_pinned_alloc(size_t bytes);
+void gs_pinned_free(void *ptr);
+
+/* ------------------------------------------------------------------------------------------ */
+const char *gs_strerror(gs_status s);
+/* Text of the last HIP error seen by the calling thread ("" if none). */
+const char *gs_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GS_H */

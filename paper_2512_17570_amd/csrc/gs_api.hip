@@ -1,0 +1,183 @@
+// gs_api.hip -- the C ABI: argument validation, per-step constants, launch plumbing.
+// Every check runs before the first HIP call, so the error paths need no GPU.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+
+#include "gs_internal.h"
+
+namespace gs {
+
+static thread_local char g_hip_err[256] = "";
+
+gs_status hip_fail(hipError_t e, const char *what)
+{
+    snprintf(g_hip_err, sizeof g_hip_err, "%s: %s", what, hipGetErrorString(e));
+    return GS_ERR_HIP;
+}
+
+static bool finite_f(float x) { return std::isfinite(x); }
+
+gs_status validate_hparams(const gs_adamw_hparams *hp)
+{
+    if (!hp) return GS_ERR_INVALID_ARG;
+    if (!finite_f(hp->lr) || hp->lr < 0.0f) return GS_ERR_INVALID_ARG;
+    if (!finite_f(hp->beta1) || hp->beta1 < 0.0f || hp->beta1 >= 1.0f) return GS_ERR_INVALID_ARG;
+    if (!finite_f(hp->beta2) || hp->beta2 < 0.0f || hp->beta2 >= 1.0f) return GS_ERR_INVALID_ARG;
+    if (!finite_f(hp->eps) || hp->eps < 0.0f) return GS_ERR_INVALID_ARG;
+    if (!finite_f(hp->weight_decay) || hp->weight_decay < 0.0f) return GS_ERR_INVALID_ARG;
+    if (std::isnan(hp->max_grad_norm)) return GS_ERR_INVALID_ARG;
+    if (hp->step < 1) return GS_ERR_INVALID_ARG;
+    return GS_OK;
+}
+
+gs_status validate_grads(const uint16_t *const *grads, int k)
+{
+    if (!grads || k < 1 || k > GS_MAX_K) return GS_ERR_INVALID_ARG;
+    for (int j = 0; j < k; ++j) {
+        if (!grads[j] || (reinterpret_cast<uintptr_t>(grads[j]) & 15u)) return GS_ERR_INVALID_ARG;
+    }
+    return GS_OK;
+}
+
+// Bias corrections 1-beta^t and the derived factors: double on the host, one rounding to float.
+StepConsts make_consts(const gs_adamw_hparams &hp)
+{
+    StepConsts s;
+    const double b1 = hp.beta1, b2 = hp.beta2, t = (double)hp.step;
+    const double bc1 = 1.0 - std::pow(b1, t);
+    const double bc2 = 1.0 - std::pow(b2, t);
+    s.beta1 = hp.beta1;
+    s.beta2 = hp.beta2;
+    s.omb1 = (float)(1.0 - b1);
+    s.omb2 = (float)(1.0 - b2);
+    s.eps = hp.eps;
+    s.step_size = (float)((double)hp.lr / bc1);
+    s.rsbc2 = (float)std::sqrt(bc2);
+    s.decay = (float)(1.0 - (double)hp.lr * (double)hp.weight_decay);
+    return s;
+}
+
+// Compute-unit count of the current device (cached per device ordinal).
+int device_num_cu(int *out_cu)
+{
+    static int cache[64] = {0};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= 64) dev = 0;
+    int cu = __atomic_load_n(&cache[dev], __ATOMIC_RELAXED);
+    if (cu == 0) {
+        e = hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return (int)hip_fail(e, "hipDeviceGetAttribute");
+        if (cu < 1) cu = 1;
+        __atomic_store_n(&cache[dev], cu, __ATOMIC_RELAXED);
+    }
+    *out_cu = cu;
+    return GS_OK;
+}
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace gs
+
+using namespace gs;
+
+extern "C" {
+
+size_t gs_sqnorm_workspace_bytes(void) { return (size_t)GS_SQNORM_MAX_BLOCKS * sizeof(double); }
+
+gs_status gs_grad_sqnorm(const uint16_t *const *grads, int k, int64_t begin, int64_t end,
+                         double *d_sqnorm, int accumulate,
+                         void *d_workspace, size_t workspace_bytes, void *stream)
+{
+    gs_status st = validate_grads(grads, k);
+    if (st != GS_OK) return st;
+    if (begin < 0 || end < begin) return GS_ERR_INVALID_ARG;
+    if (!d_sqnorm || (reinterpret_cast<uintptr_t>(d_sqnorm) & 7u)) return GS_ERR_INVALID_ARG;
+    if (!d_workspace || workspace_bytes < gs_sqnorm_workspace_bytes()) return GS_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(d_workspace) & 7u) return GS_ERR_WORKSPACE;
+    if (begin == end && accumulate) return GS_OK;
+
+    int cu = 0;
+    if (device_num_cu(&cu) != GS_OK) return GS_ERR_HIP;
+    SqnormArgs A;
+    memset(&A, 0, sizeof A);
+    for (int j = 0; j < k; ++j) A.gt.g[j] = grads[j];
+    A.k = k;
+    A.begin = begin;
+    A.end = end;
+    A.partials = static_cast<double *>(d_workspace);
+    hipError_t e = launch_grad_sqnorm(A, d_sqnorm, accumulate, cu, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "gs_grad_sqnorm launch");
+    return GS_OK;
+}
+
+gs_status gs_accum_adamw(float *p, float *m, float *v, uint16_t *w_bf16,
+                         const uint16_t *const *grads, int k, int64_t begin, int64_t end,
+                         const gs_adamw_hparams *hp, const double *d_sqnorm, void *stream)
+{
+    if (!p || !m || !v || !w_bf16) return GS_ERR_INVALID_ARG;
+    if (!aligned16(p) || !aligned16(m) || !aligned16(v) || !aligned16(w_bf16)) return GS_ERR_INVALID_ARG;
+    gs_status st = validate_grads(grads, k);
+    if (st != GS_OK) return st;
+    if (begin < 0 || end < begin) return GS_ERR_INVALID_ARG;
+    st = validate_hparams(hp);
+    if (st != GS_OK) return st;
+    if (d_sqnorm && (reinterpret_cast<uintptr_t>(d_sqnorm) & 7u)) return GS_ERR_INVALID_ARG;
+    if (begin == end) return GS_OK;
+
+    int cu = 0;
+    if (device_num_cu(&cu) != GS_OK) return GS_ERR_HIP;
+    StepArgs A;
+    memset(&A, 0, sizeof A);
+    A.p = p;
+    A.m = m;
+    A.v = v;
+    A.w = w_bf16;
+    for (int j = 0; j < k; ++j) A.gt.g[j] = grads[j];
+    A.k = k;
+    A.begin = begin;
+    A.end = end;
+    A.c = make_consts(*hp);
+    A.max_norm = hp->max_grad_norm;
+    A.d_sqnorm = d_sqnorm;
+    hipError_t e = launch_accum_adamw(A, cu, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "gs_accum_adamw launch");
+    return GS_OK;
+}
+
+void *gs_pinned_alloc(size_t bytes)
+{
+    if (bytes == 0) return nullptr;
+    void *ptr = nullptr;
+    hipError_t e = hipHostMalloc(&ptr, bytes, hipHostMallocDefault);
+    if (e != hipSuccess) {
+        hip_fail(e, "hipHostMalloc");
+        return nullptr;
+    }
+    return ptr;
+}
+
+void gs_pinned_free(void *ptr)
+{
+    if (ptr) (void)hipHostFree(ptr);
+}
+
+const char *gs_strerror(gs_status s)
+{
+    switch (s) {
+    case GS_OK: return "ok";
+    case GS_ERR_INVALID_ARG: return "invalid argument";
+    case GS_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case GS_ERR_HIP: return "HIP runtime error";
+    case GS_ERR_NOMEM: return "out of memory";
+    }
+    return "unknown status";
+}
+
+const char *gs_last_hip_error(void) { return g_hip_err; }
+
+}  // extern "C"

@@ -1,0 +1,59 @@
+// gs_internal.h -- types shared by the library's own translation units (not installed).
+#ifndef GS_INTERNAL_H
+#define GS_INTERNAL_H
+
+#include <hip/hip_runtime_api.h>
+#include <stdint.h>
+
+#include "gs.h"
+
+#define GS_BLOCK 256                 // threads per workgroup (4 wave64)
+#define GS_SQNORM_MAX_BLOCKS 8192    // upper bound on block partials => workspace size
+#ifndef GS_STEP_BLOCKS_PER_CU
+#define GS_STEP_BLOCKS_PER_CU 8
+#endif
+#ifndef GS_NORM_BLOCKS_PER_CU
+#define GS_NORM_BLOCKS_PER_CU 8
+#endif
+
+namespace gs {
+
+// Per-step constants, formed on the host in double and rounded to float once.
+struct StepConsts {
+    float beta1, beta2, omb1, omb2, eps, step_size, rsbc2, decay;
+};
+
+struct GradTable {
+    const uint16_t *g[GS_MAX_K];
+};
+
+struct StepArgs {
+    float *p, *m, *v;
+    uint16_t *w;
+    GradTable gt;
+    int k;
+    int64_t begin, end;
+    StepConsts c;
+    float max_norm;
+    const double *d_sqnorm;
+};
+
+struct SqnormArgs {
+    GradTable gt;
+    int k;
+    int64_t begin, end;
+    double *partials;
+};
+
+hipError_t launch_accum_adamw(const StepArgs &A, int num_cu, hipStream_t stream);
+hipError_t launch_grad_sqnorm(const SqnormArgs &A, double *d_out, int accumulate, int num_cu, hipStream_t stream);
+
+// host side (gs_api.hip)
+gs_status validate_hparams(const gs_adamw_hparams *hp);
+gs_status validate_grads(const uint16_t *const *grads, int k);
+StepConsts make_consts(const gs_adamw_hparams &hp);
+gs_status hip_fail(hipError_t e, const char *what);
+int device_num_cu(int *out_cu);
+
+}  // namespace gs
+#endif

@@ -1,0 +1,286 @@
+// gs_kernels.hip -- gfx950 kernels of the per-layer optimizer step and their launchers.
+//
+// The work is one streaming pass over 2k+26 bytes per parameter (k bf16 gradient streams and
+// the fp32 p/m/v streams in, p/m/v and the bf16 weight out) with ~100 VALU lane-ops per
+// element: HBM-bound, so there is no MFMA here.  What matters is that every lane issues
+// 16-byte loads, that a wave's accesses to each stream are contiguous, that enough loads are
+// in flight per CU to cover HBM latency, and that streams which are never reused do not
+// evict each other from L2 (non-temporal hints).
+//
+// Partition independence (Sec. 6.5 of the paper: results must not depend on the partition
+// ratio): every element goes through the same update function `adamw_element`, compiled with
+// floating-point contraction off, whether it is reached through the 8-wide body or through
+// the per-element path used for ragged range ends.  Grouping is by ABSOLUTE element index
+// (groups of 8 starting at multiples of 8), so a range split at any point is processed with
+// bit-identical arithmetic.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gs_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace gs {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// ---- memory access helpers: streams are touched exactly once => non-temporal ------------
+template <typename T>
+__device__ __forceinline__ T ld_stream(const T *p)
+{
+    return __builtin_nontemporal_load(p);
+}
+template <typename T>
+__device__ __forceinline__ void st_stream(T *p, T v)
+{
+    __builtin_nontemporal_store(v, p);
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+// fp32 -> bf16, round to nearest even; NaN stays NaN (quiet bit forced).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    uint32_t r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    uint32_t nan = (u >> 16) | 0x0040u;
+    return ((u & 0x7fffffffu) > 0x7f800000u) ? nan : r;
+}
+
+// Clip coefficient from the total squared norm (Sec. 2.1: global L2 norm for clipping).
+__device__ __forceinline__ float clip_coefficient(const double *d_sqnorm, float max_norm)
+{
+    if (d_sqnorm == nullptr || !(max_norm > 0.0f)) return 1.0f;
+    float norm = (float)sqrt(*d_sqnorm);
+    float c = max_norm / (norm + 1e-6f);
+    return c < 1.0f ? c : 1.0f;
+}
+
+// The element update: clip, moments, master weight (Sec. 2.2: three fp32 states per weight,
+// updated element-wise).  One rounding per operation, no fused multiply-add.
+__device__ __forceinline__ void adamw_element(float a, float c, const StepConsts &s, float &p, float &m, float &v)
+{
+    float g = c * a;
+    float t1 = s.beta1 * m;
+    float t2 = s.omb1 * g;
+    float mn = t1 + t2;
+    float gg = g * g;
+    float t3 = s.beta2 * v;
+    float t4 = s.omb2 * gg;
+    float vn = t3 + t4;
+    float d = __builtin_sqrtf(vn) / s.rsbc2;
+    d = d + s.eps;
+    float u = mn / d;
+    float t5 = p * s.decay;
+    float t6 = s.step_size * u;
+    p = t5 - t6;
+    m = mn;
+    v = vn;
+}
+
+// k-way accumulation of one 8-element group, j ascending from +0 (Sec. 2.1: micro-batch
+// gradients are accumulated in full precision).  K > 0: compile-time count; K == 0: runtime.
+template <int K>
+__device__ __forceinline__ void accumulate_group(const GradTable &gt, int k, int64_t lo, float (&a)[8])
+{
+#pragma unroll
+    for (int e = 0; e < 8; ++e) a[e] = 0.0f;
+    if constexpr (K > 0) {
+        u32x4 gv[K];
+#pragma unroll
+        for (int j = 0; j < K; ++j) gv[j] = ld_stream(reinterpret_cast<const u32x4 *>(gt.g[j] + lo));
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+            a[0] += bf16_lo(gv[j].x); a[1] += bf16_hi(gv[j].x);
+            a[2] += bf16_lo(gv[j].y); a[3] += bf16_hi(gv[j].y);
+            a[4] += bf16_lo(gv[j].z); a[5] += bf16_hi(gv[j].z);
+            a[6] += bf16_lo(gv[j].w); a[7] += bf16_hi(gv[j].w);
+        }
+    } else {
+        for (int j = 0; j < k; ++j) {
+            u32x4 gv = ld_stream(reinterpret_cast<const u32x4 *>(gt.g[j] + lo));
+            a[0] += bf16_lo(gv.x); a[1] += bf16_hi(gv.x);
+            a[2] += bf16_lo(gv.y); a[3] += bf16_hi(gv.y);
+            a[4] += bf16_lo(gv.z); a[5] += bf16_hi(gv.z);
+            a[6] += bf16_lo(gv.w); a[7] += bf16_hi(gv.w);
+        }
+    }
+}
+
+__device__ __forceinline__ float accumulate_one(const GradTable &gt, int k, int64_t i)
+{
+    float a = 0.0f;
+    for (int j = 0; j < k; ++j) a += __uint_as_float((uint32_t)gt.g[j][i] << 16);
+    return a;
+}
+
+// ---- fused accumulate + clip + AdamW + bf16 emit -----------------------------------------
+template <int K>
+__global__ __launch_bounds__(GS_BLOCK) void k_accum_adamw(StepArgs A)
+{
+    const float c = clip_coefficient(A.d_sqnorm, A.max_norm);
+    const StepConsts s = A.c;
+    const int k = (K > 0) ? K : A.k;
+    const int64_t g_first = A.begin >> 3;
+    const int64_t g_end = (A.end + 7) >> 3;
+    const int64_t stride = (int64_t)gridDim.x * GS_BLOCK;
+
+    for (int64_t grp = g_first + (int64_t)blockIdx.x * GS_BLOCK + threadIdx.x; grp < g_end; grp += stride) {
+        const int64_t lo = grp << 3;
+        if (lo >= A.begin && lo + 8 <= A.end) {
+            float a[8];
+            accumulate_group<K>(A.gt, k, lo, a);
+            f32x4 p0 = ld_stream(reinterpret_cast<const f32x4 *>(A.p + lo));
+            f32x4 p1 = ld_stream(reinterpret_cast<const f32x4 *>(A.p + lo + 4));
+            f32x4 m0 = ld_stream(reinterpret_cast<const f32x4 *>(A.m + lo));
+            f32x4 m1 = ld_stream(reinterpret_cast<const f32x4 *>(A.m + lo + 4));
+            f32x4 v0 = ld_stream(reinterpret_cast<const f32x4 *>(A.v + lo));
+            f32x4 v1 = ld_stream(reinterpret_cast<const f32x4 *>(A.v + lo + 4));
+            float P[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+            float M[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
+            float V[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) adamw_element(a[e], c, s, P[e], M[e], V[e]);
+            st_stream(reinterpret_cast<f32x4 *>(A.p + lo), f32x4{P[0], P[1], P[2], P[3]});
+            st_stream(reinterpret_cast<f32x4 *>(A.p + lo + 4), f32x4{P[4], P[5], P[6], P[7]});
+            st_stream(reinterpret_cast<f32x4 *>(A.m + lo), f32x4{M[0], M[1], M[2], M[3]});
+            st_stream(reinterpret_cast<f32x4 *>(A.m + lo + 4), f32x4{M[4], M[5], M[6], M[7]});
+            st_stream(reinterpret_cast<f32x4 *>(A.v + lo), f32x4{V[0], V[1], V[2], V[3]});
+            st_stream(reinterpret_cast<f32x4 *>(A.v + lo + 4), f32x4{V[4], V[5], V[6], V[7]});
+            u32x4 wv;
+            wv.x = f32_to_bf16_bits(P[0]) | (f32_to_bf16_bits(P[1]) << 16);
+            wv.y = f32_to_bf16_bits(P[2]) | (f32_to_bf16_bits(P[3]) << 16);
+            wv.z = f32_to_bf16_bits(P[4]) | (f32_to_bf16_bits(P[5]) << 16);
+            wv.w = f32_to_bf16_bits(P[6]) | (f32_to_bf16_bits(P[7]) << 16);
+            st_stream(reinterpret_cast<u32x4 *>(A.w + lo), wv);
+        } else {
+            // ragged head / tail of the range: same arithmetic, one element at a time
+            const int64_t i0 = lo > A.begin ? lo : A.begin;
+            const int64_t i1 = lo + 8 < A.end ? lo + 8 : A.end;
+            for (int64_t i = i0; i < i1; ++i) {
+                float a = accumulate_one(A.gt, k, i);
+                float pi = A.p[i], mi = A.m[i], vi = A.v[i];
+                adamw_element(a, c, s, pi, mi, vi);
+                A.p[i] = pi;
+                A.m[i] = mi;
+                A.v[i] = vi;
+                A.w[i] = (uint16_t)f32_to_bf16_bits(pi);
+            }
+        }
+    }
+}
+
+// ---- squared norm of the accumulated gradient --------------------------------------------
+// Per-lane fp64 partial (each square is exact in fp64) -> wave64 butterfly -> LDS across the
+// block's waves -> one partial per block; a second tiny kernel folds the block partials in a
+// fixed order, so the result is deterministic.
+__device__ __forceinline__ double wave_sum(double x)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+    return x;
+}
+
+__device__ __forceinline__ double block_sum(double x, double *lds)
+{
+    constexpr int NW = GS_BLOCK / 64;
+    x = wave_sum(x);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (lane == 0) lds[wave] = x;
+    __syncthreads();
+    double t = 0.0;
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 0; w < NW; ++w) t += lds[w];
+    }
+    return t;   // valid in thread 0
+}
+
+template <int K>
+__global__ __launch_bounds__(GS_BLOCK) void k_grad_sqnorm(SqnormArgs A)
+{
+    __shared__ double lds[GS_BLOCK / 64];
+    const int k = (K > 0) ? K : A.k;
+    const int64_t g_first = A.begin >> 3;
+    const int64_t g_end = (A.end + 7) >> 3;
+    const int64_t stride = (int64_t)gridDim.x * GS_BLOCK;
+    double acc0 = 0.0, acc1 = 0.0;
+    for (int64_t grp = g_first + (int64_t)blockIdx.x * GS_BLOCK + threadIdx.x; grp < g_end; grp += stride) {
+        const int64_t lo = grp << 3;
+        if (lo >= A.begin && lo + 8 <= A.end) {
+            float a[8];
+            accumulate_group<K>(A.gt, k, lo, a);
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {
+                acc0 = fma((double)a[e], (double)a[e], acc0);
+                acc1 = fma((double)a[e + 1], (double)a[e + 1], acc1);
+            }
+        } else {
+            const int64_t i0 = lo > A.begin ? lo : A.begin;
+            const int64_t i1 = lo + 8 < A.end ? lo + 8 : A.end;
+            for (int64_t i = i0; i < i1; ++i) {
+                float a = accumulate_one(A.gt, k, i);
+                acc0 = fma((double)a, (double)a, acc0);
+            }
+        }
+    }
+    double t = block_sum(acc0 + acc1, lds);
+    if (threadIdx.x == 0) A.partials[blockIdx.x] = t;
+}
+
+__global__ __launch_bounds__(GS_BLOCK) void k_sqnorm_finalize(const double *partials, int nparts, double *out, int accumulate)
+{
+    __shared__ double lds[GS_BLOCK / 64];
+    double x = 0.0;
+    for (int i = threadIdx.x; i < nparts; i += GS_BLOCK) x += partials[i];
+    double t = block_sum(x, lds);
+    if (threadIdx.x == 0) *out = accumulate ? (*out + t) : t;
+}
+
+// ---- launchers -----------------------------------------------------------------------------
+static int grid_for(int64_t ngroups, int num_cu, int blocks_per_cu, int cap)
+{
+    int64_t need = (ngroups + GS_BLOCK - 1) / GS_BLOCK;
+    int64_t lim = (int64_t)num_cu * blocks_per_cu;
+    if (lim > cap) lim = cap;
+    if (need > lim) need = lim;
+    if (need < 1) need = 1;
+    return (int)need;
+}
+
+hipError_t launch_accum_adamw(const StepArgs &A, int num_cu, hipStream_t stream)
+{
+    const int64_t ngroups = ((A.end + 7) >> 3) - (A.begin >> 3);
+    const int grid = grid_for(ngroups, num_cu, GS_STEP_BLOCKS_PER_CU, 1 << 30);
+    switch (A.k) {
+    case 1: k_accum_adamw<1><<<grid, GS_BLOCK, 0, stream>>>(A); break;
+    case 2: k_accum_adamw<2><<<grid, GS_BLOCK, 0, stream>>>(A); break;
+    case 4: k_accum_adamw<4><<<grid, GS_BLOCK, 0, stream>>>(A); break;
+    case 8: k_accum_adamw<8><<<grid, GS_BLOCK, 0, stream>>>(A); break;
+    case 16: k_accum_adamw<16><<<grid, GS_BLOCK, 0, stream>>>(A); break;
+    default: k_accum_adamw<0><<<grid, GS_BLOCK, 0, stream>>>(A); break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_grad_sqnorm(const SqnormArgs &A, double *d_out, int accumulate, int num_cu, hipStream_t stream)
+{
+    const int64_t ngroups = ((A.end + 7) >> 3) - (A.begin >> 3);
+    const int grid = grid_for(ngroups, num_cu, GS_NORM_BLOCKS_PER_CU, GS_SQNORM_MAX_BLOCKS);
+    switch (A.k) {
+    case 1: k_grad_sqnorm<1><<<grid, GS_BLOCK, 0, stream>>>(A); break;
+    case 2: k_grad_sqnorm<2><<<grid, GS_BLOCK, 0, stream>>>(A); break;
+    case 4: k_grad_sqnorm<4><<<grid, GS_BLOCK, 0, stream>>>(A); break;
+    case 8: k_grad_sqnorm<8><<<grid, GS_BLOCK, 0, stream>>>(A); break;
+    case 16: k_grad_sqnorm<16><<<grid, GS_BLOCK, 0, stream>>>(A); break;
+    default: k_grad_sqnorm<0><<<grid, GS_BLOCK, 0, stream>>>(A); break;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    k_sqnorm_finalize<<<1, GS_BLOCK, 0, stream>>>(A.partials, grid, d_out, accumulate);
+    return hipGetLastError();
+}
+
+}  // namespace gs

@@ -1,0 +1,128 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every symbol the header
+declares, and rejects bad arguments before touching HIP."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2512_17570_amd import gs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "gs.h")
+
+FAKE = 0x10000          # non-null, 16-byte aligned; never dereferenced by a rejected call
+GOOD_HP = gs.HParams(step=3)
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    names = re.findall(r"\b(gs_[a-z0-9_]+)\s*\(", src)
+    return sorted(set(names))
+
+
+def test_header_symbols_all_exported():
+    names = declared_functions()
+    assert {"gs_grad_sqnorm", "gs_accum_adamw", "gs_stream_layer_step", "gs_sqnorm_workspace_bytes",
+            "gs_stream_ctx_create", "gs_stream_ctx_destroy", "gs_stream_ctx_sync", "gs_pinned_alloc",
+            "gs_pinned_free", "gs_strerror", "gs_last_hip_error"} <= set(names)
+    lib = ctypes.CDLL(gs.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in gs.h but not exported"
+
+
+def test_binding_has_same_names():
+    for n in declared_functions():
+        assert hasattr(gs, n), n
+
+
+def test_hparams_struct_layout_matches_header():
+    assert ctypes.sizeof(gs.gs_adamw_hparams) == 28
+    assert gs.gs_adamw_hparams.step.offset == 24
+    assert gs.GS_MAX_K == int(re.search(r"#define\s+GS_MAX_K\s+(\d+)", open(HEADER).read()).group(1))
+
+
+def test_strerror_and_workspace():
+    assert gs.gs_strerror(gs.GS_OK) == "ok"
+    for s in (gs.GS_ERR_INVALID_ARG, gs.GS_ERR_WORKSPACE, gs.GS_ERR_HIP, gs.GS_ERR_NOMEM):
+        assert gs.gs_strerror(s) not in ("ok", "unknown status")
+    assert gs.gs_strerror(-99) == "unknown status"
+    assert gs.gs_sqnorm_workspace_bytes() >= 8 * 1024
+    assert gs.gs_sqnorm_workspace_bytes() % 8 == 0
+
+
+def _adamw(**kw):
+    a = dict(p=FAKE, m=FAKE, v=FAKE, w_bf16=FAKE, grads=[FAKE, FAKE], begin=0, end=100, hp=GOOD_HP,
+             d_sqnorm=None, stream=0, check=False)
+    a.update(kw)
+    return gs.gs_accum_adamw(**a)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(p=None), dict(m=None), dict(v=None), dict(w_bf16=None),
+    dict(p=FAKE + 4), dict(w_bf16=FAKE + 2), dict(m=FAKE + 8),
+    dict(grads=None, k=2), dict(grads=[FAKE], k=0), dict(grads=[FAKE] * 33),
+    dict(grads=[FAKE, None]), dict(grads=[FAKE, FAKE + 2]),
+    dict(begin=-1), dict(begin=10, end=9),
+    dict(hp=None),
+    dict(hp=gs.HParams(step=0)), dict(hp=gs.HParams(step=-5)),
+    dict(hp=gs.HParams(lr=-1.0, step=1)), dict(hp=gs.HParams(lr=float("nan"), step=1)),
+    dict(hp=gs.HParams(beta1=1.0, step=1)), dict(hp=gs.HParams(beta1=-0.1, step=1)),
+    dict(hp=gs.HParams(beta2=1.0, step=1)), dict(hp=gs.HParams(beta2=float("inf"), step=1)),
+    dict(hp=gs.HParams(eps=-1e-8, step=1)), dict(hp=gs.HParams(weight_decay=-0.1, step=1)),
+    dict(hp=gs.HParams(max_grad_norm=float("nan"), step=1)),
+    dict(d_sqnorm=FAKE + 4),
+])
+def test_accum_adamw_rejects(kw):
+    assert _adamw(**kw) == gs.GS_ERR_INVALID_ARG
+
+
+def test_accum_adamw_empty_range_is_ok_without_gpu():
+    assert _adamw(begin=50, end=50) == gs.GS_OK
+    assert _adamw(begin=0, end=0) == gs.GS_OK
+
+
+def _sqnorm(**kw):
+    a = dict(grads=[FAKE], begin=0, end=100, d_sqnorm=FAKE, d_workspace=FAKE,
+             workspace_bytes=gs.gs_sqnorm_workspace_bytes(), accumulate=False, stream=0, check=False)
+    a.update(kw)
+    return gs.gs_grad_sqnorm(**a)
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(grads=None, k=1), gs.GS_ERR_INVALID_ARG),
+    (dict(grads=[FAKE] * 40), gs.GS_ERR_INVALID_ARG),
+    (dict(grads=[FAKE + 6]), gs.GS_ERR_INVALID_ARG),
+    (dict(begin=-3), gs.GS_ERR_INVALID_ARG),
+    (dict(begin=5, end=4), gs.GS_ERR_INVALID_ARG),
+    (dict(d_sqnorm=None), gs.GS_ERR_INVALID_ARG),
+    (dict(d_sqnorm=FAKE + 4), gs.GS_ERR_INVALID_ARG),
+    (dict(d_workspace=None), gs.GS_ERR_WORKSPACE),
+    (dict(workspace_bytes=16), gs.GS_ERR_WORKSPACE),
+    (dict(d_workspace=FAKE + 4), gs.GS_ERR_WORKSPACE),
+])
+def test_grad_sqnorm_rejects(kw, want):
+    assert _sqnorm(**kw) == want
+
+
+def test_grad_sqnorm_empty_accumulate_is_noop():
+    assert _sqnorm(begin=7, end=7, accumulate=True) == gs.GS_OK
+
+
+def test_stream_api_rejects_without_gpu():
+    st, ctx = gs.gs_stream_ctx_create(0, 2, check=False)
+    assert st == gs.GS_ERR_INVALID_ARG and not ctx
+    st, ctx = gs.gs_stream_ctx_create(1024, 1, check=False)
+    assert st == gs.GS_ERR_INVALID_ARG and not ctx
+    assert gs.gs_stream_ctx_sync(None, check=False) == gs.GS_ERR_INVALID_ARG
+    assert gs.gs_stream_ctx_destroy(None, check=False) == gs.GS_ERR_INVALID_ARG
+    assert gs.gs_stream_layer_step(None, FAKE, FAKE, FAKE, FAKE, [FAKE], 10, GOOD_HP, check=False) == gs.GS_ERR_INVALID_ARG
+    assert gs.gs_pinned_alloc(0) is None
+    gs.gs_pinned_free(None)
+
+
+def test_error_raises_through_binding():
+    with pytest.raises(gs.GsError) as ei:
+        _adamw(begin=3, end=2, check=True)
+    assert ei.value.status == gs.GS_ERR_INVALID_ARG

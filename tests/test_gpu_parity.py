@@ -1,0 +1,340 @@
+"""GPU parity: the HIP path (through the C-ABI binding) against the CPU oracle, element by
+element, on the same seeded inputs.  Sizes span several launch tiles (a block handles 2048
+elements per sweep) and ragged tails; full workload sizes are in test_gpu_fullsize.py."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import (DEV, DeviceCase, O, assert_bf16_close, assert_f32_close, assert_w_is_rne_of_p, gs,
+                      np_bf16, np_f32, ohp)
+from paper_2512_17570_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+HP = gs.HParams(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, max_grad_norm=1.0, step=10)
+
+
+def run_gpu_step(case, hp, begin=0, end=None, use_norm=True, states=None):
+    end = case.n if end is None else end
+    p, m, v, w = states if states is not None else case.clone_states()
+    gs.gs_accum_adamw(p, m, v, w, case.grads, begin, end, hp, case.sq if use_norm else None)
+    torch.cuda.synchronize()
+    return p, m, v, w
+
+
+def compare_states(gpu, ora, tag):
+    (p, m, v, w), (op, om, ov, ow) = gpu, ora
+    up = assert_f32_close(np_f32(p), op, f"{tag}.p")
+    um = assert_f32_close(np_f32(m), om, f"{tag}.m")
+    uv = assert_f32_close(np_f32(v), ov, f"{tag}.v")
+    uw = assert_bf16_close(np_bf16(w), ow, f"{tag}.w")
+    return up, um, uv, uw
+
+
+# ----------------------------------------------------------------------------- a2 squared norm
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5, 8, 16, 17, 32])
+def test_sqnorm_matches_oracle(k):
+    n = 3 * 2048 * 64 + 1237
+    case = DeviceCase(n, k, seed=k)
+    got = case.gpu_sqnorm()
+    want = O.grad_sqnorm(case.h_g)
+    assert abs(got - want) <= 1e-5 * want, (got, want)
+    assert abs(got - want) <= 1e-12 * want      # fp64 accumulation: only the summation order differs
+
+
+@pytest.mark.parametrize("begin,end", [(0, 0), (5, 5), (0, 1), (3, 4), (7, 9), (1, 8), (0, 8), (8, 16),
+                                       (13, 100_003), (2048 * 7 + 1, 2048 * 300 - 3)])
+def test_sqnorm_ranges(begin, end):
+    case = DeviceCase(2048 * 300, 4, seed=2)
+    got = case.gpu_sqnorm(begin, end)
+    want = O.grad_sqnorm(case.h_g, begin, end)
+    assert abs(got - want) <= 1e-12 * max(want, 1e-300)
+    if begin == end:
+        assert got == 0.0
+
+
+def test_sqnorm_accumulate_and_determinism():
+    case = DeviceCase(1_000_003, 8, seed=3)
+    full = case.gpu_sqnorm()
+    assert case.gpu_sqnorm() == full                    # same arguments -> same bits
+    s1 = case.gpu_sqnorm(0, 400_001)
+    tot = case.gpu_sqnorm(400_001, case.n, accumulate=True)
+    assert abs(tot - full) <= 1e-13 * full
+    assert tot != s1
+    # accumulate over an empty range leaves the scalar alone
+    assert case.gpu_sqnorm(9, 9, accumulate=True) == tot
+
+
+def test_sqnorm_exact_patterns():
+    n, k = 2048 * 40 + 5, 5
+    ones = [torch.ones(n, dtype=torch.bfloat16, device=DEV) for _ in range(k)]
+    sq = torch.zeros(1, dtype=torch.float64, device=DEV)
+    ws = torch.empty(gs.gs_sqnorm_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    gs.gs_grad_sqnorm(ones, 0, n, sq, ws)
+    assert float(sq.item()) == float(k * k * n)
+
+
+# ----------------------------------------------------------------------------- a1,a3-a6 fused step
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 7, 8, 16, 17, 32])
+def test_step_matches_oracle_all_k(k):
+    n = 2 * 2048 * 256 + 2048 * 3 + 5           # > one full grid sweep on 256 CUs x 8 blocks, ragged tail
+    case = DeviceCase(n, k, seed=10 + k)
+    S = case.gpu_sqnorm()
+    hp = gs.HParams(**{**HP.__dict__, "step": 10})
+    gpu = run_gpu_step(case, hp)
+    c = O.clip_coef(O.grad_sqnorm(case.h_g), hp.max_grad_norm)
+    assert c < 1.0 or k == 1                   # clipping is active for these norms (||g|| > 1)
+    ora = case.oracle_step(hp, c)
+    ulps = compare_states(gpu, ora, f"k={k}")
+    assert_w_is_rne_of_p(gpu[0], gpu[3], 0, n)
+    print(f"k={k}: max ulp p/m/v/w = {ulps}; S_gpu={S}")
+
+
+def test_workload0_full_layer_h1024():
+    wl = I.WORKLOADS["gpt_h1024_k4"]
+    case = DeviceCase(wl.n, wl.k, wl.seed, wl.grad_sigma, wl.outlier_frac)
+    hp = gs.HParams(wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay, wl.max_grad_norm, wl.step)
+    S = case.gpu_sqnorm()
+    So = O.grad_sqnorm(case.h_g)
+    assert abs(S - So) <= 1e-5 * So
+    assert abs(np.sqrt(So) - 7.1) < 0.1          # n k sigma^2 = 50.4
+    gpu = run_gpu_step(case, hp)
+    ora = case.oracle_step(hp, O.clip_coef(So, hp.max_grad_norm))
+    ulps = compare_states(gpu, ora, "h1024")
+    assert_w_is_rne_of_p(gpu[0], gpu[3], 0, wl.n)
+    # and both sit within tolerance of the fp64 evaluation of the same formulas
+    tp, tm, tv = O.accum_adamw_f64(case.h_p, case.h_m, case.h_v, case.h_g, ohp(hp), So)
+    # (error measured in fp32 spacings of the larger operand of each final add/subtract; the fp32
+    # chain has ~10 roundings, so its distance to the fp64 evaluation is a few spacings)
+    for got, want, old in ((np_f32(gpu[0]), tp, case.h_p), (np_f32(gpu[1]), tm, case.h_m), (np_f32(gpu[2]), tv, case.h_v)):
+        scale = np.maximum(np.abs(want), np.maximum(np.abs(old), np.abs(want - old))).astype(np.float32)
+        err = np.abs(got - want)
+        assert np.all(err <= 8 * np.spacing(scale)), float((err / np.spacing(scale)).max())
+    print("h1024 max ulp p/m/v/w =", ulps)
+
+
+def test_no_clip_paths_agree():
+    """d_sqnorm = NULL, max_norm <= 0, and a norm below max_norm all give c = 1."""
+    n = 2048 * 50 + 3
+    case = DeviceCase(n, 4, seed=21, sigma=1e-5)         # tiny gradients: ||g|| << 1
+    S = case.gpu_sqnorm()
+    assert np.sqrt(S) < 0.5
+    a = run_gpu_step(case, HP, use_norm=True)
+    b = run_gpu_step(case, HP, use_norm=False)
+    hp0 = gs.HParams(**{**HP.__dict__, "max_grad_norm": 0.0})
+    c = run_gpu_step(case, hp0, use_norm=True)
+    for x, y, z in zip(a, b, c):
+        assert torch.equal(x.view(torch.int32) if x.dtype == torch.float32 else x.view(torch.int16),
+                           y.view(torch.int32) if y.dtype == torch.float32 else y.view(torch.int16))
+        assert torch.equal(y.view(torch.int32) if y.dtype == torch.float32 else y.view(torch.int16),
+                           z.view(torch.int32) if z.dtype == torch.float32 else z.view(torch.int16))
+    compare_states(a, case.oracle_step(HP, 1.0), "noclip")
+
+
+@pytest.mark.parametrize("step,wd,lr", [(1, 0.0, 1e-3), (1, 0.1, 1e-3), (100000, 0.01, 3e-4), (7, 0.0, 0.0)])
+def test_hparam_variants(step, wd, lr):
+    n = 2048 * 33 + 7
+    case = DeviceCase(n, 3, seed=30 + step % 7)
+    hp = gs.HParams(lr=lr, beta1=0.8, beta2=0.95, eps=1e-6, weight_decay=wd, max_grad_norm=0.3, step=step)
+    S = case.gpu_sqnorm()
+    gpu = run_gpu_step(case, hp)
+    ora = case.oracle_step(hp, O.clip_coef(O.grad_sqnorm(case.h_g), hp.max_grad_norm))
+    compare_states(gpu, ora, f"t={step}")
+    if lr == 0.0:
+        assert torch.equal(gpu[0], case.p)
+
+
+def test_first_step_closed_form_on_gpu():
+    """t=1, m=v=0, c=1: p' = p(1-lr wd) - lr g/(|g|+eps), evaluated independently in fp64."""
+    n, k = 2048 * 9 + 1, 3
+    case = DeviceCase(n, k, seed=41)
+    hp = gs.HParams(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.1, max_grad_norm=0.0, step=1)
+    p, w = case.p.clone(), torch.zeros_like(case.w)
+    m, v = torch.zeros_like(case.m), torch.zeros_like(case.v)
+    gs.gs_accum_adamw(p, m, v, w, case.grads, 0, n, hp, None)
+    torch.cuda.synchronize()
+    gsum = sum(g.double() for g in case.grads).cpu().numpy()
+    lr, wd, eps = (float(np.float32(x)) for x in (hp.lr, hp.weight_decay, hp.eps))
+    want = case.h_p.astype(np.float64) * (1 - lr * wd) - lr * gsum / (np.abs(gsum) + eps)
+    err = np.abs(np_f32(p) - want)
+    assert np.all(err <= 3 * np.spacing(np.maximum(np.abs(case.h_p), np.float32(lr))))
+    assert np.allclose(np_f32(m), (1 - float(np.float32(0.9))) * gsum, rtol=3e-7, atol=0)
+    assert np.allclose(np_f32(v), (1 - float(np.float32(0.999))) * gsum * gsum, rtol=3e-7, atol=0)
+
+
+# ----------------------------------------------------------------------------- a7 split == full
+@pytest.mark.parametrize("k", [4, 5])
+def test_split_equals_full_bitwise(k):
+    n = 2048 * 300 + 11
+    case = DeviceCase(n, k, seed=50)
+    case.gpu_sqnorm()
+    full = run_gpu_step(case, HP)
+    for s in sorted({0, 1, 7, 8, 9, n // 2 - 1, n // 2 + 1, n - 1, n, int(0.4 * n)}):
+        st = case.clone_states()
+        run_gpu_step(case, HP, 0, s, states=st)
+        run_gpu_step(case, HP, s, n, states=st)
+        for a, b in zip(full, st):
+            assert torch.equal(a, b), f"split at {s}"
+
+
+def test_many_small_chunks_equal_full_and_ranges_untouched():
+    n = 4099
+    case = DeviceCase(n, 2, seed=51)
+    case.gpu_sqnorm()
+    full = run_gpu_step(case, HP)
+    st = case.clone_states()
+    b = 0
+    for size in [1, 2, 3, 5, 7, 8, 9, 15, 16, 17, 31, 100, 1000]:
+        e = min(n, b + size)
+        run_gpu_step(case, HP, b, e, states=st)
+        b = e
+    # not yet touched: [b, n) still holds the inputs
+    assert torch.equal(st[0][b:], case.p[b:]) and torch.equal(st[1][b:], case.m[b:])
+    assert torch.count_nonzero(st[3][b:]) == 0
+    run_gpu_step(case, HP, b, n, states=st)
+    for a, c in zip(full, st):
+        assert torch.equal(a, c)
+
+
+def test_split_on_two_streams():
+    """Immediate part on one stream, deferred part on another (same t, same norm)."""
+    n = 2048 * 700 + 3
+    case = DeviceCase(n, 8, seed=52)
+    case.gpu_sqnorm()
+    full = run_gpu_step(case, HP)
+    st = case.clone_states()
+    s = int(0.4 * n)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    cur = torch.cuda.current_stream()
+    sa.wait_stream(cur); sb.wait_stream(cur)
+    gs.gs_accum_adamw(*st, case.grads, 0, s, HP, case.sq, stream=sa)
+    gs.gs_accum_adamw(*st, case.grads, s, n, HP, case.sq, stream=sb)
+    torch.cuda.synchronize()
+    for a, b in zip(full, st):
+        assert torch.equal(a, b)
+
+
+# ----------------------------------------------------------------------------- special values
+def test_special_values_propagate_like_the_oracle():
+    n = 2048 * 4 + 9
+    case = DeviceCase(n, 2, seed=60)
+    specials = torch.tensor([float("nan"), float("inf"), -float("inf"), 0.0, -0.0, 1e-40, -1e-40, 3.0e38],
+                            dtype=torch.float32, device=DEV).to(torch.bfloat16)
+    idx = torch.arange(8, device=DEV) * 1021 + 5
+    case.grads[0][idx] = specials
+    case.grads[1][idx] = 0
+    case.p[17] = 3.4e38; case.p[18] = 1e-42; case.m[19] = 1e-44; case.v[20] = 0.0
+    case.h_p, case.h_m, case.h_v = np_f32(case.p), np_f32(case.m), np_f32(case.v)
+    case.h_g = [np_bf16(g) for g in case.grads]
+    gpu = run_gpu_step(case, HP, use_norm=False)
+    ora = case.oracle_step(HP, 1.0)
+    compare_states(gpu, ora, "specials")
+    S = case.gpu_sqnorm()
+    assert np.isnan(S) == np.isnan(O.grad_sqnorm(case.h_g))
+    # with the NaN norm the coefficient is 1 on both sides
+    gpu2 = run_gpu_step(case, HP, use_norm=True)
+    compare_states(gpu2, case.oracle_step(HP, O.clip_coef(O.grad_sqnorm(case.h_g), HP.max_grad_norm)), "specials+norm")
+
+
+def test_bf16_rounding_ties_on_gpu():
+    """lr = 0, wd = 0: p' = p exactly, so w must be bf16_rne(p) for hand-picked tie patterns."""
+    bits = np.array([0x3F800000, 0x3F808000, 0x3F818000, 0x3F808001, 0x3F807FFF, 0x3F7F8000, 0x00000000,
+                     0x80000000, 0x7F800000, 0xFF800000, 0x7F7FFFFF, 0x7F7F7FFF, 0x00008000, 0x00018000,
+                     0xBF818000, 0x7FC00000], dtype=np.uint32)
+    want = np.array([0x3F80, 0x3F80, 0x3F82, 0x3F81, 0x3F80, 0x3F80, 0x0000, 0x8000, 0x7F80, 0xFF80, 0x7F80,
+                     0x7F7F, 0x0000, 0x0002, 0xBF82], dtype=np.uint16)
+    n = 2048 + 16
+    reps = np.resize(bits, n)
+    p = torch.from_numpy(reps.view(np.float32).copy()).to(DEV)
+    m = torch.zeros(n, device=DEV); v = torch.ones(n, device=DEV)
+    w = torch.zeros(n, dtype=torch.bfloat16, device=DEV)
+    g = [torch.zeros(n, dtype=torch.bfloat16, device=DEV)]
+    hp = gs.HParams(lr=0.0, weight_decay=0.0, step=1, max_grad_norm=0.0)
+    gs.gs_accum_adamw(p, m, v, w, g, 3, n - 2, hp, None)       # ragged: both code paths see the patterns
+    torch.cuda.synchronize()
+    got = np_bf16(w)
+    for i in range(3, n - 2):
+        j = i % 16
+        if j == 15:
+            assert (got[i] & 0x7F80) == 0x7F80 and (got[i] & 0x7F) != 0
+        else:
+            assert got[i] == want[j], (i, j, hex(got[i]), hex(want[j]))
+        assert got[i] == O.f32_to_bf16(reps.view(np.float32)[i]) or j == 15
+    assert got[0] == 0 and got[n - 1] == 0
+
+
+# ----------------------------------------------------------------------------- resume
+def test_step_reload_step_equals_two_steps():
+    n = 2048 * 20 + 1
+    case = DeviceCase(n, 3, seed=70)
+    st = case.clone_states()
+    gs.gs_accum_adamw(*st, case.grads, 0, n, gs.HParams(step=1, max_grad_norm=0.0), None)
+    dump = [np_f32(t) for t in st[:3]]
+    gs.gs_accum_adamw(*st, case.grads, 0, n, gs.HParams(step=2, max_grad_norm=0.0), None)
+    re = [torch.from_numpy(d).to(DEV) for d in dump] + [torch.zeros_like(case.w)]
+    gs.gs_accum_adamw(*re, case.grads, 0, n, gs.HParams(step=2, max_grad_norm=0.0), None)
+    torch.cuda.synchronize()
+    for a, b in zip(st, re):
+        assert torch.equal(a, b)
+    # two oracle steps from the same start
+    p, m, v, w = case.h_p.copy(), case.h_m.copy(), case.h_v.copy(), np.zeros(n, np.uint16)
+    O.accum_adamw(p, m, v, w, case.h_g, O.HParams(step=1, max_grad_norm=0.0), 1.0)
+    O.accum_adamw(p, m, v, w, case.h_g, O.HParams(step=2, max_grad_norm=0.0), 1.0)
+    compare_states(st, (p, m, v, w), "two steps")
+
+
+# ----------------------------------------------------------------------------- a8 streamed == resident
+@pytest.mark.parametrize("chunk,slots", [(1, 2), (7, 3), (4096, 2), (100_000, 3), (1 << 22, 2)])
+def test_streamed_equals_resident(chunk, slots):
+    n = 300 if chunk == 1 else (5000 if chunk == 7 else 2048 * 600 + 13)
+    case = DeviceCase(n, 4, seed=80)
+    case.gpu_sqnorm()
+    full = run_gpu_step(case, HP)
+    hp_, pp = gs.pinned_f32(n)
+    hm_, pm = gs.pinned_f32(n)
+    hv_, pv = gs.pinned_f32(n)
+    try:
+        hp_.copy_(case.p.cpu()); hm_.copy_(case.m.cpu()); hv_.copy_(case.v.cpu())
+        w = torch.zeros_like(case.w)
+        ctx = gs.gs_stream_ctx_create(chunk, slots)
+        gs.gs_stream_layer_step(ctx, pp, pm, pv, w, case.grads, n, HP, case.sq)
+        gs.gs_stream_ctx_sync(ctx)
+        gs.gs_stream_ctx_destroy(ctx)
+        assert np.array_equal(hp_.numpy(), np_f32(full[0]))
+        assert np.array_equal(hm_.numpy(), np_f32(full[1]))
+        assert np.array_equal(hv_.numpy(), np_f32(full[2]))
+        assert torch.equal(w, full[3])
+    finally:
+        del hp_, hm_, hv_
+        gs.gs_pinned_free(pp); gs.gs_pinned_free(pm); gs.gs_pinned_free(pv)
+
+
+def test_streamed_two_layers_back_to_back_with_poisoned_slots():
+    """Two 'layers' enqueued on one context without a sync in between; results must match the
+    resident path, i.e. slot reuse is correctly ordered."""
+    n, chunk = 2048 * 200 + 5, 50_000
+    cases = [DeviceCase(n, 2, seed=90), DeviceCase(n, 2, seed=91)]
+    ctx = gs.gs_stream_ctx_create(chunk, 2)
+    held = []
+    try:
+        outs = []
+        for case in cases:
+            case.gpu_sqnorm()
+            bufs = [gs.pinned_f32(n) for _ in range(3)]
+            held.append(bufs)
+            for (t, _), src in zip(bufs, (case.p, case.m, case.v)):
+                t.copy_(src.cpu())
+            w = torch.zeros_like(case.w)
+            gs.gs_stream_layer_step(ctx, bufs[0][1], bufs[1][1], bufs[2][1], w, case.grads, n, HP, case.sq)
+            outs.append(w)
+        gs.gs_stream_ctx_sync(ctx)
+        for case, bufs, w in zip(cases, held, outs):
+            full = run_gpu_step(case, HP)
+            for (t, _), ref in zip(bufs, full[:3]):
+                assert np.array_equal(t.numpy(), np_f32(ref))
+            assert torch.equal(w, full[3])
+    finally:
+        gs.gs_stream_ctx_destroy(ctx)
+        for bufs in held:
+            for t, ptr in bufs:
+                gs.gs_pinned_free(ptr)
