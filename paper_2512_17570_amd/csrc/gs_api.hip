@@ -60,25 +60,6 @@ StepConsts make_consts(const gs_adamw_hparams &hp)
     return s;
 }
 
-// Compute-unit count of the current device (cached per device ordinal).
-int device_num_cu(int *out_cu)
-{
-    static int cache[64] = {0};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return (int)hip_fail(e, "hipGetDevice");
-    if (dev < 0 || dev >= 64) dev = 0;
-    int cu = __atomic_load_n(&cache[dev], __ATOMIC_RELAXED);
-    if (cu == 0) {
-        e = hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e != hipSuccess) return (int)hip_fail(e, "hipDeviceGetAttribute");
-        if (cu < 1) cu = 1;
-        __atomic_store_n(&cache[dev], cu, __ATOMIC_RELAXED);
-    }
-    *out_cu = cu;
-    return GS_OK;
-}
-
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace gs
@@ -101,8 +82,6 @@ gs_status gs_grad_sqnorm(const uint16_t *const *grads, int k, int64_t begin, int
     if (reinterpret_cast<uintptr_t>(d_workspace) & 7u) return GS_ERR_WORKSPACE;
     if (begin == end && accumulate) return GS_OK;
 
-    int cu = 0;
-    if (device_num_cu(&cu) != GS_OK) return GS_ERR_HIP;
     SqnormArgs A;
     memset(&A, 0, sizeof A);
     for (int j = 0; j < k; ++j) A.gt.g[j] = grads[j];
@@ -110,7 +89,7 @@ gs_status gs_grad_sqnorm(const uint16_t *const *grads, int k, int64_t begin, int
     A.begin = begin;
     A.end = end;
     A.partials = static_cast<double *>(d_workspace);
-    hipError_t e = launch_grad_sqnorm(A, d_sqnorm, accumulate, cu, static_cast<hipStream_t>(stream));
+    hipError_t e = launch_grad_sqnorm(A, d_sqnorm, accumulate, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e, "gs_grad_sqnorm launch");
     return GS_OK;
 }
@@ -129,8 +108,6 @@ gs_status gs_accum_adamw(float *p, float *m, float *v, uint16_t *w_bf16,
     if (d_sqnorm && (reinterpret_cast<uintptr_t>(d_sqnorm) & 7u)) return GS_ERR_INVALID_ARG;
     if (begin == end) return GS_OK;
 
-    int cu = 0;
-    if (device_num_cu(&cu) != GS_OK) return GS_ERR_HIP;
     StepArgs A;
     memset(&A, 0, sizeof A);
     A.p = p;
@@ -144,7 +121,7 @@ gs_status gs_accum_adamw(float *p, float *m, float *v, uint16_t *w_bf16,
     A.c = make_consts(*hp);
     A.max_norm = hp->max_grad_norm;
     A.d_sqnorm = d_sqnorm;
-    hipError_t e = launch_accum_adamw(A, cu, static_cast<hipStream_t>(stream));
+    hipError_t e = launch_accum_adamw(A, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e, "gs_accum_adamw launch");
     return GS_OK;
 }

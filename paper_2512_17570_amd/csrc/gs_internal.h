@@ -7,14 +7,11 @@
 
 #include "gs.h"
 
-#define GS_BLOCK 256                 // threads per workgroup (4 wave64)
-#define GS_SQNORM_MAX_BLOCKS 8192    // upper bound on block partials => workspace size
-#ifndef GS_STEP_BLOCKS_PER_CU
-#define GS_STEP_BLOCKS_PER_CU 8
-#endif
-#ifndef GS_NORM_BLOCKS_PER_CU
-#define GS_NORM_BLOCKS_PER_CU 8
-#endif
+#define GS_BLOCK 256                  // threads per workgroup (4 wave64)
+#define GS_TILE (GS_BLOCK * 4)        // elements per workgroup tile: one group of 4 per lane
+#define GS_FINAL_BLOCK 1024           // threads of the partial-folding kernel
+#define GS_SQNORM_MAX_BLOCKS 65536    // upper bound on block partials => workspace size
+#define GS_NORM_SPAN 8                // consecutive tiles per norm workgroup (grows for huge ranges)
 
 namespace gs {
 
@@ -45,15 +42,14 @@ struct SqnormArgs {
     double *partials;
 };
 
-hipError_t launch_accum_adamw(const StepArgs &A, int num_cu, hipStream_t stream);
-hipError_t launch_grad_sqnorm(const SqnormArgs &A, double *d_out, int accumulate, int num_cu, hipStream_t stream);
+hipError_t launch_accum_adamw(const StepArgs &A, hipStream_t stream);
+hipError_t launch_grad_sqnorm(const SqnormArgs &A, double *d_out, int accumulate, hipStream_t stream);
 
 // host side (gs_api.hip)
 gs_status validate_hparams(const gs_adamw_hparams *hp);
 gs_status validate_grads(const uint16_t *const *grads, int k);
 StepConsts make_consts(const gs_adamw_hparams &hp);
 gs_status hip_fail(hipError_t e, const char *what);
-int device_num_cu(int *out_cu);
 
 }  // namespace gs
 #endif

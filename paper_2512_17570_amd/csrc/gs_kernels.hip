@@ -2,16 +2,23 @@
 //
 // The work is one streaming pass over 2k+26 bytes per parameter (k bf16 gradient streams and
 // the fp32 p/m/v streams in, p/m/v and the bf16 weight out) with ~100 VALU lane-ops per
-// element: HBM-bound, so there is no MFMA here.  What matters is that every lane issues
-// 16-byte loads, that a wave's accesses to each stream are contiguous, that enough loads are
-// in flight per CU to cover HBM latency, and that streams which are never reused do not
-// evict each other from L2 (non-temporal hints).
+// element: HBM-bound, so there is no MFMA here.  Measured on MI355X, what decides the achieved
+// bandwidth of such a many-stream read+write pass is the shape of the memory traffic:
+//   * every wave-level memory instruction covers whole, contiguous 128-byte lines -- a lane owns
+//     4 consecutive elements, i.e. one 8-byte load per bf16 stream (512 B per wave) and one
+//     16-byte load/store per fp32 stream (1 KB per wave); lanes that own 8 elements would split
+//     each fp32 line across two instructions and fetch it twice;
+//   * workgroups are NOT persistent: one 1024-element tile per workgroup, dispatched in order,
+//     keeps the set of addresses in flight compact, which HBM rewards (a grid-stride loop costs
+//     30-40 % on stores on this part);
+//   * every stream is touched once, so loads and stores carry the non-temporal hint.
+// The norm pass is read-only and does best with short contiguous spans of tiles per workgroup.
 //
 // Partition independence (Sec. 6.5 of the paper: results must not depend on the partition
 // ratio): every element goes through the same update function `adamw_element`, compiled with
-// floating-point contraction off, whether it is reached through the 8-wide body or through
+// floating-point contraction off, whether it is reached through the 4-wide body or through
 // the per-element path used for ragged range ends.  Grouping is by ABSOLUTE element index
-// (groups of 8 starting at multiples of 8), so a range split at any point is processed with
+// (groups of 4 starting at multiples of 4), so a range split at any point is processed with
 // bit-identical arithmetic.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -22,7 +29,7 @@
 
 namespace gs {
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // ---- memory access helpers: streams are touched exactly once => non-temporal ------------
@@ -80,31 +87,27 @@ __device__ __forceinline__ void adamw_element(float a, float c, const StepConsts
     v = vn;
 }
 
-// k-way accumulation of one 8-element group, j ascending from +0 (Sec. 2.1: micro-batch
+// k-way accumulation of one 4-element group, j ascending from +0 (Sec. 2.1: micro-batch
 // gradients are accumulated in full precision).  K > 0: compile-time count; K == 0: runtime.
 template <int K>
-__device__ __forceinline__ void accumulate_group(const GradTable &gt, int k, int64_t lo, float (&a)[8])
+__device__ __forceinline__ void accumulate_group(const GradTable &gt, int k, int64_t lo, float (&a)[4])
 {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) a[e] = 0.0f;
+    for (int e = 0; e < 4; ++e) a[e] = 0.0f;
     if constexpr (K > 0) {
-        u32x4 gv[K];
+        u32x2 gv[K];
 #pragma unroll
-        for (int j = 0; j < K; ++j) gv[j] = ld_stream(reinterpret_cast<const u32x4 *>(gt.g[j] + lo));
+        for (int j = 0; j < K; ++j) gv[j] = ld_stream(reinterpret_cast<const u32x2 *>(gt.g[j] + lo));
 #pragma unroll
         for (int j = 0; j < K; ++j) {
             a[0] += bf16_lo(gv[j].x); a[1] += bf16_hi(gv[j].x);
             a[2] += bf16_lo(gv[j].y); a[3] += bf16_hi(gv[j].y);
-            a[4] += bf16_lo(gv[j].z); a[5] += bf16_hi(gv[j].z);
-            a[6] += bf16_lo(gv[j].w); a[7] += bf16_hi(gv[j].w);
         }
     } else {
         for (int j = 0; j < k; ++j) {
-            u32x4 gv = ld_stream(reinterpret_cast<const u32x4 *>(gt.g[j] + lo));
+            u32x2 gv = ld_stream(reinterpret_cast<const u32x2 *>(gt.g[j] + lo));
             a[0] += bf16_lo(gv.x); a[1] += bf16_hi(gv.x);
             a[2] += bf16_lo(gv.y); a[3] += bf16_hi(gv.y);
-            a[4] += bf16_lo(gv.z); a[5] += bf16_hi(gv.z);
-            a[6] += bf16_lo(gv.w); a[7] += bf16_hi(gv.w);
         }
     }
 }
@@ -117,57 +120,48 @@ __device__ __forceinline__ float accumulate_one(const GradTable &gt, int k, int6
 }
 
 // ---- fused accumulate + clip + AdamW + bf16 emit -----------------------------------------
+// One workgroup = one tile of GS_TILE consecutive elements (GS_BLOCK lanes x 4), one group of 4
+// per lane.  Tiles start at multiples of 4 counted from element 0 of the arrays, not from
+// `begin`, so the grouping does not move with the range.
 template <int K>
 __global__ __launch_bounds__(GS_BLOCK) void k_accum_adamw(StepArgs A)
 {
+    const int k = (K > 0) ? K : A.k;
+    const int64_t lo = ((A.begin >> 2) + (int64_t)blockIdx.x * GS_BLOCK + threadIdx.x) << 2;
+    if (lo >= A.end) return;
     const float c = clip_coefficient(A.d_sqnorm, A.max_norm);
     const StepConsts s = A.c;
-    const int k = (K > 0) ? K : A.k;
-    const int64_t g_first = A.begin >> 3;
-    const int64_t g_end = (A.end + 7) >> 3;
-    const int64_t stride = (int64_t)gridDim.x * GS_BLOCK;
 
-    for (int64_t grp = g_first + (int64_t)blockIdx.x * GS_BLOCK + threadIdx.x; grp < g_end; grp += stride) {
-        const int64_t lo = grp << 3;
-        if (lo >= A.begin && lo + 8 <= A.end) {
-            float a[8];
-            accumulate_group<K>(A.gt, k, lo, a);
-            f32x4 p0 = ld_stream(reinterpret_cast<const f32x4 *>(A.p + lo));
-            f32x4 p1 = ld_stream(reinterpret_cast<const f32x4 *>(A.p + lo + 4));
-            f32x4 m0 = ld_stream(reinterpret_cast<const f32x4 *>(A.m + lo));
-            f32x4 m1 = ld_stream(reinterpret_cast<const f32x4 *>(A.m + lo + 4));
-            f32x4 v0 = ld_stream(reinterpret_cast<const f32x4 *>(A.v + lo));
-            f32x4 v1 = ld_stream(reinterpret_cast<const f32x4 *>(A.v + lo + 4));
-            float P[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
-            float M[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
-            float V[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+    if (lo >= A.begin && lo + 4 <= A.end) {
+        float a[4];
+        accumulate_group<K>(A.gt, k, lo, a);
+        f32x4 p = ld_stream(reinterpret_cast<const f32x4 *>(A.p + lo));
+        f32x4 m = ld_stream(reinterpret_cast<const f32x4 *>(A.m + lo));
+        f32x4 v = ld_stream(reinterpret_cast<const f32x4 *>(A.v + lo));
+        float P[4] = {p.x, p.y, p.z, p.w};
+        float M[4] = {m.x, m.y, m.z, m.w};
+        float V[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-            for (int e = 0; e < 8; ++e) adamw_element(a[e], c, s, P[e], M[e], V[e]);
-            st_stream(reinterpret_cast<f32x4 *>(A.p + lo), f32x4{P[0], P[1], P[2], P[3]});
-            st_stream(reinterpret_cast<f32x4 *>(A.p + lo + 4), f32x4{P[4], P[5], P[6], P[7]});
-            st_stream(reinterpret_cast<f32x4 *>(A.m + lo), f32x4{M[0], M[1], M[2], M[3]});
-            st_stream(reinterpret_cast<f32x4 *>(A.m + lo + 4), f32x4{M[4], M[5], M[6], M[7]});
-            st_stream(reinterpret_cast<f32x4 *>(A.v + lo), f32x4{V[0], V[1], V[2], V[3]});
-            st_stream(reinterpret_cast<f32x4 *>(A.v + lo + 4), f32x4{V[4], V[5], V[6], V[7]});
-            u32x4 wv;
-            wv.x = f32_to_bf16_bits(P[0]) | (f32_to_bf16_bits(P[1]) << 16);
-            wv.y = f32_to_bf16_bits(P[2]) | (f32_to_bf16_bits(P[3]) << 16);
-            wv.z = f32_to_bf16_bits(P[4]) | (f32_to_bf16_bits(P[5]) << 16);
-            wv.w = f32_to_bf16_bits(P[6]) | (f32_to_bf16_bits(P[7]) << 16);
-            st_stream(reinterpret_cast<u32x4 *>(A.w + lo), wv);
-        } else {
-            // ragged head / tail of the range: same arithmetic, one element at a time
-            const int64_t i0 = lo > A.begin ? lo : A.begin;
-            const int64_t i1 = lo + 8 < A.end ? lo + 8 : A.end;
-            for (int64_t i = i0; i < i1; ++i) {
-                float a = accumulate_one(A.gt, k, i);
-                float pi = A.p[i], mi = A.m[i], vi = A.v[i];
-                adamw_element(a, c, s, pi, mi, vi);
-                A.p[i] = pi;
-                A.m[i] = mi;
-                A.v[i] = vi;
-                A.w[i] = (uint16_t)f32_to_bf16_bits(pi);
-            }
+        for (int e = 0; e < 4; ++e) adamw_element(a[e], c, s, P[e], M[e], V[e]);
+        st_stream(reinterpret_cast<f32x4 *>(A.p + lo), f32x4{P[0], P[1], P[2], P[3]});
+        st_stream(reinterpret_cast<f32x4 *>(A.m + lo), f32x4{M[0], M[1], M[2], M[3]});
+        st_stream(reinterpret_cast<f32x4 *>(A.v + lo), f32x4{V[0], V[1], V[2], V[3]});
+        u32x2 wv;
+        wv.x = f32_to_bf16_bits(P[0]) | (f32_to_bf16_bits(P[1]) << 16);
+        wv.y = f32_to_bf16_bits(P[2]) | (f32_to_bf16_bits(P[3]) << 16);
+        st_stream(reinterpret_cast<u32x2 *>(A.w + lo), wv);
+    } else {
+        // ragged head / tail of the range: same arithmetic, one element at a time
+        const int64_t i0 = lo > A.begin ? lo : A.begin;
+        const int64_t i1 = lo + 4 < A.end ? lo + 4 : A.end;
+        for (int64_t i = i0; i < i1; ++i) {
+            float a = accumulate_one(A.gt, k, i);
+            float pi = A.p[i], mi = A.m[i], vi = A.v[i];
+            adamw_element(a, c, s, pi, mi, vi);
+            A.p[i] = pi;
+            A.m[i] = mi;
+            A.v[i] = vi;
+            A.w[i] = (uint16_t)f32_to_bf16_bits(pi);
         }
     }
 }
@@ -183,9 +177,10 @@ __device__ __forceinline__ double wave_sum(double x)
     return x;
 }
 
+template <int BLOCK>
 __device__ __forceinline__ double block_sum(double x, double *lds)
 {
-    constexpr int NW = GS_BLOCK / 64;
+    constexpr int NW = BLOCK / 64;
     x = wave_sum(x);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     if (lane == 0) lds[wave] = x;
@@ -198,62 +193,60 @@ __device__ __forceinline__ double block_sum(double x, double *lds)
     return t;   // valid in thread 0
 }
 
+// Workgroup b reads `span` consecutive tiles starting at tile b*span (tiles counted from the
+// 4-aligned start of the range): a short contiguous run per workgroup is what the read path
+// likes best.
 template <int K>
-__global__ __launch_bounds__(GS_BLOCK) void k_grad_sqnorm(SqnormArgs A)
+__global__ __launch_bounds__(GS_BLOCK) void k_grad_sqnorm(SqnormArgs A, int span)
 {
     __shared__ double lds[GS_BLOCK / 64];
     const int k = (K > 0) ? K : A.k;
-    const int64_t g_first = A.begin >> 3;
-    const int64_t g_end = (A.end + 7) >> 3;
-    const int64_t stride = (int64_t)gridDim.x * GS_BLOCK;
+    const int64_t first = ((A.begin >> 2) + (int64_t)blockIdx.x * span * GS_BLOCK + threadIdx.x) << 2;
     double acc0 = 0.0, acc1 = 0.0;
-    for (int64_t grp = g_first + (int64_t)blockIdx.x * GS_BLOCK + threadIdx.x; grp < g_end; grp += stride) {
-        const int64_t lo = grp << 3;
-        if (lo >= A.begin && lo + 8 <= A.end) {
-            float a[8];
+    for (int it = 0; it < span; ++it) {
+        const int64_t lo = first + (int64_t)it * GS_TILE;
+        if (lo >= A.end) break;
+        if (lo >= A.begin && lo + 4 <= A.end) {
+            float a[4];
             accumulate_group<K>(A.gt, k, lo, a);
-#pragma unroll
-            for (int e = 0; e < 8; e += 2) {
-                acc0 = fma((double)a[e], (double)a[e], acc0);
-                acc1 = fma((double)a[e + 1], (double)a[e + 1], acc1);
-            }
+            acc0 = fma((double)a[0], (double)a[0], acc0);
+            acc1 = fma((double)a[1], (double)a[1], acc1);
+            acc0 = fma((double)a[2], (double)a[2], acc0);
+            acc1 = fma((double)a[3], (double)a[3], acc1);
         } else {
             const int64_t i0 = lo > A.begin ? lo : A.begin;
-            const int64_t i1 = lo + 8 < A.end ? lo + 8 : A.end;
+            const int64_t i1 = lo + 4 < A.end ? lo + 4 : A.end;
             for (int64_t i = i0; i < i1; ++i) {
                 float a = accumulate_one(A.gt, k, i);
                 acc0 = fma((double)a, (double)a, acc0);
             }
         }
     }
-    double t = block_sum(acc0 + acc1, lds);
+    double t = block_sum<GS_BLOCK>(acc0 + acc1, lds);
     if (threadIdx.x == 0) A.partials[blockIdx.x] = t;
 }
 
-__global__ __launch_bounds__(GS_BLOCK) void k_sqnorm_finalize(const double *partials, int nparts, double *out, int accumulate)
+__global__ __launch_bounds__(GS_FINAL_BLOCK) void k_sqnorm_finalize(const double *partials, int nparts, double *out, int accumulate)
 {
-    __shared__ double lds[GS_BLOCK / 64];
+    __shared__ double lds[GS_FINAL_BLOCK / 64];
     double x = 0.0;
-    for (int i = threadIdx.x; i < nparts; i += GS_BLOCK) x += partials[i];
-    double t = block_sum(x, lds);
+    for (int i = threadIdx.x; i < nparts; i += GS_FINAL_BLOCK) x += partials[i];
+    double t = block_sum<GS_FINAL_BLOCK>(x, lds);
     if (threadIdx.x == 0) *out = accumulate ? (*out + t) : t;
 }
 
 // ---- launchers -----------------------------------------------------------------------------
-static int grid_for(int64_t ngroups, int num_cu, int blocks_per_cu, int cap)
+static int64_t tiles_of(int64_t begin, int64_t end)
 {
-    int64_t need = (ngroups + GS_BLOCK - 1) / GS_BLOCK;
-    int64_t lim = (int64_t)num_cu * blocks_per_cu;
-    if (lim > cap) lim = cap;
-    if (need > lim) need = lim;
-    if (need < 1) need = 1;
-    return (int)need;
+    const int64_t groups = ((end + 3) >> 2) - (begin >> 2);
+    return (groups + GS_BLOCK - 1) / GS_BLOCK;
 }
 
-hipError_t launch_accum_adamw(const StepArgs &A, int num_cu, hipStream_t stream)
+hipError_t launch_accum_adamw(const StepArgs &A, hipStream_t stream)
 {
-    const int64_t ngroups = ((A.end + 7) >> 3) - (A.begin >> 3);
-    const int grid = grid_for(ngroups, num_cu, GS_STEP_BLOCKS_PER_CU, 1 << 30);
+    const int64_t tiles = tiles_of(A.begin, A.end);
+    if (tiles < 1 || tiles > 0x7fffffff) return hipErrorInvalidValue;
+    const int grid = (int)tiles;
     switch (A.k) {
     case 1: k_accum_adamw<1><<<grid, GS_BLOCK, 0, stream>>>(A); break;
     case 2: k_accum_adamw<2><<<grid, GS_BLOCK, 0, stream>>>(A); break;
@@ -265,21 +258,26 @@ hipError_t launch_accum_adamw(const StepArgs &A, int num_cu, hipStream_t stream)
     return hipGetLastError();
 }
 
-hipError_t launch_grad_sqnorm(const SqnormArgs &A, double *d_out, int accumulate, int num_cu, hipStream_t stream)
+hipError_t launch_grad_sqnorm(const SqnormArgs &A, double *d_out, int accumulate, hipStream_t stream)
 {
-    const int64_t ngroups = ((A.end + 7) >> 3) - (A.begin >> 3);
-    const int grid = grid_for(ngroups, num_cu, GS_NORM_BLOCKS_PER_CU, GS_SQNORM_MAX_BLOCKS);
+    int64_t tiles = tiles_of(A.begin, A.end);
+    if (tiles < 1) tiles = 1;
+    int64_t span = GS_NORM_SPAN;
+    if ((tiles + span - 1) / span > GS_SQNORM_MAX_BLOCKS) span = (tiles + GS_SQNORM_MAX_BLOCKS - 1) / GS_SQNORM_MAX_BLOCKS;
+    if (span > 0x7fffffff) return hipErrorInvalidValue;
+    const int grid = (int)((tiles + span - 1) / span);
+    const int sp = (int)span;
     switch (A.k) {
-    case 1: k_grad_sqnorm<1><<<grid, GS_BLOCK, 0, stream>>>(A); break;
-    case 2: k_grad_sqnorm<2><<<grid, GS_BLOCK, 0, stream>>>(A); break;
-    case 4: k_grad_sqnorm<4><<<grid, GS_BLOCK, 0, stream>>>(A); break;
-    case 8: k_grad_sqnorm<8><<<grid, GS_BLOCK, 0, stream>>>(A); break;
-    case 16: k_grad_sqnorm<16><<<grid, GS_BLOCK, 0, stream>>>(A); break;
-    default: k_grad_sqnorm<0><<<grid, GS_BLOCK, 0, stream>>>(A); break;
+    case 1: k_grad_sqnorm<1><<<grid, GS_BLOCK, 0, stream>>>(A, sp); break;
+    case 2: k_grad_sqnorm<2><<<grid, GS_BLOCK, 0, stream>>>(A, sp); break;
+    case 4: k_grad_sqnorm<4><<<grid, GS_BLOCK, 0, stream>>>(A, sp); break;
+    case 8: k_grad_sqnorm<8><<<grid, GS_BLOCK, 0, stream>>>(A, sp); break;
+    case 16: k_grad_sqnorm<16><<<grid, GS_BLOCK, 0, stream>>>(A, sp); break;
+    default: k_grad_sqnorm<0><<<grid, GS_BLOCK, 0, stream>>>(A, sp); break;
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    k_sqnorm_finalize<<<1, GS_BLOCK, 0, stream>>>(A.partials, grid, d_out, accumulate);
+    k_sqnorm_finalize<<<1, GS_FINAL_BLOCK, 0, stream>>>(A.partials, grid, d_out, accumulate);
     return hipGetLastError();
 }
 

@@ -8,8 +8,9 @@
 //
 // Staging keeps the absolute-index grouping of the kernel: chunk [b,e) is placed in its slot
 // at offset (b mod 8), and the kernel is handed a base pointer such that element i of the
-// layer sits at base[i].  The 8-element groups therefore fall exactly where they fall for
-// device-resident states, which makes the streamed result bit-identical for any chunk size.
+// layer sits at base[i].  The kernel's 4-element groups (and their 16-byte alignment)
+// therefore fall exactly where they fall for device-resident states, which makes the streamed
+// result bit-identical for any chunk size.
 #include <hip/hip_runtime.h>
 
 #include <cstring>
@@ -22,7 +23,6 @@ using namespace gs;
 
 struct gs_stream_ctx {
     int device = 0;
-    int num_cu = 0;
     int64_t chunk = 0;
     int slots = 0;
     int64_t slot_elems = 0;                 // chunk + 8 (room for the (b mod 8) offset)
@@ -73,7 +73,6 @@ gs_status gs_stream_ctx_create(gs_stream_ctx **out, int64_t chunk_elems, int slo
     c->slot_elems = ((chunk_elems + 8 + 63) / 64) * 64;   // keep every slot array 256-byte aligned
     hipError_t e = hipGetDevice(&c->device);
     if (e != hipSuccess) { destroy_partial(c); return hip_fail(e, "hipGetDevice"); }
-    if (device_num_cu(&c->num_cu) != GS_OK) { destroy_partial(c); return GS_ERR_HIP; }
 
     // default priority on every stream
     if ((e = hipStreamCreateWithFlags(&c->s_h2d, hipStreamNonBlocking)) != hipSuccess ||
@@ -184,7 +183,7 @@ gs_status gs_stream_layer_step(gs_stream_ctx *c, float *h_p, float *h_m, float *
         A.v = reinterpret_cast<float *>(reinterpret_cast<intptr_t>(sv) + shift);
         A.begin = b;
         A.end = e;
-        hipError_t le = launch_accum_adamw(A, c->num_cu, c->s_comp);
+        hipError_t le = launch_accum_adamw(A, c->s_comp);
         if (le != hipSuccess) return hip_fail(le, "gs_stream_layer_step launch");
         GS_TRY(hipEventRecord(c->ev_comp[slot], c->s_comp), "hipEventRecord(compute)");
 

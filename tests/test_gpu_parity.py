@@ -1,6 +1,7 @@
 """GPU parity: the HIP path (through the C-ABI binding) against the CPU oracle, element by
-element, on the same seeded inputs.  Sizes span several launch tiles (a block handles 2048
-elements per sweep) and ragged tails; full workload sizes are in test_gpu_fullsize.py."""
+element, on the same seeded inputs.  Sizes span many launch tiles (a workgroup handles 1024
+elements; a norm workgroup a run of 8 such tiles) and ragged tails; full workload sizes are in
+test_gpu_fullsize.py."""
 import numpy as np
 import pytest
 import torch
@@ -77,7 +78,7 @@ def test_sqnorm_exact_patterns():
 # ----------------------------------------------------------------------------- a1,a3-a6 fused step
 @pytest.mark.parametrize("k", [1, 2, 3, 4, 7, 8, 16, 17, 32])
 def test_step_matches_oracle_all_k(k):
-    n = 2 * 2048 * 256 + 2048 * 3 + 5           # > one full grid sweep on 256 CUs x 8 blocks, ragged tail
+    n = 2 * 2048 * 256 + 2048 * 3 + 5           # ~1000 tiles, ragged tail
     case = DeviceCase(n, k, seed=10 + k)
     S = case.gpu_sqnorm()
     hp = gs.HParams(**{**HP.__dict__, "step": 10})
