@@ -31,7 +31,7 @@ HEADLINE = "gpt65b_layer_h8192_k16"
 # HBM bytes per gs_accum_adamw launch on the headline workload from rocprofv3 --pmc runs
 # (FETCH_SIZE and WRITE_SIZE, each scaled by the same counter's reading on a plain copy kernel
 # of known size); see profiles/.  None until measured for the workload being run.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {"gpt65b_layer_h8192_k16": 46_714_044_211}   # profiles/gs_step_gpt65b_layer_h8192_k16.txt
 
 
 def parse():
@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default=HEADLINE)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain elementwise copy of 2^28 floats (1 GiB in, 1 GiB out) three times before the "
+                         "timed region, as the known-size reference for rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     ap.add_argument("--cpu-sample", type=int, default=1 << 27, help="elements of the workload the oracle is timed on")
     return ap.parse_args()
 
@@ -127,6 +130,14 @@ def main():
         gs.gs_accum_adamw(p, m, v, w, grads, 0, n, hp_at(i), sq)
         if evs:
             evs[2].record()
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     for i in range(args.warmup):
         one_step(i)
