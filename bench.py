@@ -45,6 +45,7 @@ def parse():
                     help="also run a plain elementwise copy of 2^28 floats (1 GiB in, 1 GiB out) three times before the "
                          "timed region, as the known-size reference for rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     ap.add_argument("--cpu-sample", type=int, default=1 << 27, help="elements of the workload the oracle is timed on")
+    ap.add_argument("--slots", type=int, default=3, help="staging slots of the streamed workload")
     return ap.parse_args()
 
 
@@ -81,6 +82,221 @@ def cpu_baseline(wl, p, m, v, grads, hp, sample: int):
                       f"{cores} threads over disjoint ranges, {dt:.2f} s wall"}
 
 
+def _hp_of(gs, wl, i=0):
+    return gs.HParams(wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay, wl.max_grad_norm, wl.step + i)
+
+
+def _base_record(wl, props, value, steps, warmup, ms_per_step, extra_cfg=None):
+    cfg = {"workload": wl.name, "h": wl.h, "layers": wl.layers, "n_params": wl.n, "k_grad_buffers": wl.k,
+           "grad_dtype": "bf16", "state_dtype": "f32", "clip_max_norm": wl.max_grad_norm,
+           "device": props.name, "compute_units": props.multi_processor_count, "hbm_bytes": props.total_memory}
+    cfg.update(extra_cfg or {})
+    return {"metric": "params/s, fused grad-norm + accumulate + AdamW step", "value": value, "unit": "params/s",
+            "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic", "config": cfg}
+
+
+def bench_split(args, wl):
+    """Split step (delay ratio alpha, Sec. 4.4 of the paper): the immediate part of the range is
+    updated right away, the deferred part on a second stream while a bf16 GEMM standing in for the
+    next iteration's forward runs on the first.  Reports the step's and the GEMM's slowdown under
+    contention.  Timing only; split == full is checked bit for bit by the GPU tests."""
+    import torch
+
+    from paper_2512_17570_amd import gs
+    from paper_2512_17570_amd import inputs as I
+
+    dev = "cuda:0"
+    props = torch.cuda.get_device_properties(0)
+    n, k = wl.n, wl.k
+    s_pt = int(wl.extra["immediate_frac"] * n)
+    p, m, v, grads = I.make_workload_tensors(wl, dev)
+    w = torch.zeros(n, dtype=torch.bfloat16, device=dev)
+    sq = torch.zeros(1, dtype=torch.float64, device=dev)
+    ws = torch.empty(gs.gs_sqnorm_workspace_bytes(), dtype=torch.uint8, device=dev)
+    tokens = wl.extra["gemm_tokens"]
+    ga = torch.randn(tokens, wl.h, dtype=torch.bfloat16, device=dev)
+    gb = torch.randn(wl.h, wl.h, dtype=torch.bfloat16, device=dev)
+    gc = torch.empty(tokens, wl.h, dtype=torch.bfloat16, device=dev)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    hp = _hp_of(gs, wl)
+    gs.gs_grad_sqnorm(grads, 0, n, sq, ws)
+    torch.cuda.synchronize()
+
+    def timed(fn, stream, reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(stream):
+            e0.record(stream)
+            for _ in range(reps):
+                fn(stream)
+            e1.record(stream)
+        return e0, e1
+
+    def full(st):
+        gs.gs_accum_adamw(p, m, v, w, grads, 0, n, hp, sq, stream=st)
+
+    def immediate(st):
+        gs.gs_accum_adamw(p, m, v, w, grads, 0, s_pt, hp, sq, stream=st)
+
+    def deferred(st):
+        gs.gs_accum_adamw(p, m, v, w, grads, s_pt, n, hp, sq, stream=st)
+
+    def gemm(st):
+        torch.matmul(ga, gb, out=gc)
+
+    def alone(fn, stream, reps):
+        for _ in range(args.warmup):
+            with torch.cuda.stream(stream):
+                fn(stream)
+        torch.cuda.synchronize()
+        e0, e1 = timed(fn, stream, reps)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    t_full = alone(full, sb, args.steps)
+    t_imm = alone(immediate, sb, args.steps)
+    t_def = alone(deferred, sb, args.steps)
+    t_gemm = alone(gemm, sa, 4 * args.steps)
+    reps_gemm = max(1, int(round(t_def / t_gemm)))     # GEMMs that cover one deferred step
+    # concurrent: each iteration = one deferred step on sb || reps_gemm GEMMs on sa
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    pairs = []
+    for _ in range(args.steps):
+        eg = timed(gemm, sa, reps_gemm)
+        ed = timed(deferred, sb, 1)
+        pairs.append((eg, ed))
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / args.steps * 1e3
+    t_gemm_c = sum(a.elapsed_time(b) for (a, b), _ in pairs) / args.steps / reps_gemm
+    t_def_c = sum(a.elapsed_time(b) for _, (a, b) in pairs) / args.steps
+    bpp = 2 * k + 26
+    rec = _base_record(wl, props, n / ((t_imm + t_def) * 1e-3), args.steps, args.warmup, t_imm + t_def,
+                       {"split_point": s_pt, "immediate_frac": wl.extra["immediate_frac"],
+                        "gemm": f"bf16 {tokens}x{wl.h} @ {wl.h}x{wl.h}", "gemms_per_deferred_step": reps_gemm})
+    rec["roofline"] = {"bound": "hbm", "kernel": "gs_accum_adamw (full range)", "achieved": n * bpp / (t_full * 1e-3) / 1e9,
+                       "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": n * bpp / (t_full * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       "traffic": None, "algorithmic_bytes_per_launch": n * bpp, "avg_launch_ms": t_full}
+    gemm_flop = 2.0 * tokens * wl.h * wl.h
+    rec["split"] = {
+        "full_ms": t_full, "immediate_ms": t_imm, "deferred_alone_ms": t_def,
+        "deferred_alone_GBps": (n - s_pt) * bpp / (t_def * 1e-3) / 1e9,
+        "gemm_alone_ms": t_gemm, "gemm_alone_TFLOPs": gemm_flop / (t_gemm * 1e-3) / 1e12,
+        "deferred_concurrent_ms": t_def_c, "gemm_concurrent_ms": t_gemm_c,
+        "deferred_slowdown": t_def_c / t_def, "gemm_slowdown": t_gemm_c / t_gemm,
+        "concurrent_wall_ms_per_iter": wall, "serial_ms_per_iter": t_def + reps_gemm * t_gemm,
+    }
+    rec["cpu_baseline"] = None
+    print(json.dumps(rec))
+
+
+def bench_streamed(args, wl):
+    """Streamed step (Sec. 2.2 chunk loop / Sec. 4.3 pipeline of the paper, with host<->HBM PCIe as
+    the slow link): fp32 p/m/v of all layers live in pinned host memory and are processed in
+    2^26-element chunks, upload | kernel | download overlapped on three streams.  Reports params/s
+    against the measured duplex pinned-copy ceiling (12 B up + 12 B down per parameter)."""
+    import torch
+
+    from paper_2512_17570_amd import gs
+    from paper_2512_17570_amd import inputs as I
+
+    dev = "cuda:0"
+    props = torch.cuda.get_device_properties(0)
+    chunk = wl.extra["chunk_elems"]
+    layers, nl, k = wl.layers, I.layer_numel(wl.h), wl.k
+    # pin as many layers as the host allows
+    bufs = None
+    while layers > 0:
+        bufs = gs.pinned_f32_set(layers * nl, 3)
+        if bufs is not None:
+            break
+        layers -= 1
+    if layers == 0:
+        print("bench.py: cannot pin host memory for even one layer", file=sys.stderr)
+        sys.exit(1)
+    n = layers * nl
+    (hp_t, hp_p), (hm_t, hm_p), (hv_t, hv_p) = bufs
+    grads_l, w_l = [], []
+    for L in range(layers):
+        pd, md, vd = I.make_states(nl, wl.seed + L, dev)
+        for dst, src in ((hp_t, pd), (hm_t, md), (hv_t, vd)):
+            dst[L * nl:(L + 1) * nl].copy_(src)
+        del pd, md, vd
+        grads_l.append(I.make_grads(nl, k, wl.grad_sigma, wl.seed + L, dev))
+        w_l.append(torch.zeros(nl, dtype=torch.bfloat16, device=dev))
+    sq = torch.zeros(1, dtype=torch.float64, device=dev)
+    ws = torch.empty(gs.gs_sqnorm_workspace_bytes(), dtype=torch.uint8, device=dev)
+    for L in range(layers):                      # global norm over all layers
+        gs.gs_grad_sqnorm(grads_l[L], 0, nl, sq, ws, accumulate=(L > 0))
+    torch.cuda.synchronize()
+
+    # duplex pinned-copy ceiling with the same chunk size: raw hipMemcpyAsync both ways at once
+    import ctypes
+    hip = ctypes.CDLL(os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so"))
+    hip.hipMemcpyAsync.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
+    hip.hipMemcpyAsync.restype = ctypes.c_int
+    up, dn = torch.cuda.Stream(), torch.cuda.Stream()
+    stage = [torch.empty(chunk, dtype=torch.float32, device=dev) for _ in range(2)]
+    stage[1].zero_()
+
+    def copy_pass(nchunks, h2d, d2h):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for c in range(nchunks):
+            lo = ((c * chunk) % max(1, n - chunk)) * 4
+            if h2d:
+                r = hip.hipMemcpyAsync(stage[0].data_ptr(), hp_p + lo, chunk * 4, 1, up.cuda_stream)
+                assert r == 0, r
+            if d2h:
+                r = hip.hipMemcpyAsync(hm_p + lo, stage[1].data_ptr(), chunk * 4, 2, dn.cuda_stream)
+                assert r == 0, r
+        torch.cuda.synchronize()
+        return nchunks * chunk * 4 / (time.perf_counter() - t0) / 1e9
+
+    copy_pass(8, True, True)                      # warm the copy engines and both streams
+    h2d_only_gbs = copy_pass(32, True, False)
+    d2h_only_gbs = copy_pass(32, False, True)
+    duplex_dir_gbs = copy_pass(48, True, True)
+    hm_t[:].copy_(hp_t)         # the probe overwrote parts of m: restore finite values (timing only)
+    del stage
+
+    ctx = gs.gs_stream_ctx_create(chunk, args.slots)
+    cur = torch.cuda.current_stream()
+
+    def one_pass(i):
+        hp = _hp_of(gs, wl, i)
+        for L in range(layers):
+            o = L * nl * 4
+            gs.gs_stream_layer_step(ctx, hp_p + o, hm_p + o, hv_p + o, w_l[L], grads_l[L], nl, hp, sq, producer_stream=cur)
+        gs.gs_stream_ctx_sync(ctx)
+
+    for i in range(args.warmup):
+        one_pass(i)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        one_pass(args.warmup + i)
+    elapsed = time.perf_counter() - t0
+    gs.gs_stream_ctx_destroy(ctx)
+    per = elapsed / args.steps
+    rec = _base_record(wl, props, n / per, args.steps, args.warmup, per * 1e3,
+                       {"layers_pinned": layers, "n_params": n, "chunk_elems": chunk, "slots": args.slots,
+                        "host_pinned_bytes": 12 * n})
+    pcie_dir = 12 * n / per / 1e9
+    link = min(h2d_only_gbs, d2h_only_gbs)
+    rec["roofline"] = {"bound": "pcie", "kernel": "gs_stream_layer_step (H2D 12 B + D2H 12 B per parameter)",
+                       "achieved": pcie_dir, "peak": link, "unit": "GB/s per direction",
+                       "frac": pcie_dir / link, "traffic": None,
+                       "peak_source": "measured on this host: one-directional pinned hipMemcpyAsync of the same chunk "
+                                      "size (the slower of H2D and D2H); a full-duplex link would sustain it both ways",
+                       "h2d_only_GBps": h2d_only_gbs, "d2h_only_GBps": d2h_only_gbs,
+                       "duplex_probe_GBps_per_direction": duplex_dir_gbs,
+                       "params_per_s_bound": link * 1e9 / 12}
+    rec["cpu_baseline"] = None
+    print(json.dumps(rec))
+    for t, ptr in bufs:
+        gs.gs_pinned_free(ptr)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -102,6 +318,10 @@ def main():
     wl = I.WORKLOADS[args.workload]
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if "immediate_frac" in wl.extra:
+        return bench_split(args, wl)
+    if "chunk_elems" in wl.extra:
+        return bench_streamed(args, wl)
     props = torch.cuda.get_device_properties(0)
 
     t_gen = time.perf_counter()

@@ -133,6 +133,7 @@ void *gs_pinned_alloc(size_t bytes)
     hipError_t e = hipHostMalloc(&ptr, bytes, hipHostMallocDefault);
     if (e != hipSuccess) {
         hip_fail(e, "hipHostMalloc");
+        (void)hipGetLastError();   // do not leave a sticky error for the caller's next HIP call
         return nullptr;
     }
     return ptr;

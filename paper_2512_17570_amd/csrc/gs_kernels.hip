@@ -121,14 +121,16 @@ __device__ __forceinline__ float accumulate_one(const GradTable &gt, int k, int6
 
 // ---- fused accumulate + clip + AdamW + bf16 emit -----------------------------------------
 // One workgroup = one tile of GS_TILE consecutive elements (GS_BLOCK lanes x 4), one group of 4
-// per lane.  Tiles start at multiples of 4 counted from element 0 of the arrays, not from
-// `begin`, so the grouping does not move with the range.
+// per lane.  Tiles start at multiples of GS_TILE counted from element 0 of the arrays, not from
+// `begin`: the grouping does not move with the range (partition independence), and a wave's
+// 1 KB accesses stay line-aligned for any `begin` (a split point in the middle of a layer would
+// otherwise make every wave straddle two extra lines).
 template <int K>
 __global__ __launch_bounds__(GS_BLOCK) void k_accum_adamw(StepArgs A)
 {
     const int k = (K > 0) ? K : A.k;
-    const int64_t lo = ((A.begin >> 2) + (int64_t)blockIdx.x * GS_BLOCK + threadIdx.x) << 2;
-    if (lo >= A.end) return;
+    const int64_t lo = (A.begin / GS_TILE + (int64_t)blockIdx.x) * GS_TILE + (int64_t)threadIdx.x * 4;
+    if (lo >= A.end || lo + 4 <= A.begin) return;
     const float c = clip_coefficient(A.d_sqnorm, A.max_norm);
     const StepConsts s = A.c;
 
@@ -194,18 +196,19 @@ __device__ __forceinline__ double block_sum(double x, double *lds)
 }
 
 // Workgroup b reads `span` consecutive tiles starting at tile b*span (tiles counted from the
-// 4-aligned start of the range): a short contiguous run per workgroup is what the read path
-// likes best.
+// GS_TILE-aligned start of the range): a short contiguous run per workgroup is what the read
+// path likes best.
 template <int K>
 __global__ __launch_bounds__(GS_BLOCK) void k_grad_sqnorm(SqnormArgs A, int span)
 {
     __shared__ double lds[GS_BLOCK / 64];
     const int k = (K > 0) ? K : A.k;
-    const int64_t first = ((A.begin >> 2) + (int64_t)blockIdx.x * span * GS_BLOCK + threadIdx.x) << 2;
+    const int64_t first = (A.begin / GS_TILE + (int64_t)blockIdx.x * span) * GS_TILE + (int64_t)threadIdx.x * 4;
     double acc0 = 0.0, acc1 = 0.0;
     for (int it = 0; it < span; ++it) {
         const int64_t lo = first + (int64_t)it * GS_TILE;
         if (lo >= A.end) break;
+        if (lo + 4 <= A.begin) continue;
         if (lo >= A.begin && lo + 4 <= A.end) {
             float a[4];
             accumulate_group<K>(A.gt, k, lo, a);
@@ -238,8 +241,8 @@ __global__ __launch_bounds__(GS_FINAL_BLOCK) void k_sqnorm_finalize(const double
 // ---- launchers -----------------------------------------------------------------------------
 static int64_t tiles_of(int64_t begin, int64_t end)
 {
-    const int64_t groups = ((end + 3) >> 2) - (begin >> 2);
-    return (groups + GS_BLOCK - 1) / GS_BLOCK;
+    if (end <= begin) return 0;
+    return (end - 1) / GS_TILE - begin / GS_TILE + 1;
 }
 
 hipError_t launch_accum_adamw(const StepArgs &A, hipStream_t stream)

@@ -226,3 +226,17 @@ def pinned_f32(n: int):
         raise MemoryError(f"gs_pinned_alloc({n * 4}) failed: {gs_last_hip_error()}")
     buf = (ctypes.c_float * n).from_address(ptr)
     return torch.from_numpy(np.ctypeslib.as_array(buf)), ptr
+
+
+def pinned_f32_set(n: int, count: int = 3):
+    """`count` pinned float32 tensors of n elements each, or None if the host cannot pin that much
+    (anything allocated on the way is released).  Returns [(tensor, ptr), ...]."""
+    got = []
+    try:
+        for _ in range(count):
+            got.append(pinned_f32(n))
+        return got
+    except MemoryError:
+        for _, ptr in got:
+            gs_pinned_free(ptr)
+        return None
