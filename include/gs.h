@@ -125,6 +125,50 @@ gs_status gs_accum_adamw(float *p, float *m, float *v, uint16_t *w_bf16,
                          const gs_adamw_hparams *hp, const double *d_sqnorm, void *stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Staged two-pass variant (same results, fewer bytes when k > 4).  The paper keeps a layer's
+ * gradients accumulated in ONE full-precision GPU buffer (Sec. 1 footnote; Sec. 3.4; Sec. 6.2
+ * notes that such gradient buffers are resident in GPU memory); the global-norm dependency (Sec. 2.1) forces two passes over
+ * the gradients anyway, so the first pass can leave that fp32 sum behind and the second pass reads
+ * 4 bytes per parameter instead of 2k:  (2k+4) + 30 bytes per parameter in total instead of
+ * 2k + (2k+26).
+ * ------------------------------------------------------------------------------------------ */
+
+/*
+ * gs_grad_sqnorm that also writes acc_f32[i] = a_i (the fp32 sum of the k bf16 gradients, j
+ * ascending) for i in [begin,end).  acc_f32: device fp32, >= end elements, 16-byte aligned, caller
+ * owned.  All other arguments and the value left in *d_sqnorm are exactly those of gs_grad_sqnorm.
+ */
+gs_status gs_grad_accum_sqnorm(const uint16_t *const *grads, int k, int64_t begin, int64_t end,
+                               float *acc_f32, double *d_sqnorm, int accumulate,
+                               void *d_workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * gs_accum_adamw with the gradient sum taken from acc_f32 (as written by gs_grad_accum_sqnorm)
+ * instead of k bf16 buffers.  p, m, v, w come out bit-identical to gs_accum_adamw on the
+ * same gradients, and the same partition independence holds.
+ */
+gs_status gs_adamw_from_acc(float *p, float *m, float *v, uint16_t *w_bf16, const float *acc_f32,
+                            int64_t begin, int64_t end, const gs_adamw_hparams *hp,
+                            const double *d_sqnorm, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Compute-unit budget for the deferred part (Sec. 4.4: the delayed fraction of the optimizer
+ * step runs concurrently with the next iteration's forward pass and only has to finish before
+ * its layer executes).  A bandwidth-bound step that fills every CU slows a concurrent GEMM far
+ * more than it is slowed itself; a stream confined to a subset of the CUs leaves the rest of the
+ * chip, and part of the memory system, to the forward pass.
+ * ------------------------------------------------------------------------------------------ */
+
+/*
+ * Creates a HIP stream (default priority) whose kernels run on at most `num_cus` compute units
+ * (the lowest-numbered ones; 1 <= num_cus <= CUs of the current device).  *stream receives a
+ * hipStream_t to pass as the `stream` argument of the calls above.  Destroy with
+ * gs_cu_stream_destroy after the work on it has finished.
+ */
+gs_status gs_cu_stream_create(void **stream, int num_cus);
+gs_status gs_cu_stream_destroy(void *stream);
+
+/* ------------------------------------------------------------------------------------------
  * Streamed step for states that live in pinned host memory (Sec. 2.2: for each parameter
  * chunk, load gradients + master parameters + optimizer states, step, write back; Sec. 4.3
  * the five optimizer-step stages of the backward pipeline -- here the slow link is

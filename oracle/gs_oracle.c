@@ -72,6 +72,13 @@ static float accumulate_f32(const uint16_t *const *grads, int k, int64_t i)
     return a;
 }
 
+/* a1 on its own: out[i] = fp32 sum of the k buffers at i, for i in [begin,end). */
+void gs_oracle_accumulate(const uint16_t *const *grads, int k, int64_t begin, int64_t end, float *out)
+{
+    for (int64_t i = begin; i < end; ++i)
+        out[i] = accumulate_f32(grads, k, i);
+}
+
 /* ---- a2: squared L2 norm of the accumulated gradient over [begin,end) ------------------ */
 /* (Sec. 2.1: clipping needs the global L2 norm.)  Each square is exact in double. */
 double gs_oracle_grad_sqnorm(const uint16_t *const *grads, int k, int64_t begin, int64_t end)

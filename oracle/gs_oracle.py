@@ -64,6 +64,8 @@ def lib():
         L.gs_oracle_f32_to_bf16.restype = ctypes.c_uint16
         L.gs_oracle_grad_sqnorm.argtypes = [u16pp, ctypes.c_int, ctypes.c_int64, ctypes.c_int64]
         L.gs_oracle_grad_sqnorm.restype = ctypes.c_double
+        L.gs_oracle_accumulate.argtypes = [u16pp, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p]
+        L.gs_oracle_accumulate.restype = None
         L.gs_oracle_clip_coef.argtypes = [ctypes.c_double, ctypes.c_float]
         L.gs_oracle_clip_coef.restype = ctypes.c_float
         L.gs_oracle_accum_adamw.argtypes = [ctypes.c_void_p] * 4 + [
@@ -105,6 +107,16 @@ def grad_sqnorm(grads, begin: int = 0, end: int | None = None) -> float:
     end = n if end is None else end
     assert 0 <= begin <= end <= n
     return float(lib().gs_oracle_grad_sqnorm(tab, k, begin, end))
+
+
+def accumulate(grads, begin: int = 0, end: int | None = None) -> np.ndarray:
+    """fp32 sum of the k bf16 buffers (j ascending); entries outside [begin,end) are 0."""
+    tab, k, n = _grad_table(grads)
+    end = n if end is None else end
+    assert 0 <= begin <= end <= n
+    out = np.zeros(n, np.float32)
+    lib().gs_oracle_accumulate(tab, k, begin, end, out.ctypes.data)
+    return out
 
 
 def clip_coef(sqnorm_total: float, max_norm: float) -> float:

@@ -70,9 +70,9 @@ extern "C" {
 
 size_t gs_sqnorm_workspace_bytes(void) { return (size_t)GS_SQNORM_MAX_BLOCKS * sizeof(double); }
 
-gs_status gs_grad_sqnorm(const uint16_t *const *grads, int k, int64_t begin, int64_t end,
-                         double *d_sqnorm, int accumulate,
-                         void *d_workspace, size_t workspace_bytes, void *stream)
+static gs_status sqnorm_impl(const uint16_t *const *grads, int k, int64_t begin, int64_t end, float *acc,
+                             double *d_sqnorm, int accumulate, void *d_workspace, size_t workspace_bytes,
+                             void *stream)
 {
     gs_status st = validate_grads(grads, k);
     if (st != GS_OK) return st;
@@ -89,21 +89,42 @@ gs_status gs_grad_sqnorm(const uint16_t *const *grads, int k, int64_t begin, int
     A.begin = begin;
     A.end = end;
     A.partials = static_cast<double *>(d_workspace);
+    A.acc = acc;
     hipError_t e = launch_grad_sqnorm(A, d_sqnorm, accumulate, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e, "gs_grad_sqnorm launch");
     return GS_OK;
 }
 
-gs_status gs_accum_adamw(float *p, float *m, float *v, uint16_t *w_bf16,
-                         const uint16_t *const *grads, int k, int64_t begin, int64_t end,
-                         const gs_adamw_hparams *hp, const double *d_sqnorm, void *stream)
+gs_status gs_grad_sqnorm(const uint16_t *const *grads, int k, int64_t begin, int64_t end,
+                         double *d_sqnorm, int accumulate,
+                         void *d_workspace, size_t workspace_bytes, void *stream)
+{
+    return sqnorm_impl(grads, k, begin, end, nullptr, d_sqnorm, accumulate, d_workspace, workspace_bytes, stream);
+}
+
+gs_status gs_grad_accum_sqnorm(const uint16_t *const *grads, int k, int64_t begin, int64_t end,
+                               float *acc_f32, double *d_sqnorm, int accumulate,
+                               void *d_workspace, size_t workspace_bytes, void *stream)
+{
+    if (!acc_f32 || !aligned16(acc_f32)) return GS_ERR_INVALID_ARG;
+    return sqnorm_impl(grads, k, begin, end, acc_f32, d_sqnorm, accumulate, d_workspace, workspace_bytes, stream);
+}
+
+static gs_status adamw_impl(float *p, float *m, float *v, uint16_t *w_bf16,
+                            const uint16_t *const *grads, int k, const float *acc,
+                            int64_t begin, int64_t end, const gs_adamw_hparams *hp,
+                            const double *d_sqnorm, void *stream)
 {
     if (!p || !m || !v || !w_bf16) return GS_ERR_INVALID_ARG;
     if (!aligned16(p) || !aligned16(m) || !aligned16(v) || !aligned16(w_bf16)) return GS_ERR_INVALID_ARG;
-    gs_status st = validate_grads(grads, k);
-    if (st != GS_OK) return st;
+    if (acc) {
+        if (!aligned16(acc)) return GS_ERR_INVALID_ARG;
+    } else {
+        gs_status sg = validate_grads(grads, k);
+        if (sg != GS_OK) return sg;
+    }
     if (begin < 0 || end < begin) return GS_ERR_INVALID_ARG;
-    st = validate_hparams(hp);
+    gs_status st = validate_hparams(hp);
     if (st != GS_OK) return st;
     if (d_sqnorm && (reinterpret_cast<uintptr_t>(d_sqnorm) & 7u)) return GS_ERR_INVALID_ARG;
     if (begin == end) return GS_OK;
@@ -114,8 +135,10 @@ gs_status gs_accum_adamw(float *p, float *m, float *v, uint16_t *w_bf16,
     A.m = m;
     A.v = v;
     A.w = w_bf16;
-    for (int j = 0; j < k; ++j) A.gt.g[j] = grads[j];
-    A.k = k;
+    if (!acc)
+        for (int j = 0; j < k; ++j) A.gt.g[j] = grads[j];
+    A.k = acc ? 0 : k;
+    A.acc = acc;
     A.begin = begin;
     A.end = end;
     A.c = make_consts(*hp);
@@ -123,6 +146,56 @@ gs_status gs_accum_adamw(float *p, float *m, float *v, uint16_t *w_bf16,
     A.d_sqnorm = d_sqnorm;
     hipError_t e = launch_accum_adamw(A, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e, "gs_accum_adamw launch");
+    return GS_OK;
+}
+
+gs_status gs_accum_adamw(float *p, float *m, float *v, uint16_t *w_bf16,
+                         const uint16_t *const *grads, int k, int64_t begin, int64_t end,
+                         const gs_adamw_hparams *hp, const double *d_sqnorm, void *stream)
+{
+    return adamw_impl(p, m, v, w_bf16, grads, k, nullptr, begin, end, hp, d_sqnorm, stream);
+}
+
+gs_status gs_adamw_from_acc(float *p, float *m, float *v, uint16_t *w_bf16, const float *acc_f32,
+                            int64_t begin, int64_t end, const gs_adamw_hparams *hp,
+                            const double *d_sqnorm, void *stream)
+{
+    if (!acc_f32) return GS_ERR_INVALID_ARG;
+    return adamw_impl(p, m, v, w_bf16, nullptr, 0, acc_f32, begin, end, hp, d_sqnorm, stream);
+}
+
+gs_status gs_cu_stream_create(void **stream, int num_cus)
+{
+    if (!stream) return GS_ERR_INVALID_ARG;
+    *stream = nullptr;
+    if (num_cus < 1) return GS_ERR_INVALID_ARG;
+    int dev = 0, cus = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return hip_fail(e, "hipDeviceGetAttribute");
+    if (num_cus > cus) return GS_ERR_INVALID_ARG;
+    // one bit per CU, lowest-numbered CUs enabled (the driver rejects scattered masks)
+    const uint32_t words = (uint32_t)((cus + 31) / 32);
+    uint32_t mask[64] = {0};
+    if (words > 64) return GS_ERR_INVALID_ARG;
+    for (int cu = 0; cu < num_cus; ++cu) mask[cu / 32] |= (1u << (cu % 32));
+    hipStream_t s = nullptr;
+    e = hipExtStreamCreateWithCUMask(&s, words, mask);
+    if (e != hipSuccess) {
+        gs_status r = hip_fail(e, "hipExtStreamCreateWithCUMask");
+        (void)hipGetLastError();
+        return r;
+    }
+    *stream = s;
+    return GS_OK;
+}
+
+gs_status gs_cu_stream_destroy(void *stream)
+{
+    if (!stream) return GS_ERR_INVALID_ARG;
+    hipError_t e = hipStreamDestroy(static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "hipStreamDestroy");
     return GS_OK;
 }
 

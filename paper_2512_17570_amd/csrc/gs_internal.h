@@ -33,6 +33,7 @@ struct StepArgs {
     StepConsts c;
     float max_norm;
     const double *d_sqnorm;
+    const float *acc;   // non-null: staged fp32 gradient sum replaces the k bf16 streams
 };
 
 struct SqnormArgs {
@@ -40,6 +41,7 @@ struct SqnormArgs {
     int k;
     int64_t begin, end;
     double *partials;
+    float *acc;         // non-null: also write the fp32 gradient sum here
 };
 
 hipError_t launch_accum_adamw(const StepArgs &A, hipStream_t stream);

@@ -128,7 +128,7 @@ __device__ __forceinline__ float accumulate_one(const GradTable &gt, int k, int6
 template <int K>
 __global__ __launch_bounds__(GS_BLOCK) void k_accum_adamw(StepArgs A)
 {
-    const int k = (K > 0) ? K : A.k;
+    const int k = (K > 0) ? K : A.k;     // K < 0: gradients come as one staged fp32 sum (A.acc)
     const int64_t lo = (A.begin / GS_TILE + (int64_t)blockIdx.x) * GS_TILE + (int64_t)threadIdx.x * 4;
     if (lo >= A.end || lo + 4 <= A.begin) return;
     const float c = clip_coefficient(A.d_sqnorm, A.max_norm);
@@ -136,7 +136,12 @@ __global__ __launch_bounds__(GS_BLOCK) void k_accum_adamw(StepArgs A)
 
     if (lo >= A.begin && lo + 4 <= A.end) {
         float a[4];
-        accumulate_group<K>(A.gt, k, lo, a);
+        if constexpr (K < 0) {
+            f32x4 av = ld_stream(reinterpret_cast<const f32x4 *>(A.acc + lo));
+            a[0] = av.x; a[1] = av.y; a[2] = av.z; a[3] = av.w;
+        } else {
+            accumulate_group<K>(A.gt, k, lo, a);
+        }
         f32x4 p = ld_stream(reinterpret_cast<const f32x4 *>(A.p + lo));
         f32x4 m = ld_stream(reinterpret_cast<const f32x4 *>(A.m + lo));
         f32x4 v = ld_stream(reinterpret_cast<const f32x4 *>(A.v + lo));
@@ -157,7 +162,8 @@ __global__ __launch_bounds__(GS_BLOCK) void k_accum_adamw(StepArgs A)
         const int64_t i0 = lo > A.begin ? lo : A.begin;
         const int64_t i1 = lo + 4 < A.end ? lo + 4 : A.end;
         for (int64_t i = i0; i < i1; ++i) {
-            float a = accumulate_one(A.gt, k, i);
+            float a;
+            if constexpr (K < 0) a = A.acc[i]; else a = accumulate_one(A.gt, k, i);
             float pi = A.p[i], mi = A.m[i], vi = A.v[i];
             adamw_element(a, c, s, pi, mi, vi);
             A.p[i] = pi;
@@ -198,7 +204,9 @@ __device__ __forceinline__ double block_sum(double x, double *lds)
 // Workgroup b reads `span` consecutive tiles starting at tile b*span (tiles counted from the
 // GS_TILE-aligned start of the range): a short contiguous run per workgroup is what the read
 // path likes best.
-template <int K>
+// STAGE: also write the fp32 sum a_i to A.acc (the staged two-pass variant: the step then reads
+// one fp32 stream instead of re-reading k bf16 streams).
+template <int K, bool STAGE>
 __global__ __launch_bounds__(GS_BLOCK) void k_grad_sqnorm(SqnormArgs A, int span)
 {
     __shared__ double lds[GS_BLOCK / 64];
@@ -212,6 +220,7 @@ __global__ __launch_bounds__(GS_BLOCK) void k_grad_sqnorm(SqnormArgs A, int span
         if (lo >= A.begin && lo + 4 <= A.end) {
             float a[4];
             accumulate_group<K>(A.gt, k, lo, a);
+            if constexpr (STAGE) st_stream(reinterpret_cast<f32x4 *>(A.acc + lo), f32x4{a[0], a[1], a[2], a[3]});
             acc0 = fma((double)a[0], (double)a[0], acc0);
             acc1 = fma((double)a[1], (double)a[1], acc1);
             acc0 = fma((double)a[2], (double)a[2], acc0);
@@ -221,6 +230,7 @@ __global__ __launch_bounds__(GS_BLOCK) void k_grad_sqnorm(SqnormArgs A, int span
             const int64_t i1 = lo + 4 < A.end ? lo + 4 : A.end;
             for (int64_t i = i0; i < i1; ++i) {
                 float a = accumulate_one(A.gt, k, i);
+                if constexpr (STAGE) A.acc[i] = a;
                 acc0 = fma((double)a, (double)a, acc0);
             }
         }
@@ -250,6 +260,10 @@ hipError_t launch_accum_adamw(const StepArgs &A, hipStream_t stream)
     const int64_t tiles = tiles_of(A.begin, A.end);
     if (tiles < 1 || tiles > 0x7fffffff) return hipErrorInvalidValue;
     const int grid = (int)tiles;
+    if (A.acc) {
+        k_accum_adamw<-1><<<grid, GS_BLOCK, 0, stream>>>(A);
+        return hipGetLastError();
+    }
     switch (A.k) {
     case 1: k_accum_adamw<1><<<grid, GS_BLOCK, 0, stream>>>(A); break;
     case 2: k_accum_adamw<2><<<grid, GS_BLOCK, 0, stream>>>(A); break;
@@ -270,14 +284,19 @@ hipError_t launch_grad_sqnorm(const SqnormArgs &A, double *d_out, int accumulate
     if (span > 0x7fffffff) return hipErrorInvalidValue;
     const int grid = (int)((tiles + span - 1) / span);
     const int sp = (int)span;
+#define GS_NORM_CASE(KK)                                                              \
+    if (A.acc) k_grad_sqnorm<KK, true><<<grid, GS_BLOCK, 0, stream>>>(A, sp);          \
+    else k_grad_sqnorm<KK, false><<<grid, GS_BLOCK, 0, stream>>>(A, sp);               \
+    break
     switch (A.k) {
-    case 1: k_grad_sqnorm<1><<<grid, GS_BLOCK, 0, stream>>>(A, sp); break;
-    case 2: k_grad_sqnorm<2><<<grid, GS_BLOCK, 0, stream>>>(A, sp); break;
-    case 4: k_grad_sqnorm<4><<<grid, GS_BLOCK, 0, stream>>>(A, sp); break;
-    case 8: k_grad_sqnorm<8><<<grid, GS_BLOCK, 0, stream>>>(A, sp); break;
-    case 16: k_grad_sqnorm<16><<<grid, GS_BLOCK, 0, stream>>>(A, sp); break;
-    default: k_grad_sqnorm<0><<<grid, GS_BLOCK, 0, stream>>>(A, sp); break;
+    case 1: GS_NORM_CASE(1);
+    case 2: GS_NORM_CASE(2);
+    case 4: GS_NORM_CASE(4);
+    case 8: GS_NORM_CASE(8);
+    case 16: GS_NORM_CASE(16);
+    default: GS_NORM_CASE(0);
     }
+#undef GS_NORM_CASE
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     k_sqnorm_finalize<<<1, GS_FINAL_BLOCK, 0, stream>>>(A.partials, grid, d_out, accumulate);

@@ -69,6 +69,14 @@ _lib.gs_grad_sqnorm.restype = ctypes.c_int
 _lib.gs_accum_adamw.argtypes = [_vp, _vp, _vp, _vp, _pp, ctypes.c_int, _i64, _i64,
                                 ctypes.POINTER(gs_adamw_hparams), _vp, _vp]
 _lib.gs_accum_adamw.restype = ctypes.c_int
+_lib.gs_grad_accum_sqnorm.argtypes = [_pp, ctypes.c_int, _i64, _i64, _vp, _vp, ctypes.c_int, _vp, ctypes.c_size_t, _vp]
+_lib.gs_grad_accum_sqnorm.restype = ctypes.c_int
+_lib.gs_adamw_from_acc.argtypes = [_vp, _vp, _vp, _vp, _vp, _i64, _i64, ctypes.POINTER(gs_adamw_hparams), _vp, _vp]
+_lib.gs_adamw_from_acc.restype = ctypes.c_int
+_lib.gs_cu_stream_create.argtypes = [ctypes.POINTER(_vp), ctypes.c_int]
+_lib.gs_cu_stream_create.restype = ctypes.c_int
+_lib.gs_cu_stream_destroy.argtypes = [_vp]
+_lib.gs_cu_stream_destroy.restype = ctypes.c_int
 _lib.gs_stream_ctx_create.argtypes = [ctypes.POINTER(_vp), _i64, ctypes.c_int]
 _lib.gs_stream_ctx_create.restype = ctypes.c_int
 _lib.gs_stream_ctx_destroy.argtypes = [_vp]
@@ -177,6 +185,43 @@ def gs_accum_adamw(p, m, v, w_bf16, grads, begin: int, end: int, hp, d_sqnorm=No
     st = _lib.gs_accum_adamw(_addr(p), _addr(m), _addr(v), _addr(w_bf16), tab, kk if k is None else k,
                              begin, end, _hp(hp), _addr(d_sqnorm), _stream(stream))
     return _check(st, "gs_accum_adamw", check)
+
+
+def gs_grad_accum_sqnorm(grads, begin: int, end: int, acc_f32, d_sqnorm, d_workspace,
+                         workspace_bytes: int | None = None, accumulate: bool = False, stream=None,
+                         check: bool = True, k: int | None = None) -> int:
+    tab, kk = _table(grads) if grads is not None else (None, 0)
+    for j, g in enumerate(grads or ()):
+        _need(g, end, 2, f"grads[{j}]")
+    _need(acc_f32, end, 4, "acc_f32")
+    if workspace_bytes is None:
+        workspace_bytes = d_workspace.numel() * d_workspace.element_size() if hasattr(d_workspace, "numel") else 0
+    st = _lib.gs_grad_accum_sqnorm(tab, kk if k is None else k, begin, end, _addr(acc_f32), _addr(d_sqnorm),
+                                   int(bool(accumulate)), _addr(d_workspace), workspace_bytes, _stream(stream))
+    return _check(st, "gs_grad_accum_sqnorm", check)
+
+
+def gs_adamw_from_acc(p, m, v, w_bf16, acc_f32, begin: int, end: int, hp, d_sqnorm=None, stream=None,
+                      check: bool = True) -> int:
+    for x, eb, nm in ((p, 4, "p"), (m, 4, "m"), (v, 4, "v"), (w_bf16, 2, "w_bf16"), (acc_f32, 4, "acc_f32")):
+        _need(x, end, eb, nm)
+    st = _lib.gs_adamw_from_acc(_addr(p), _addr(m), _addr(v), _addr(w_bf16), _addr(acc_f32), begin, end,
+                                _hp(hp), _addr(d_sqnorm), _stream(stream))
+    return _check(st, "gs_adamw_from_acc", check)
+
+
+def gs_cu_stream_create(num_cus: int, check: bool = True):
+    """Returns the raw hipStream_t (int) of a stream confined to `num_cus` compute units."""
+    out = ctypes.c_void_p()
+    st = _lib.gs_cu_stream_create(ctypes.byref(out), num_cus)
+    if check:
+        _check(st, "gs_cu_stream_create", True)
+        return out.value
+    return st, out.value
+
+
+def gs_cu_stream_destroy(stream, check: bool = True) -> int:
+    return _check(_lib.gs_cu_stream_destroy(stream), "gs_cu_stream_destroy", check)
 
 
 def gs_stream_ctx_create(chunk_elems: int, slots: int = 3, check: bool = True):

@@ -26,7 +26,8 @@ def test_header_symbols_all_exported():
     names = declared_functions()
     assert {"gs_grad_sqnorm", "gs_accum_adamw", "gs_stream_layer_step", "gs_sqnorm_workspace_bytes",
             "gs_stream_ctx_create", "gs_stream_ctx_destroy", "gs_stream_ctx_sync", "gs_pinned_alloc",
-            "gs_pinned_free", "gs_strerror", "gs_last_hip_error"} <= set(names)
+            "gs_pinned_free", "gs_strerror", "gs_last_hip_error", "gs_grad_accum_sqnorm", "gs_adamw_from_acc",
+            "gs_cu_stream_create", "gs_cu_stream_destroy"} <= set(names)
     lib = ctypes.CDLL(gs.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in gs.h but not exported"
@@ -120,6 +121,31 @@ def test_stream_api_rejects_without_gpu():
     assert gs.gs_stream_layer_step(None, FAKE, FAKE, FAKE, FAKE, [FAKE], 10, GOOD_HP, check=False) == gs.GS_ERR_INVALID_ARG
     assert gs.gs_pinned_alloc(0) is None
     gs.gs_pinned_free(None)
+
+
+def test_staged_variant_rejects_without_gpu():
+    ws = gs.gs_sqnorm_workspace_bytes()
+    ok = dict(grads=[FAKE], begin=0, end=64, acc_f32=FAKE, d_sqnorm=FAKE, d_workspace=FAKE, workspace_bytes=ws,
+              stream=0, check=False)
+    for kw, want in ((dict(acc_f32=None), gs.GS_ERR_INVALID_ARG), (dict(acc_f32=FAKE + 4), gs.GS_ERR_INVALID_ARG),
+                     (dict(grads=[FAKE] * 33), gs.GS_ERR_INVALID_ARG), (dict(begin=9, end=3), gs.GS_ERR_INVALID_ARG),
+                     (dict(workspace_bytes=8), gs.GS_ERR_WORKSPACE), (dict(d_sqnorm=None), gs.GS_ERR_INVALID_ARG)):
+        assert gs.gs_grad_accum_sqnorm(**{**ok, **kw}) == want
+    assert gs.gs_grad_accum_sqnorm(**{**ok, "begin": 5, "end": 5, "accumulate": True}) == gs.GS_OK
+    ok2 = dict(p=FAKE, m=FAKE, v=FAKE, w_bf16=FAKE, acc_f32=FAKE, begin=0, end=64, hp=GOOD_HP, d_sqnorm=None,
+               stream=0, check=False)
+    for kw in (dict(acc_f32=None), dict(acc_f32=FAKE + 8), dict(p=None), dict(hp=gs.HParams(step=0)),
+               dict(begin=-1), dict(d_sqnorm=FAKE + 4)):
+        assert gs.gs_adamw_from_acc(**{**ok2, **kw}) == gs.GS_ERR_INVALID_ARG
+    assert gs.gs_adamw_from_acc(**{**ok2, "begin": 7, "end": 7}) == gs.GS_OK
+
+
+def test_cu_stream_rejects_without_gpu():
+    st, s = gs.gs_cu_stream_create(0, check=False)
+    assert st == gs.GS_ERR_INVALID_ARG and not s
+    st, s = gs.gs_cu_stream_create(-4, check=False)
+    assert st == gs.GS_ERR_INVALID_ARG and not s
+    assert gs.gs_cu_stream_destroy(None, check=False) == gs.GS_ERR_INVALID_ARG
 
 
 def test_error_raises_through_binding():

@@ -339,3 +339,74 @@ def test_streamed_two_layers_back_to_back_with_poisoned_slots():
         for bufs in held:
             for t, ptr in bufs:
                 gs.gs_pinned_free(ptr)
+
+
+# ----------------------------------------------------------------------------- staged two-pass variant
+@pytest.mark.parametrize("k", [1, 3, 8, 16, 20])
+def test_staged_variant_equals_fused_and_oracle(k):
+    n = 2048 * 130 + 7
+    case = DeviceCase(n, k, seed=100 + k)
+    acc = torch.full((n,), float("nan"), dtype=torch.float32, device=DEV)
+    sq2 = torch.zeros(1, dtype=torch.float64, device=DEV)
+    S = case.gpu_sqnorm()
+    gs.gs_grad_accum_sqnorm(case.grads, 0, n, acc, sq2, case.ws)
+    torch.cuda.synchronize()
+    assert float(sq2.item()) == S                          # same reduction, same bits
+    assert np.array_equal(np_f32(acc), O.accumulate(case.h_g))
+    fused = run_gpu_step(case, HP)
+    st = case.clone_states()
+    gs.gs_adamw_from_acc(*st, acc, 0, n, HP, sq2)
+    torch.cuda.synchronize()
+    for a, b in zip(fused, st):
+        assert torch.equal(a, b)
+    compare_states(st, case.oracle_step(HP, O.clip_coef(O.grad_sqnorm(case.h_g), HP.max_grad_norm)), f"staged k={k}")
+
+
+def test_staged_variant_ranges_and_split():
+    n = 2048 * 90 + 11
+    case = DeviceCase(n, 4, seed=120)
+    acc = torch.full((n,), 7.0, dtype=torch.float32, device=DEV)
+    sq2 = torch.zeros(1, dtype=torch.float64, device=DEV)
+    b, e = 1021, n - 1030
+    gs.gs_grad_accum_sqnorm(case.grads, b, e, acc, sq2, case.ws)
+    torch.cuda.synchronize()
+    want = O.accumulate(case.h_g, b, e)
+    got = np_f32(acc)
+    assert np.array_equal(got[b:e], want[b:e]) and np.all(got[:b] == 7.0) and np.all(got[e:] == 7.0)
+    assert abs(float(sq2.item()) - O.grad_sqnorm(case.h_g, b, e)) <= 1e-12 * float(sq2.item())
+    # accumulate the norm over two ranges while staging both
+    gs.gs_grad_accum_sqnorm(case.grads, 0, b, acc, sq2, case.ws, accumulate=True)
+    gs.gs_grad_accum_sqnorm(case.grads, e, n, acc, sq2, case.ws, accumulate=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(np_f32(acc), O.accumulate(case.h_g))
+    assert abs(float(sq2.item()) - case.gpu_sqnorm()) <= 1e-13 * float(sq2.item())
+    full = run_gpu_step(case, HP)
+    st = case.clone_states()
+    s_pt = int(0.4 * n)
+    gs.gs_adamw_from_acc(*st, acc, 0, s_pt, HP, case.sq)
+    gs.gs_adamw_from_acc(*st, acc, s_pt, n, HP, case.sq)
+    torch.cuda.synchronize()
+    for a, c in zip(full, st):
+        assert torch.equal(a, c)
+
+
+# ----------------------------------------------------------------------------- CU-budgeted stream
+def test_cu_budget_stream_gives_same_result():
+    n = 2048 * 400 + 3
+    case = DeviceCase(n, 8, seed=130)
+    case.gpu_sqnorm()
+    full = run_gpu_step(case, HP)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    st_, raw = gs.gs_cu_stream_create(cus + 1, check=False)
+    assert st_ == gs.GS_ERR_INVALID_ARG and not raw
+    raw = gs.gs_cu_stream_create(max(1, cus // 2))
+    try:
+        st = case.clone_states()
+        torch.cuda.synchronize()
+        gs.gs_accum_adamw(*st, case.grads, 0, n, HP, case.sq, stream=raw)
+        ext = torch.cuda.ExternalStream(raw)
+        ext.synchronize()
+        for a, b in zip(full, st):
+            assert torch.equal(a, b)
+    finally:
+        gs.gs_cu_stream_destroy(raw)

@@ -331,6 +331,25 @@ def test_k_buffers_equal_one_step_on_their_sum():
     assert O.grad_sqnorm(gk) == O.grad_sqnorm(g1)
 
 
+def test_accumulate_matches_sequential_float32_adds_and_exact_sum():
+    """a1 on its own: equal to numpy float32 adds in the same order (library arithmetic), and to
+    the exact (fp64) sum whenever that sum is representable in fp32."""
+    n, k = 10_000, 7
+    _, _, _, g = rand_case(n, k, seed=70, sigma=1e-2)
+    want = np.zeros(n, np.float32)
+    for b in g:
+        want = (want + bf16_bits_to_f64(b).astype(np.float32)).astype(np.float32)
+    got = O.accumulate(g)
+    assert np.array_equal(got, want)
+    exact = sum(bf16_bits_to_f64(b) for b in g)
+    assert np.allclose(got, exact, rtol=4e-7, atol=0)
+    rep = exact.astype(np.float32).astype(np.float64) == exact
+    assert rep.sum() > n // 4 and np.array_equal(got[rep].astype(np.float64), exact[rep])
+    part = O.accumulate(g, 100, 200)
+    assert np.array_equal(part[100:200], want[100:200]) and not part[:100].any() and not part[200:].any()
+    assert math.isclose(float(np.dot(got.astype(np.float64), got.astype(np.float64))), O.grad_sqnorm(g), rel_tol=1e-12)
+
+
 def test_sum_not_mean():
     n = 256
     one = np.full(n, 0x3C00, dtype=np.uint16)       # 2^-7
