@@ -205,16 +205,20 @@ __device__ __forceinline__ double block_sum(double x, double *lds)
 // GS_TILE-aligned start of the range): a short contiguous run per workgroup is what the read
 // path likes best.
 // STAGE: also write the fp32 sum a_i to A.acc (the staged two-pass variant: the step then reads
-// one fp32 stream instead of re-reading k bf16 streams).
-template <int K, bool STAGE>
-__global__ __launch_bounds__(GS_BLOCK) void k_grad_sqnorm(SqnormArgs A, int span)
+// one fp32 stream instead of re-reading k bf16 streams).  Once a store stream is involved, runs
+// of tiles per workgroup cost bandwidth again (stores want in-order, one-tile workgroups), so
+// the staged kernel uses 1024-lane workgroups (4096-element tiles) and a span of 1 wherever the
+// partials still fit the workspace.
+template <int K, bool STAGE, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void k_grad_sqnorm(SqnormArgs A, int span)
 {
-    __shared__ double lds[GS_BLOCK / 64];
+    constexpr int TILE = BLOCK * 4;
+    __shared__ double lds[BLOCK / 64];
     const int k = (K > 0) ? K : A.k;
-    const int64_t first = (A.begin / GS_TILE + (int64_t)blockIdx.x * span) * GS_TILE + (int64_t)threadIdx.x * 4;
+    const int64_t first = (A.begin / TILE + (int64_t)blockIdx.x * span) * TILE + (int64_t)threadIdx.x * 4;
     double acc0 = 0.0, acc1 = 0.0;
     for (int it = 0; it < span; ++it) {
-        const int64_t lo = first + (int64_t)it * GS_TILE;
+        const int64_t lo = first + (int64_t)it * TILE;
         if (lo >= A.end) break;
         if (lo + 4 <= A.begin) continue;
         if (lo >= A.begin && lo + 4 <= A.end) {
@@ -235,7 +239,7 @@ __global__ __launch_bounds__(GS_BLOCK) void k_grad_sqnorm(SqnormArgs A, int span
             }
         }
     }
-    double t = block_sum<GS_BLOCK>(acc0 + acc1, lds);
+    double t = block_sum<BLOCK>(acc0 + acc1, lds);
     if (threadIdx.x == 0) A.partials[blockIdx.x] = t;
 }
 
@@ -249,10 +253,10 @@ __global__ __launch_bounds__(GS_FINAL_BLOCK) void k_sqnorm_finalize(const double
 }
 
 // ---- launchers -----------------------------------------------------------------------------
-static int64_t tiles_of(int64_t begin, int64_t end)
+static int64_t tiles_of(int64_t begin, int64_t end, int64_t tile = GS_TILE)
 {
     if (end <= begin) return 0;
-    return (end - 1) / GS_TILE - begin / GS_TILE + 1;
+    return (end - 1) / tile - begin / tile + 1;
 }
 
 hipError_t launch_accum_adamw(const StepArgs &A, hipStream_t stream)
@@ -277,16 +281,18 @@ hipError_t launch_accum_adamw(const StepArgs &A, hipStream_t stream)
 
 hipError_t launch_grad_sqnorm(const SqnormArgs &A, double *d_out, int accumulate, hipStream_t stream)
 {
-    int64_t tiles = tiles_of(A.begin, A.end);
+    const bool stage = A.acc != nullptr;
+    const int block = stage ? GS_STAGE_BLOCK : GS_BLOCK;
+    int64_t tiles = tiles_of(A.begin, A.end, (int64_t)block * 4);
     if (tiles < 1) tiles = 1;
-    int64_t span = GS_NORM_SPAN;
+    int64_t span = stage ? 1 : GS_NORM_SPAN;
     if ((tiles + span - 1) / span > GS_SQNORM_MAX_BLOCKS) span = (tiles + GS_SQNORM_MAX_BLOCKS - 1) / GS_SQNORM_MAX_BLOCKS;
     if (span > 0x7fffffff) return hipErrorInvalidValue;
     const int grid = (int)((tiles + span - 1) / span);
     const int sp = (int)span;
-#define GS_NORM_CASE(KK)                                                              \
-    if (A.acc) k_grad_sqnorm<KK, true><<<grid, GS_BLOCK, 0, stream>>>(A, sp);          \
-    else k_grad_sqnorm<KK, false><<<grid, GS_BLOCK, 0, stream>>>(A, sp);               \
+#define GS_NORM_CASE(KK)                                                                              \
+    if (stage) k_grad_sqnorm<KK, true, GS_STAGE_BLOCK><<<grid, GS_STAGE_BLOCK, 0, stream>>>(A, sp);   \
+    else k_grad_sqnorm<KK, false, GS_BLOCK><<<grid, GS_BLOCK, 0, stream>>>(A, sp);                    \
     break
     switch (A.k) {
     case 1: GS_NORM_CASE(1);
