@@ -56,7 +56,9 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        L = ctypes.CDLL(build())
+        # GS_ORACLE_LIB: used only by the mutation test, which points the pins at a deliberately
+        # broken build of the oracle to show that they notice.
+        L = ctypes.CDLL(os.environ.get("GS_ORACLE_LIB") or build())
         u16pp = ctypes.POINTER(ctypes.c_void_p)
         L.gs_oracle_bf16_to_f32.argtypes = [ctypes.c_uint16]
         L.gs_oracle_bf16_to_f32.restype = ctypes.c_float
