@@ -152,6 +152,43 @@ gs_status gs_adamw_from_acc(float *p, float *m, float *v, uint16_t *w_bf16, cons
                             const double *d_sqnorm, void *stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Speculative single-pass step.  Sec. 2.1 of the paper points at prior work that takes the
+ * optimizer step before the global gradient norm is known, because clipping rarely changes the
+ * gradients; the step then does not have to wait for the whole backward pass, and the gradients
+ * are read once (2k+26 bytes per parameter in total instead of 2k + 2k+26).  Undoing a wrong
+ * guess needs the old states, so these entry points are out of place.
+ * ------------------------------------------------------------------------------------------ */
+
+/*
+ * Out-of-place form of gs_accum_adamw: states are read from p, m, v and written to p_out,
+ * m_out, v_out (device fp32, >= end elements, 16-byte aligned).  Each output may be exactly its
+ * own input (then this is gs_accum_adamw) or must not overlap it; anything else is rejected.
+ */
+gs_status gs_accum_adamw_oop(const float *p, const float *m, const float *v,
+                             float *p_out, float *m_out, float *v_out, uint16_t *w_bf16,
+                             const uint16_t *const *grads, int k, int64_t begin, int64_t end,
+                             const gs_adamw_hparams *hp, const double *d_sqnorm, void *stream);
+
+/*
+ * The step with clip coefficient 1 (hp->max_grad_norm is not applied), written out of place,
+ * while the squared norm S of the same accumulated gradients over [begin,end) is reduced into
+ * *d_sqnorm (= S, or += S when accumulate != 0; same value as gs_grad_sqnorm up to fp64
+ * summation order).  Workspace as for gs_grad_sqnorm.  Protocol: run it over every range that is
+ * clipped together, accumulating S; read S back; if gs_clip_coefficient(S, max_grad_norm) == 1
+ * the outputs are the new states (swap the buffers); otherwise redo the ranges with
+ * gs_accum_adamw_oop from the untouched inputs and the finished *d_sqnorm.
+ */
+gs_status gs_accum_adamw_spec(const float *p, const float *m, const float *v,
+                              float *p_out, float *m_out, float *v_out, uint16_t *w_bf16,
+                              const uint16_t *const *grads, int k, int64_t begin, int64_t end,
+                              const gs_adamw_hparams *hp, double *d_sqnorm, int accumulate,
+                              void *d_workspace, size_t workspace_bytes, void *stream);
+
+/* Host-side copy of the clip coefficient the kernels derive from a total squared norm:
+ * min(1, max_grad_norm / ((float)sqrt(S) + 1e-6)); 1 when max_grad_norm <= 0.  No HIP call. */
+float gs_clip_coefficient(double sqnorm_total, float max_grad_norm);
+
+/* ------------------------------------------------------------------------------------------
  * Compute-unit budget for the deferred part (Sec. 4.4: the delayed fraction of the optimizer
  * step runs concurrently with the next iteration's forward pass and only has to finish before
  * its layer executes).  A bandwidth-bound step that fills every CU slows a concurrent GEMM far

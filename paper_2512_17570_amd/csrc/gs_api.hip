@@ -110,13 +110,34 @@ gs_status gs_grad_accum_sqnorm(const uint16_t *const *grads, int k, int64_t begi
     return sqnorm_impl(grads, k, begin, end, acc_f32, d_sqnorm, accumulate, d_workspace, workspace_bytes, stream);
 }
 
-static gs_status adamw_impl(float *p, float *m, float *v, uint16_t *w_bf16,
-                            const uint16_t *const *grads, int k, const float *acc,
-                            int64_t begin, int64_t end, const gs_adamw_hparams *hp,
-                            const double *d_sqnorm, void *stream)
+// host mirror of the kernels' clip coefficient
+static float clip_coefficient_host(double sqnorm_total, float max_norm)
 {
-    if (!p || !m || !v || !w_bf16) return GS_ERR_INVALID_ARG;
+    if (!(max_norm > 0.0f)) return 1.0f;
+    const float norm = (float)std::sqrt(sqnorm_total);
+    const float c = max_norm / (norm + 1e-6f);
+    return c < 1.0f ? c : 1.0f;
+}
+
+static bool alias_ok(const float *in, const float *out, int64_t end)
+{
+    // an output may be its own input, or must not overlap it at all
+    if (in == out) return true;
+    const uintptr_t a = reinterpret_cast<uintptr_t>(in), b = reinterpret_cast<uintptr_t>(out);
+    const uintptr_t bytes = (uintptr_t)end * sizeof(float);
+    return a + bytes <= b || b + bytes <= a;
+}
+
+// spec_norm_out != nullptr: speculative pass (c = 1, squared norm reduced into *spec_norm_out)
+static gs_status adamw_impl(const float *p, const float *m, const float *v, float *po, float *mo, float *vo,
+                            uint16_t *w_bf16, const uint16_t *const *grads, int k, const float *acc,
+                            int64_t begin, int64_t end, const gs_adamw_hparams *hp,
+                            const double *d_sqnorm, double *spec_norm_out, int accumulate,
+                            void *d_workspace, size_t workspace_bytes, void *stream)
+{
+    if (!p || !m || !v || !po || !mo || !vo || !w_bf16) return GS_ERR_INVALID_ARG;
     if (!aligned16(p) || !aligned16(m) || !aligned16(v) || !aligned16(w_bf16)) return GS_ERR_INVALID_ARG;
+    if (!aligned16(po) || !aligned16(mo) || !aligned16(vo)) return GS_ERR_INVALID_ARG;
     if (acc) {
         if (!aligned16(acc)) return GS_ERR_INVALID_ARG;
     } else {
@@ -124,16 +145,25 @@ static gs_status adamw_impl(float *p, float *m, float *v, uint16_t *w_bf16,
         if (sg != GS_OK) return sg;
     }
     if (begin < 0 || end < begin) return GS_ERR_INVALID_ARG;
+    if (!alias_ok(p, po, end) || !alias_ok(m, mo, end) || !alias_ok(v, vo, end)) return GS_ERR_INVALID_ARG;
     gs_status st = validate_hparams(hp);
     if (st != GS_OK) return st;
     if (d_sqnorm && (reinterpret_cast<uintptr_t>(d_sqnorm) & 7u)) return GS_ERR_INVALID_ARG;
-    if (begin == end) return GS_OK;
+    if (spec_norm_out) {
+        if (reinterpret_cast<uintptr_t>(spec_norm_out) & 7u) return GS_ERR_INVALID_ARG;
+        if (!d_workspace || workspace_bytes < gs_sqnorm_workspace_bytes()) return GS_ERR_WORKSPACE;
+        if (reinterpret_cast<uintptr_t>(d_workspace) & 7u) return GS_ERR_WORKSPACE;
+    }
+    if (begin == end && !(spec_norm_out && !accumulate)) return GS_OK;
 
     StepArgs A;
     memset(&A, 0, sizeof A);
     A.p = p;
     A.m = m;
     A.v = v;
+    A.po = po;
+    A.mo = mo;
+    A.vo = vo;
     A.w = w_bf16;
     if (!acc)
         for (int j = 0; j < k; ++j) A.gt.g[j] = grads[j];
@@ -144,7 +174,12 @@ static gs_status adamw_impl(float *p, float *m, float *v, uint16_t *w_bf16,
     A.c = make_consts(*hp);
     A.max_norm = hp->max_grad_norm;
     A.d_sqnorm = d_sqnorm;
-    hipError_t e = launch_accum_adamw(A, static_cast<hipStream_t>(stream));
+    hipError_t e;
+    if (spec_norm_out)
+        e = launch_accum_adamw_spec(A, static_cast<double *>(d_workspace), spec_norm_out, accumulate,
+                                    static_cast<hipStream_t>(stream));
+    else
+        e = launch_accum_adamw(A, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e, "gs_accum_adamw launch");
     return GS_OK;
 }
@@ -153,7 +188,33 @@ gs_status gs_accum_adamw(float *p, float *m, float *v, uint16_t *w_bf16,
                          const uint16_t *const *grads, int k, int64_t begin, int64_t end,
                          const gs_adamw_hparams *hp, const double *d_sqnorm, void *stream)
 {
-    return adamw_impl(p, m, v, w_bf16, grads, k, nullptr, begin, end, hp, d_sqnorm, stream);
+    return adamw_impl(p, m, v, p, m, v, w_bf16, grads, k, nullptr, begin, end, hp, d_sqnorm, nullptr, 0, nullptr, 0,
+                      stream);
+}
+
+gs_status gs_accum_adamw_oop(const float *p, const float *m, const float *v,
+                             float *p_out, float *m_out, float *v_out, uint16_t *w_bf16,
+                             const uint16_t *const *grads, int k, int64_t begin, int64_t end,
+                             const gs_adamw_hparams *hp, const double *d_sqnorm, void *stream)
+{
+    return adamw_impl(p, m, v, p_out, m_out, v_out, w_bf16, grads, k, nullptr, begin, end, hp, d_sqnorm, nullptr, 0,
+                      nullptr, 0, stream);
+}
+
+gs_status gs_accum_adamw_spec(const float *p, const float *m, const float *v,
+                              float *p_out, float *m_out, float *v_out, uint16_t *w_bf16,
+                              const uint16_t *const *grads, int k, int64_t begin, int64_t end,
+                              const gs_adamw_hparams *hp, double *d_sqnorm, int accumulate,
+                              void *d_workspace, size_t workspace_bytes, void *stream)
+{
+    if (!d_sqnorm) return GS_ERR_INVALID_ARG;
+    return adamw_impl(p, m, v, p_out, m_out, v_out, w_bf16, grads, k, nullptr, begin, end, hp, nullptr, d_sqnorm,
+                      accumulate, d_workspace, workspace_bytes, stream);
+}
+
+float gs_clip_coefficient(double sqnorm_total, float max_grad_norm)
+{
+    return clip_coefficient_host(sqnorm_total, max_grad_norm);
 }
 
 gs_status gs_adamw_from_acc(float *p, float *m, float *v, uint16_t *w_bf16, const float *acc_f32,
@@ -161,7 +222,8 @@ gs_status gs_adamw_from_acc(float *p, float *m, float *v, uint16_t *w_bf16, cons
                             const double *d_sqnorm, void *stream)
 {
     if (!acc_f32) return GS_ERR_INVALID_ARG;
-    return adamw_impl(p, m, v, w_bf16, nullptr, 0, acc_f32, begin, end, hp, d_sqnorm, stream);
+    return adamw_impl(p, m, v, p, m, v, w_bf16, nullptr, 0, acc_f32, begin, end, hp, d_sqnorm, nullptr, 0, nullptr, 0,
+                      stream);
 }
 
 gs_status gs_cu_stream_create(void **stream, int num_cus)

@@ -26,7 +26,8 @@ struct GradTable {
 };
 
 struct StepArgs {
-    float *p, *m, *v;
+    const float *p, *m, *v;   // states in
+    float *po, *mo, *vo;      // states out (the same arrays for the in-place entry points)
     uint16_t *w;
     GradTable gt;
     int k;
@@ -46,6 +47,7 @@ struct SqnormArgs {
 };
 
 hipError_t launch_accum_adamw(const StepArgs &A, hipStream_t stream);
+hipError_t launch_accum_adamw_spec(const StepArgs &A, double *partials, double *d_out, int accumulate, hipStream_t stream);
 hipError_t launch_grad_sqnorm(const SqnormArgs &A, double *d_out, int accumulate, hipStream_t stream);
 
 // host side (gs_api.hip)

@@ -119,62 +119,7 @@ __device__ __forceinline__ float accumulate_one(const GradTable &gt, int k, int6
     return a;
 }
 
-// ---- fused accumulate + clip + AdamW + bf16 emit -----------------------------------------
-// One workgroup = one tile of GS_TILE consecutive elements (GS_BLOCK lanes x 4), one group of 4
-// per lane.  Tiles start at multiples of GS_TILE counted from element 0 of the arrays, not from
-// `begin`: the grouping does not move with the range (partition independence), and a wave's
-// 1 KB accesses stay line-aligned for any `begin` (a split point in the middle of a layer would
-// otherwise make every wave straddle two extra lines).
-template <int K>
-__global__ __launch_bounds__(GS_BLOCK) void k_accum_adamw(StepArgs A)
-{
-    const int k = (K > 0) ? K : A.k;     // K < 0: gradients come as one staged fp32 sum (A.acc)
-    const int64_t lo = (A.begin / GS_TILE + (int64_t)blockIdx.x) * GS_TILE + (int64_t)threadIdx.x * 4;
-    if (lo >= A.end || lo + 4 <= A.begin) return;
-    const float c = clip_coefficient(A.d_sqnorm, A.max_norm);
-    const StepConsts s = A.c;
-
-    if (lo >= A.begin && lo + 4 <= A.end) {
-        float a[4];
-        if constexpr (K < 0) {
-            f32x4 av = ld_stream(reinterpret_cast<const f32x4 *>(A.acc + lo));
-            a[0] = av.x; a[1] = av.y; a[2] = av.z; a[3] = av.w;
-        } else {
-            accumulate_group<K>(A.gt, k, lo, a);
-        }
-        f32x4 p = ld_stream(reinterpret_cast<const f32x4 *>(A.p + lo));
-        f32x4 m = ld_stream(reinterpret_cast<const f32x4 *>(A.m + lo));
-        f32x4 v = ld_stream(reinterpret_cast<const f32x4 *>(A.v + lo));
-        float P[4] = {p.x, p.y, p.z, p.w};
-        float M[4] = {m.x, m.y, m.z, m.w};
-        float V[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) adamw_element(a[e], c, s, P[e], M[e], V[e]);
-        st_stream(reinterpret_cast<f32x4 *>(A.p + lo), f32x4{P[0], P[1], P[2], P[3]});
-        st_stream(reinterpret_cast<f32x4 *>(A.m + lo), f32x4{M[0], M[1], M[2], M[3]});
-        st_stream(reinterpret_cast<f32x4 *>(A.v + lo), f32x4{V[0], V[1], V[2], V[3]});
-        u32x2 wv;
-        wv.x = f32_to_bf16_bits(P[0]) | (f32_to_bf16_bits(P[1]) << 16);
-        wv.y = f32_to_bf16_bits(P[2]) | (f32_to_bf16_bits(P[3]) << 16);
-        st_stream(reinterpret_cast<u32x2 *>(A.w + lo), wv);
-    } else {
-        // ragged head / tail of the range: same arithmetic, one element at a time
-        const int64_t i0 = lo > A.begin ? lo : A.begin;
-        const int64_t i1 = lo + 4 < A.end ? lo + 4 : A.end;
-        for (int64_t i = i0; i < i1; ++i) {
-            float a;
-            if constexpr (K < 0) a = A.acc[i]; else a = accumulate_one(A.gt, k, i);
-            float pi = A.p[i], mi = A.m[i], vi = A.v[i];
-            adamw_element(a, c, s, pi, mi, vi);
-            A.p[i] = pi;
-            A.m[i] = mi;
-            A.v[i] = vi;
-            A.w[i] = (uint16_t)f32_to_bf16_bits(pi);
-        }
-    }
-}
-
-// ---- squared norm of the accumulated gradient --------------------------------------------
+// ---- block reduction used by the norm kernels ----------------------------------------------
 // Per-lane fp64 partial (each square is exact in fp64) -> wave64 butterfly -> LDS across the
 // block's waves -> one partial per block; a second tiny kernel folds the block partials in a
 // fixed order, so the result is deterministic.
@@ -201,6 +146,101 @@ __device__ __forceinline__ double block_sum(double x, double *lds)
     return t;   // valid in thread 0
 }
 
+// ---- fused accumulate + clip + AdamW + bf16 emit -----------------------------------------
+// The group of 4 elements starting at `lo` (a multiple of 4): whole-group vector path when the
+// group lies inside [begin,end), per-element path for ragged range ends -- same arithmetic.
+// States are read from A.p/m/v and written to A.po/mo/vo (the same arrays for the in-place
+// entry points).  NORM: also add the squares of the accumulated gradients to acc0/acc1.
+template <int K, bool NORM>
+__device__ __forceinline__ void step_group(const StepArgs &A, int k, int64_t lo, float c, const StepConsts &s,
+                                           double &acc0, double &acc1)
+{
+    if (lo >= A.begin && lo + 4 <= A.end) {
+        float a[4];
+        if constexpr (K < 0) {
+            f32x4 av = ld_stream(reinterpret_cast<const f32x4 *>(A.acc + lo));
+            a[0] = av.x; a[1] = av.y; a[2] = av.z; a[3] = av.w;
+        } else {
+            accumulate_group<K>(A.gt, k, lo, a);
+        }
+        f32x4 p = ld_stream(reinterpret_cast<const f32x4 *>(A.p + lo));
+        f32x4 m = ld_stream(reinterpret_cast<const f32x4 *>(A.m + lo));
+        f32x4 v = ld_stream(reinterpret_cast<const f32x4 *>(A.v + lo));
+        float P[4] = {p.x, p.y, p.z, p.w};
+        float M[4] = {m.x, m.y, m.z, m.w};
+        float V[4] = {v.x, v.y, v.z, v.w};
+        if constexpr (NORM) {
+            acc0 = fma((double)a[0], (double)a[0], acc0);
+            acc1 = fma((double)a[1], (double)a[1], acc1);
+            acc0 = fma((double)a[2], (double)a[2], acc0);
+            acc1 = fma((double)a[3], (double)a[3], acc1);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) adamw_element(a[e], c, s, P[e], M[e], V[e]);
+        st_stream(reinterpret_cast<f32x4 *>(A.po + lo), f32x4{P[0], P[1], P[2], P[3]});
+        st_stream(reinterpret_cast<f32x4 *>(A.mo + lo), f32x4{M[0], M[1], M[2], M[3]});
+        st_stream(reinterpret_cast<f32x4 *>(A.vo + lo), f32x4{V[0], V[1], V[2], V[3]});
+        u32x2 wv;
+        wv.x = f32_to_bf16_bits(P[0]) | (f32_to_bf16_bits(P[1]) << 16);
+        wv.y = f32_to_bf16_bits(P[2]) | (f32_to_bf16_bits(P[3]) << 16);
+        st_stream(reinterpret_cast<u32x2 *>(A.w + lo), wv);
+    } else {
+        const int64_t i0 = lo > A.begin ? lo : A.begin;
+        const int64_t i1 = lo + 4 < A.end ? lo + 4 : A.end;
+        for (int64_t i = i0; i < i1; ++i) {
+            float a;
+            if constexpr (K < 0) a = A.acc[i]; else a = accumulate_one(A.gt, k, i);
+            if constexpr (NORM) acc0 = fma((double)a, (double)a, acc0);
+            float pi = A.p[i], mi = A.m[i], vi = A.v[i];
+            adamw_element(a, c, s, pi, mi, vi);
+            A.po[i] = pi;
+            A.mo[i] = mi;
+            A.vo[i] = vi;
+            A.w[i] = (uint16_t)f32_to_bf16_bits(pi);
+        }
+    }
+}
+
+// One workgroup = one tile of GS_TILE consecutive elements (GS_BLOCK lanes x 4), one group of 4
+// per lane.  Tiles start at multiples of GS_TILE counted from element 0 of the arrays, not from
+// `begin`: the grouping does not move with the range (partition independence), and a wave's
+// 1 KB accesses stay line-aligned for any `begin` (a split point in the middle of a layer would
+// otherwise make every wave straddle two extra lines).
+template <int K>
+__global__ __launch_bounds__(GS_BLOCK) void k_accum_adamw(StepArgs A)
+{
+    const int k = (K > 0) ? K : A.k;     // K < 0: gradients come as one staged fp32 sum (A.acc)
+    const int64_t lo = (A.begin / GS_TILE + (int64_t)blockIdx.x) * GS_TILE + (int64_t)threadIdx.x * 4;
+    if (lo >= A.end || lo + 4 <= A.begin) return;
+    const float c = clip_coefficient(A.d_sqnorm, A.max_norm);
+    double unused0 = 0.0, unused1 = 0.0;
+    step_group<K, false>(A, k, lo, c, A.c, unused0, unused1);
+}
+
+// Speculative single pass (Sec. 2.1 of the paper: prior work steps before the global norm is
+// known because clipping rarely changes the gradients): the step is applied with c = 1 and the
+// squared norm of the same accumulated gradients is reduced on the way, so the gradients are
+// read once.  Needs per-workgroup partials, hence the same 4096-element tiles / span logic as
+// the staged norm kernel.
+template <int K>
+__global__ __launch_bounds__(GS_STAGE_BLOCK) void k_accum_adamw_spec(StepArgs A, double *partials, int span)
+{
+    constexpr int TILE = GS_STAGE_BLOCK * 4;
+    __shared__ double lds[GS_STAGE_BLOCK / 64];
+    const int k = (K > 0) ? K : A.k;
+    const int64_t first = (A.begin / TILE + (int64_t)blockIdx.x * span) * TILE + (int64_t)threadIdx.x * 4;
+    double acc0 = 0.0, acc1 = 0.0;
+    for (int it = 0; it < span; ++it) {
+        const int64_t lo = first + (int64_t)it * TILE;
+        if (lo >= A.end) break;
+        if (lo + 4 <= A.begin) continue;
+        step_group<K, true>(A, k, lo, 1.0f, A.c, acc0, acc1);
+    }
+    double t = block_sum<GS_STAGE_BLOCK>(acc0 + acc1, lds);
+    if (threadIdx.x == 0) partials[blockIdx.x] = t;
+}
+
+// ---- squared norm of the accumulated gradient --------------------------------------------
 // Workgroup b reads `span` consecutive tiles starting at tile b*span (tiles counted from the
 // GS_TILE-aligned start of the range): a short contiguous run per workgroup is what the read
 // path likes best.
@@ -276,6 +316,29 @@ hipError_t launch_accum_adamw(const StepArgs &A, hipStream_t stream)
     case 16: k_accum_adamw<16><<<grid, GS_BLOCK, 0, stream>>>(A); break;
     default: k_accum_adamw<0><<<grid, GS_BLOCK, 0, stream>>>(A); break;
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_accum_adamw_spec(const StepArgs &A, double *partials, double *d_out, int accumulate, hipStream_t stream)
+{
+    int64_t tiles = tiles_of(A.begin, A.end, (int64_t)GS_STAGE_BLOCK * 4);
+    if (tiles < 1) tiles = 1;
+    int64_t span = 1;
+    if (tiles > GS_SQNORM_MAX_BLOCKS) span = (tiles + GS_SQNORM_MAX_BLOCKS - 1) / GS_SQNORM_MAX_BLOCKS;
+    if (span > 0x7fffffff) return hipErrorInvalidValue;
+    const int grid = (int)((tiles + span - 1) / span);
+    const int sp = (int)span;
+    switch (A.k) {
+    case 1: k_accum_adamw_spec<1><<<grid, GS_STAGE_BLOCK, 0, stream>>>(A, partials, sp); break;
+    case 2: k_accum_adamw_spec<2><<<grid, GS_STAGE_BLOCK, 0, stream>>>(A, partials, sp); break;
+    case 4: k_accum_adamw_spec<4><<<grid, GS_STAGE_BLOCK, 0, stream>>>(A, partials, sp); break;
+    case 8: k_accum_adamw_spec<8><<<grid, GS_STAGE_BLOCK, 0, stream>>>(A, partials, sp); break;
+    case 16: k_accum_adamw_spec<16><<<grid, GS_STAGE_BLOCK, 0, stream>>>(A, partials, sp); break;
+    default: k_accum_adamw_spec<0><<<grid, GS_STAGE_BLOCK, 0, stream>>>(A, partials, sp); break;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    k_sqnorm_finalize<<<1, GS_FINAL_BLOCK, 0, stream>>>(partials, grid, d_out, accumulate);
     return hipGetLastError();
 }
 

@@ -178,9 +178,12 @@ gs_status gs_stream_layer_step(gs_stream_ctx *c, float *h_p, float *h_m, float *
         // compute: base pointers chosen so that base[i] is element i of the layer
         GS_TRY(hipStreamWaitEvent(c->s_comp, c->ev_h2d[slot], 0), "hipStreamWaitEvent(h2d)");
         const intptr_t shift = (intptr_t)(pad - b) * (intptr_t)sizeof(float);
-        A.p = reinterpret_cast<float *>(reinterpret_cast<intptr_t>(sp) + shift);
-        A.m = reinterpret_cast<float *>(reinterpret_cast<intptr_t>(sm) + shift);
-        A.v = reinterpret_cast<float *>(reinterpret_cast<intptr_t>(sv) + shift);
+        A.po = reinterpret_cast<float *>(reinterpret_cast<intptr_t>(sp) + shift);
+        A.mo = reinterpret_cast<float *>(reinterpret_cast<intptr_t>(sm) + shift);
+        A.vo = reinterpret_cast<float *>(reinterpret_cast<intptr_t>(sv) + shift);
+        A.p = A.po;
+        A.m = A.mo;
+        A.v = A.vo;
         A.begin = b;
         A.end = e;
         hipError_t le = launch_accum_adamw(A, c->s_comp);

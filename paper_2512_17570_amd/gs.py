@@ -73,6 +73,13 @@ _lib.gs_grad_accum_sqnorm.argtypes = [_pp, ctypes.c_int, _i64, _i64, _vp, _vp, c
 _lib.gs_grad_accum_sqnorm.restype = ctypes.c_int
 _lib.gs_adamw_from_acc.argtypes = [_vp, _vp, _vp, _vp, _vp, _i64, _i64, ctypes.POINTER(gs_adamw_hparams), _vp, _vp]
 _lib.gs_adamw_from_acc.restype = ctypes.c_int
+_lib.gs_accum_adamw_oop.argtypes = [_vp] * 7 + [_pp, ctypes.c_int, _i64, _i64, ctypes.POINTER(gs_adamw_hparams), _vp, _vp]
+_lib.gs_accum_adamw_oop.restype = ctypes.c_int
+_lib.gs_accum_adamw_spec.argtypes = [_vp] * 7 + [_pp, ctypes.c_int, _i64, _i64, ctypes.POINTER(gs_adamw_hparams), _vp,
+                                     ctypes.c_int, _vp, ctypes.c_size_t, _vp]
+_lib.gs_accum_adamw_spec.restype = ctypes.c_int
+_lib.gs_clip_coefficient.argtypes = [ctypes.c_double, ctypes.c_float]
+_lib.gs_clip_coefficient.restype = ctypes.c_float
 _lib.gs_cu_stream_create.argtypes = [ctypes.POINTER(_vp), ctypes.c_int]
 _lib.gs_cu_stream_create.restype = ctypes.c_int
 _lib.gs_cu_stream_destroy.argtypes = [_vp]
@@ -208,6 +215,41 @@ def gs_adamw_from_acc(p, m, v, w_bf16, acc_f32, begin: int, end: int, hp, d_sqno
     st = _lib.gs_adamw_from_acc(_addr(p), _addr(m), _addr(v), _addr(w_bf16), _addr(acc_f32), begin, end,
                                 _hp(hp), _addr(d_sqnorm), _stream(stream))
     return _check(st, "gs_adamw_from_acc", check)
+
+
+def gs_accum_adamw_oop(p, m, v, p_out, m_out, v_out, w_bf16, grads, begin: int, end: int, hp, d_sqnorm=None,
+                       stream=None, check: bool = True, k: int | None = None) -> int:
+    tab, kk = _table(grads) if grads is not None else (None, 0)
+    for j, g in enumerate(grads or ()):
+        _need(g, end, 2, f"grads[{j}]")
+    for x, eb, nm in ((p, 4, "p"), (m, 4, "m"), (v, 4, "v"), (p_out, 4, "p_out"), (m_out, 4, "m_out"),
+                      (v_out, 4, "v_out"), (w_bf16, 2, "w_bf16")):
+        _need(x, end, eb, nm)
+    st = _lib.gs_accum_adamw_oop(_addr(p), _addr(m), _addr(v), _addr(p_out), _addr(m_out), _addr(v_out),
+                                 _addr(w_bf16), tab, kk if k is None else k, begin, end, _hp(hp), _addr(d_sqnorm),
+                                 _stream(stream))
+    return _check(st, "gs_accum_adamw_oop", check)
+
+
+def gs_accum_adamw_spec(p, m, v, p_out, m_out, v_out, w_bf16, grads, begin: int, end: int, hp, d_sqnorm,
+                        d_workspace, workspace_bytes: int | None = None, accumulate: bool = False, stream=None,
+                        check: bool = True, k: int | None = None) -> int:
+    tab, kk = _table(grads) if grads is not None else (None, 0)
+    for j, g in enumerate(grads or ()):
+        _need(g, end, 2, f"grads[{j}]")
+    for x, eb, nm in ((p, 4, "p"), (m, 4, "m"), (v, 4, "v"), (p_out, 4, "p_out"), (m_out, 4, "m_out"),
+                      (v_out, 4, "v_out"), (w_bf16, 2, "w_bf16")):
+        _need(x, end, eb, nm)
+    if workspace_bytes is None:
+        workspace_bytes = d_workspace.numel() * d_workspace.element_size() if hasattr(d_workspace, "numel") else 0
+    st = _lib.gs_accum_adamw_spec(_addr(p), _addr(m), _addr(v), _addr(p_out), _addr(m_out), _addr(v_out),
+                                  _addr(w_bf16), tab, kk if k is None else k, begin, end, _hp(hp), _addr(d_sqnorm),
+                                  int(bool(accumulate)), _addr(d_workspace), workspace_bytes, _stream(stream))
+    return _check(st, "gs_accum_adamw_spec", check)
+
+
+def gs_clip_coefficient(sqnorm_total: float, max_grad_norm: float) -> float:
+    return float(_lib.gs_clip_coefficient(float(sqnorm_total), float(max_grad_norm)))
 
 
 def gs_cu_stream_create(num_cus: int, check: bool = True):

@@ -27,7 +27,8 @@ def test_header_symbols_all_exported():
     assert {"gs_grad_sqnorm", "gs_accum_adamw", "gs_stream_layer_step", "gs_sqnorm_workspace_bytes",
             "gs_stream_ctx_create", "gs_stream_ctx_destroy", "gs_stream_ctx_sync", "gs_pinned_alloc",
             "gs_pinned_free", "gs_strerror", "gs_last_hip_error", "gs_grad_accum_sqnorm", "gs_adamw_from_acc",
-            "gs_cu_stream_create", "gs_cu_stream_destroy"} <= set(names)
+            "gs_cu_stream_create", "gs_cu_stream_destroy", "gs_accum_adamw_oop", "gs_accum_adamw_spec",
+            "gs_clip_coefficient"} <= set(names)
     lib = ctypes.CDLL(gs.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in gs.h but not exported"
@@ -138,6 +139,32 @@ def test_staged_variant_rejects_without_gpu():
                dict(begin=-1), dict(d_sqnorm=FAKE + 4)):
         assert gs.gs_adamw_from_acc(**{**ok2, **kw}) == gs.GS_ERR_INVALID_ARG
     assert gs.gs_adamw_from_acc(**{**ok2, "begin": 7, "end": 7}) == gs.GS_OK
+
+
+def test_speculative_and_oop_reject_without_gpu():
+    ws = gs.gs_sqnorm_workspace_bytes()
+    F2 = FAKE + (1 << 20)
+    oop = dict(p=FAKE, m=FAKE, v=FAKE, p_out=F2, m_out=F2, v_out=F2, w_bf16=FAKE, grads=[FAKE], begin=0, end=64,
+               hp=GOOD_HP, d_sqnorm=None, stream=0, check=False)
+    assert gs.gs_accum_adamw_oop(**{**oop, "begin": 4, "end": 4}) == gs.GS_OK
+    for kw in (dict(p_out=None), dict(m_out=FAKE + 4), dict(p_out=FAKE + 64),       # partial overlap with p
+               dict(v_out=FAKE - 128), dict(grads=[FAKE] * 33), dict(hp=None), dict(begin=5, end=1)):
+        assert gs.gs_accum_adamw_oop(**{**oop, **kw}) == gs.GS_ERR_INVALID_ARG, kw
+    assert gs.gs_accum_adamw_oop(**{**oop, "p_out": FAKE, "m_out": FAKE, "v_out": FAKE, "begin": 9, "end": 9}) == gs.GS_OK
+    spec = dict(p=FAKE, m=FAKE, v=FAKE, p_out=F2, m_out=F2, v_out=F2, w_bf16=FAKE, grads=[FAKE], begin=0, end=64,
+                hp=GOOD_HP, d_sqnorm=FAKE, d_workspace=FAKE, workspace_bytes=ws, stream=0, check=False)
+    for kw, want in ((dict(d_sqnorm=None), gs.GS_ERR_INVALID_ARG), (dict(d_sqnorm=FAKE + 4), gs.GS_ERR_INVALID_ARG),
+                     (dict(d_workspace=None), gs.GS_ERR_WORKSPACE), (dict(workspace_bytes=64), gs.GS_ERR_WORKSPACE),
+                     (dict(p_out=FAKE + 16), gs.GS_ERR_INVALID_ARG), (dict(v=None), gs.GS_ERR_INVALID_ARG)):
+        assert gs.gs_accum_adamw_spec(**{**spec, **kw}) == want, kw
+    assert gs.gs_accum_adamw_spec(**{**spec, "begin": 3, "end": 3, "accumulate": True}) == gs.GS_OK
+
+
+def test_host_clip_coefficient_matches_oracle():
+    from oracle import gs_oracle as O
+    for S, mx in ((0.0, 1.0), (0.25, 1.0), (1.0, 1.0), (4.0, 1.0), (3221.8, 1.0), (1e12, 0.5), (7.0, 0.0), (7.0, -1.0),
+                  (float("inf"), 1.0), (float("nan"), 1.0), (1e-30, 1e-3), (0.99999, 1.0), (1.00001, 1.0)):
+        assert gs.gs_clip_coefficient(S, mx) == O.clip_coef(S, mx), (S, mx)
 
 
 def test_cu_stream_rejects_without_gpu():

@@ -410,3 +410,64 @@ def test_cu_budget_stream_gives_same_result():
             assert torch.equal(a, b)
     finally:
         gs.gs_cu_stream_destroy(raw)
+
+
+# ----------------------------------------------------------------------------- speculative / out-of-place
+@pytest.mark.parametrize("k", [1, 4, 16, 19])
+def test_speculative_step_matches_oracle_and_redo_path(k):
+    n = 4096 * 70 + 4099
+    case = DeviceCase(n, k, seed=140 + k)
+    S_ref = case.gpu_sqnorm()
+    So = O.grad_sqnorm(case.h_g)
+    po, mo, vo = (torch.full_like(case.p, float("nan")) for _ in range(3))
+    w = torch.zeros_like(case.w)
+    sq = torch.zeros(1, dtype=torch.float64, device=DEV)
+    p0, m0, v0 = case.p.clone(), case.m.clone(), case.v.clone()
+    gs.gs_accum_adamw_spec(case.p, case.m, case.v, po, mo, vo, w, case.grads, 0, n, HP, sq, case.ws)
+    torch.cuda.synchronize()
+    S = float(sq.item())
+    assert abs(S - So) <= 1e-5 * So and abs(S - S_ref) <= 1e-13 * S_ref
+    for a, b in ((case.p, p0), (case.m, m0), (case.v, v0)):
+        assert torch.equal(a, b)                           # inputs untouched
+    compare_states((po, mo, vo, w), case.oracle_step(HP, 1.0), f"spec k={k}")     # c = 1 by construction
+    assert_w_is_rne_of_p(po, w, 0, n)
+    # the guess was wrong here (||g|| > max_norm): redo out of place with the finished norm
+    c = gs.gs_clip_coefficient(S, HP.max_grad_norm)
+    assert c == O.clip_coef(So, HP.max_grad_norm) or abs(c - O.clip_coef(So, HP.max_grad_norm)) < 1e-7
+    if c < 1.0:
+        gs.gs_accum_adamw_oop(case.p, case.m, case.v, po, mo, vo, w, case.grads, 0, n, HP, sq)
+        torch.cuda.synchronize()
+        inplace = run_gpu_step(case, HP)                   # uses case.sq (same squares, other tree)
+        compare_states((po, mo, vo, w), case.oracle_step(HP, O.clip_coef(So, HP.max_grad_norm)), f"redo k={k}")
+        for a, b in zip(inplace, (po, mo, vo, w)):
+            assert_f32_close(np_f32(a), np_f32(b), "oop vs in-place") if a.dtype == torch.float32 else None
+
+
+def test_speculative_accepts_when_norm_is_small_and_ranges_accumulate():
+    n = 4096 * 33 + 5
+    case = DeviceCase(n, 4, seed=150, sigma=1e-5)
+    po, mo, vo = case.p.clone(), case.m.clone(), case.v.clone()
+    w = torch.zeros_like(case.w)
+    sq = torch.zeros(1, dtype=torch.float64, device=DEV)
+    cuts = [0, 1, 4097, n // 2 + 3, n]
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        gs.gs_accum_adamw_spec(case.p, case.m, case.v, po, mo, vo, w, case.grads, a, b, HP, sq, case.ws, accumulate=(a > 0))
+    torch.cuda.synchronize()
+    S = float(sq.item())
+    assert abs(S - O.grad_sqnorm(case.h_g)) <= 1e-12 * S
+    assert gs.gs_clip_coefficient(S, HP.max_grad_norm) == 1.0           # speculation holds: outputs are final
+    full = run_gpu_step(case, HP, use_norm=False)
+    for x, y in zip(full, (po, mo, vo, w)):
+        assert torch.equal(x, y)
+
+
+def test_oop_in_place_alias_equals_in_place_entry():
+    n = 2048 * 21 + 1
+    case = DeviceCase(n, 2, seed=160)
+    case.gpu_sqnorm()
+    a = run_gpu_step(case, HP)
+    p, m, v, w = case.clone_states()
+    gs.gs_accum_adamw_oop(p, m, v, p, m, v, w, case.grads, 0, n, HP, case.sq)
+    torch.cuda.synchronize()
+    for x, y in zip(a, (p, m, v, w)):
+        assert torch.equal(x, y)
