@@ -7,8 +7,9 @@
 
 #include "gs.h"
 
-#define GS_BLOCK 256                  // threads per workgroup (4 wave64)
-#define GS_TILE (GS_BLOCK * 4)        // elements per workgroup tile: one group of 4 per lane
+#define GS_STEP_BLOCK 128             // threads per workgroup of the step kernels (2 wave64)
+#define GS_BLOCK 256                  // threads per workgroup of the norm kernel (4 wave64)
+#define GS_TILE (GS_BLOCK * 4)        // elements per norm tile: one group of 4 per lane
 #define GS_FINAL_BLOCK 1024           // threads of the partial-folding kernel
 #define GS_STAGE_BLOCK 1024           // threads per workgroup of the staged norm kernel
 #define GS_SQNORM_MAX_BLOCKS 262144   // upper bound on block partials => workspace size (2 MB)

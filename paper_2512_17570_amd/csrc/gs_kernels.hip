@@ -89,12 +89,15 @@ __device__ __forceinline__ void adamw_element(float a, float c, const StepConsts
 
 // k-way accumulation of one 4-element group, j ascending from +0 (Sec. 2.1: micro-batch
 // gradients are accumulated in full precision).  K > 0: compile-time count; K == 0: runtime.
-template <int K>
+// WIDE: all loads of a group in flight at once (compile-time K) or four and two at a time
+// (runtime k) -- what the read-only norm kernels want; the step kernels, which mix 19 read with 4
+// write streams, do better with one gradient load in flight per wave.
+template <int K, bool WIDE = false>
 __device__ __forceinline__ void accumulate_group(const GradTable &gt, int k, int64_t lo, float (&a)[4])
 {
 #pragma unroll
     for (int e = 0; e < 4; ++e) a[e] = 0.0f;
-    if constexpr (K > 0) {
+    if constexpr (K > 0 && WIDE) {
         u32x2 gv[K];
 #pragma unroll
         for (int j = 0; j < K; ++j) gv[j] = ld_stream(reinterpret_cast<const u32x2 *>(gt.g[j] + lo));
@@ -103,8 +106,40 @@ __device__ __forceinline__ void accumulate_group(const GradTable &gt, int k, int
             a[0] += bf16_lo(gv[j].x); a[1] += bf16_hi(gv[j].x);
             a[2] += bf16_lo(gv[j].y); a[3] += bf16_hi(gv[j].y);
         }
+    } else if constexpr (K > 0) {
+        // one gradient load in flight per wave: each load is consumed before the next is issued.
+        // With 19 read and 4 write streams, keeping the memory queues shallow is worth ~5 % on
+        // MI355X over issuing all K loads at once (the runtime-k loop below behaves the same way).
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+            u32x2 gv = ld_stream(reinterpret_cast<const u32x2 *>(gt.g[j] + lo));
+            a[0] += bf16_lo(gv.x); a[1] += bf16_hi(gv.x);
+            a[2] += bf16_lo(gv.y); a[3] += bf16_hi(gv.y);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     } else {
-        for (int j = 0; j < k; ++j) {
+        // runtime k; the adds stay in ascending order of j
+        int j = 0;
+        if constexpr (WIDE) {
+            for (; j + 4 <= k; j += 4) {
+                u32x2 gv[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) gv[q] = ld_stream(reinterpret_cast<const u32x2 *>(gt.g[j + q] + lo));
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    a[0] += bf16_lo(gv[q].x); a[1] += bf16_hi(gv[q].x);
+                    a[2] += bf16_lo(gv[q].y); a[3] += bf16_hi(gv[q].y);
+                }
+            }
+            if (j + 2 <= k) {
+                u32x2 g0 = ld_stream(reinterpret_cast<const u32x2 *>(gt.g[j] + lo));
+                u32x2 g1 = ld_stream(reinterpret_cast<const u32x2 *>(gt.g[j + 1] + lo));
+                a[0] += bf16_lo(g0.x); a[1] += bf16_hi(g0.x); a[2] += bf16_lo(g0.y); a[3] += bf16_hi(g0.y);
+                a[0] += bf16_lo(g1.x); a[1] += bf16_hi(g1.x); a[2] += bf16_lo(g1.y); a[3] += bf16_hi(g1.y);
+                j += 2;
+            }
+        }
+        for (; j < k; ++j) {
             u32x2 gv = ld_stream(reinterpret_cast<const u32x2 *>(gt.g[j] + lo));
             a[0] += bf16_lo(gv.x); a[1] += bf16_hi(gv.x);
             a[2] += bf16_lo(gv.y); a[3] += bf16_hi(gv.y);
@@ -151,21 +186,22 @@ __device__ __forceinline__ double block_sum(double x, double *lds)
 // group lies inside [begin,end), per-element path for ragged range ends -- same arithmetic.
 // States are read from A.p/m/v and written to A.po/mo/vo (the same arrays for the in-place
 // entry points).  NORM: also add the squares of the accumulated gradients to acc0/acc1.
-template <int K, bool NORM>
+template <int K, bool NORM, bool WIDE = false>
 __device__ __forceinline__ void step_group(const StepArgs &A, int k, int64_t lo, float c, const StepConsts &s,
                                            double &acc0, double &acc1)
 {
     if (lo >= A.begin && lo + 4 <= A.end) {
+        // state loads go first and stay in flight while the gradient loads are walked one by one
+        f32x4 p = ld_stream(reinterpret_cast<const f32x4 *>(A.p + lo));
+        f32x4 m = ld_stream(reinterpret_cast<const f32x4 *>(A.m + lo));
+        f32x4 v = ld_stream(reinterpret_cast<const f32x4 *>(A.v + lo));
         float a[4];
         if constexpr (K < 0) {
             f32x4 av = ld_stream(reinterpret_cast<const f32x4 *>(A.acc + lo));
             a[0] = av.x; a[1] = av.y; a[2] = av.z; a[3] = av.w;
         } else {
-            accumulate_group<K>(A.gt, k, lo, a);
+            accumulate_group<K, WIDE>(A.gt, k, lo, a);
         }
-        f32x4 p = ld_stream(reinterpret_cast<const f32x4 *>(A.p + lo));
-        f32x4 m = ld_stream(reinterpret_cast<const f32x4 *>(A.m + lo));
-        f32x4 v = ld_stream(reinterpret_cast<const f32x4 *>(A.v + lo));
         float P[4] = {p.x, p.y, p.z, p.w};
         float M[4] = {m.x, m.y, m.z, m.w};
         float V[4] = {v.x, v.y, v.z, v.w};
@@ -201,16 +237,17 @@ __device__ __forceinline__ void step_group(const StepArgs &A, int k, int64_t lo,
     }
 }
 
-// One workgroup = one tile of GS_TILE consecutive elements (GS_BLOCK lanes x 4), one group of 4
-// per lane.  Tiles start at multiples of GS_TILE counted from element 0 of the arrays, not from
+// One workgroup = one tile of 512 consecutive elements (GS_STEP_BLOCK = 128 lanes x 4), one group of
+// 4 per lane.  Tiles start at multiples of the tile size counted from element 0 of the arrays, not from
 // `begin`: the grouping does not move with the range (partition independence), and a wave's
 // 1 KB accesses stay line-aligned for any `begin` (a split point in the middle of a layer would
 // otherwise make every wave straddle two extra lines).
 template <int K>
-__global__ __launch_bounds__(GS_BLOCK) void k_accum_adamw(StepArgs A)
+__global__ __launch_bounds__(GS_STEP_BLOCK) void k_accum_adamw(StepArgs A)
 {
+    constexpr int TILE = GS_STEP_BLOCK * 4;
     const int k = (K > 0) ? K : A.k;     // K < 0: gradients come as one staged fp32 sum (A.acc)
-    const int64_t lo = (A.begin / GS_TILE + (int64_t)blockIdx.x) * GS_TILE + (int64_t)threadIdx.x * 4;
+    const int64_t lo = (A.begin / TILE + (int64_t)blockIdx.x) * TILE + (int64_t)threadIdx.x * 4;
     if (lo >= A.end || lo + 4 <= A.begin) return;
     const float c = clip_coefficient(A.d_sqnorm, A.max_norm);
     double unused0 = 0.0, unused1 = 0.0;
@@ -234,7 +271,7 @@ __global__ __launch_bounds__(GS_STAGE_BLOCK) void k_accum_adamw_spec(StepArgs A,
         const int64_t lo = first + (int64_t)it * TILE;
         if (lo >= A.end) break;
         if (lo + 4 <= A.begin) continue;
-        step_group<K, true>(A, k, lo, 1.0f, A.c, acc0, acc1);
+        step_group<K, true, true>(A, k, lo, 1.0f, A.c, acc0, acc1);   // 1024-lane workgroups: all loads in flight
     }
     double t = block_sum<GS_STAGE_BLOCK>(acc0 + acc1, lds);
     if (threadIdx.x == 0) partials[blockIdx.x] = t;
@@ -263,7 +300,7 @@ __global__ __launch_bounds__(BLOCK) void k_grad_sqnorm(SqnormArgs A, int span)
         if (lo + 4 <= A.begin) continue;
         if (lo >= A.begin && lo + 4 <= A.end) {
             float a[4];
-            accumulate_group<K>(A.gt, k, lo, a);
+            accumulate_group<K, true>(A.gt, k, lo, a);
             if constexpr (STAGE) st_stream(reinterpret_cast<f32x4 *>(A.acc + lo), f32x4{a[0], a[1], a[2], a[3]});
             acc0 = fma((double)a[0], (double)a[0], acc0);
             acc1 = fma((double)a[1], (double)a[1], acc1);
@@ -301,20 +338,20 @@ static int64_t tiles_of(int64_t begin, int64_t end, int64_t tile = GS_TILE)
 
 hipError_t launch_accum_adamw(const StepArgs &A, hipStream_t stream)
 {
-    const int64_t tiles = tiles_of(A.begin, A.end);
+    const int64_t tiles = tiles_of(A.begin, A.end, (int64_t)GS_STEP_BLOCK * 4);
     if (tiles < 1 || tiles > 0x7fffffff) return hipErrorInvalidValue;
     const int grid = (int)tiles;
     if (A.acc) {
-        k_accum_adamw<-1><<<grid, GS_BLOCK, 0, stream>>>(A);
+        k_accum_adamw<-1><<<grid, GS_STEP_BLOCK, 0, stream>>>(A);
         return hipGetLastError();
     }
     switch (A.k) {
-    case 1: k_accum_adamw<1><<<grid, GS_BLOCK, 0, stream>>>(A); break;
-    case 2: k_accum_adamw<2><<<grid, GS_BLOCK, 0, stream>>>(A); break;
-    case 4: k_accum_adamw<4><<<grid, GS_BLOCK, 0, stream>>>(A); break;
-    case 8: k_accum_adamw<8><<<grid, GS_BLOCK, 0, stream>>>(A); break;
-    case 16: k_accum_adamw<16><<<grid, GS_BLOCK, 0, stream>>>(A); break;
-    default: k_accum_adamw<0><<<grid, GS_BLOCK, 0, stream>>>(A); break;
+    case 1: k_accum_adamw<1><<<grid, GS_STEP_BLOCK, 0, stream>>>(A); break;
+    case 2: k_accum_adamw<2><<<grid, GS_STEP_BLOCK, 0, stream>>>(A); break;
+    case 4: k_accum_adamw<4><<<grid, GS_STEP_BLOCK, 0, stream>>>(A); break;
+    case 8: k_accum_adamw<8><<<grid, GS_STEP_BLOCK, 0, stream>>>(A); break;
+    case 16: k_accum_adamw<16><<<grid, GS_STEP_BLOCK, 0, stream>>>(A); break;
+    default: k_accum_adamw<0><<<grid, GS_STEP_BLOCK, 0, stream>>>(A); break;
     }
     return hipGetLastError();
 }
