@@ -68,7 +68,7 @@ using namespace gs;
 
 extern "C" {
 
-size_t gs_sqnorm_workspace_bytes(void) { return (size_t)GS_SQNORM_MAX_BLOCKS * sizeof(double); }
+size_t gs_sqnorm_workspace_bytes(void) { return (size_t)(GS_SQNORM_MAX_BLOCKS + GS_FINAL_SLICES) * sizeof(double); }
 
 static gs_status sqnorm_impl(const uint16_t *const *grads, int k, int64_t begin, int64_t end, float *acc,
                              double *d_sqnorm, int accumulate, void *d_workspace, size_t workspace_bytes,

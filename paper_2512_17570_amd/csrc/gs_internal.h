@@ -10,7 +10,9 @@
 #define GS_STEP_BLOCK 128             // threads per workgroup of the step kernels (2 wave64)
 #define GS_BLOCK 256                  // threads per workgroup of the norm kernel (4 wave64)
 #define GS_TILE (GS_BLOCK * 4)        // elements per norm tile: one group of 4 per lane
-#define GS_FINAL_BLOCK 1024           // threads of the partial-folding kernel
+#define GS_FINAL_BLOCK 1024           // threads of the partial-folding kernels
+#define GS_FINAL_SLICES 128           // workgroups of the first folding stage for large partial counts
+#define GS_FINAL_DIRECT_MAX 8192      // up to this many partials are folded by one workgroup directly
 #define GS_STAGE_BLOCK 1024           // threads per workgroup of the staged norm kernel
 #define GS_SQNORM_MAX_BLOCKS 262144   // upper bound on block partials => workspace size (2 MB)
 #define GS_NORM_SPAN 8                // consecutive tiles per norm workgroup (grows for huge ranges)

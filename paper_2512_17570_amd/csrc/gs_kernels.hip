@@ -340,6 +340,21 @@ __global__ __launch_bounds__(BLOCK) void k_grad_sqnorm(SqnormArgs A, int span)
     if (threadIdx.x == 0) A.partials[blockIdx.x] = t;
 }
 
+// Folding the workgroup partials, in a fixed order (deterministic).  Up to 262144 partials are too
+// many for one workgroup to read quickly, so large counts go through GS_FINAL_SLICES workgroups
+// that each fold a contiguous slice into the tail of the workspace, then one workgroup folds those.
+__global__ __launch_bounds__(GS_FINAL_BLOCK) void k_sqnorm_fold_slices(const double *partials, int nparts, double *slices)
+{
+    __shared__ double lds[GS_FINAL_BLOCK / 64];
+    const int per = (nparts + GS_FINAL_SLICES - 1) / GS_FINAL_SLICES;
+    const int lo = blockIdx.x * per;
+    const int hi = lo + per < nparts ? lo + per : nparts;
+    double x = 0.0;
+    for (int i = lo + threadIdx.x; i < hi; i += GS_FINAL_BLOCK) x += partials[i];
+    double t = block_sum<GS_FINAL_BLOCK>(x, lds);
+    if (threadIdx.x == 0) slices[blockIdx.x] = t;
+}
+
 __global__ __launch_bounds__(GS_FINAL_BLOCK) void k_sqnorm_finalize(const double *partials, int nparts, double *out, int accumulate)
 {
     __shared__ double lds[GS_FINAL_BLOCK / 64];
@@ -347,6 +362,20 @@ __global__ __launch_bounds__(GS_FINAL_BLOCK) void k_sqnorm_finalize(const double
     for (int i = threadIdx.x; i < nparts; i += GS_FINAL_BLOCK) x += partials[i];
     double t = block_sum<GS_FINAL_BLOCK>(x, lds);
     if (threadIdx.x == 0) *out = accumulate ? (*out + t) : t;
+}
+
+static hipError_t launch_fold(double *partials, int nparts, double *d_out, int accumulate, hipStream_t stream)
+{
+    if (nparts > GS_FINAL_DIRECT_MAX) {
+        double *slices = partials + GS_SQNORM_MAX_BLOCKS;
+        k_sqnorm_fold_slices<<<GS_FINAL_SLICES, GS_FINAL_BLOCK, 0, stream>>>(partials, nparts, slices);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        k_sqnorm_finalize<<<1, GS_FINAL_BLOCK, 0, stream>>>(slices, GS_FINAL_SLICES, d_out, accumulate);
+    } else {
+        k_sqnorm_finalize<<<1, GS_FINAL_BLOCK, 0, stream>>>(partials, nparts, d_out, accumulate);
+    }
+    return hipGetLastError();
 }
 
 // ---- launchers -----------------------------------------------------------------------------
@@ -395,8 +424,7 @@ hipError_t launch_accum_adamw_spec(const StepArgs &A, double *partials, double *
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    k_sqnorm_finalize<<<1, GS_FINAL_BLOCK, 0, stream>>>(partials, grid, d_out, accumulate);
-    return hipGetLastError();
+    return launch_fold(partials, grid, d_out, accumulate, stream);
 }
 
 hipError_t launch_grad_sqnorm(const SqnormArgs &A, double *d_out, int accumulate, hipStream_t stream)
@@ -425,8 +453,7 @@ hipError_t launch_grad_sqnorm(const SqnormArgs &A, double *d_out, int accumulate
 #undef GS_NORM_CASE
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    k_sqnorm_finalize<<<1, GS_FINAL_BLOCK, 0, stream>>>(A.partials, grid, d_out, accumulate);
-    return hipGetLastError();
+    return launch_fold(A.partials, grid, d_out, accumulate, stream);
 }
 
 }  // namespace gs
