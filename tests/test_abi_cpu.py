@@ -179,3 +179,18 @@ def test_error_raises_through_binding():
     with pytest.raises(gs.GsError) as ei:
         _adamw(begin=3, end=2, check=True)
     assert ei.value.status == gs.GS_ERR_INVALID_ARG
+
+
+def test_header_is_plain_c_and_cxx(tmp_path):
+    """include/gs.h must be usable from a C99 translation unit (and from C++) on its own."""
+    import subprocess
+    c = tmp_path / "use_gs.c"
+    c.write_text('#include "gs.h"\n'
+                 'int probe(void) { gs_adamw_hparams hp = {1e-4f, 0.9f, 0.999f, 1e-8f, 0.01f, 1.0f, 1};\n'
+                 '  const char *(*f)(gs_status) = gs_strerror; (void)f;\n'
+                 '  return (int)sizeof(hp) + (int)GS_MAX_K + (int)GS_ERR_NOMEM; }\n')
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", inc, "-fsyntax-only", str(c)], check=True)
+    cxx = tmp_path / "use_gs.cpp"
+    cxx.write_text(c.read_text())
+    subprocess.run(["g++", "-std=c++17", "-Wall", "-Wextra", "-Werror", "-I", inc, "-fsyntax-only", str(cxx)], check=True)

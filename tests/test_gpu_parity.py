@@ -471,3 +471,35 @@ def test_oop_in_place_alias_equals_in_place_entry():
     torch.cuda.synchronize()
     for x, y in zip(a, (p, m, v, w)):
         assert torch.equal(x, y)
+
+
+# ----------------------------------------------------------------------------- HIP graph capture
+def test_norm_and_step_replay_from_a_hip_graph():
+    """The entry points only enqueue kernels (no allocation, no memset, no host sync), so a
+    norm + step pair can be captured once and replayed; every replay must equal the eager run."""
+    n = 2048 * 150 + 9
+    case = DeviceCase(n, 8, seed=170)
+    p, m, v, w = case.clone_states()
+    gs.gs_grad_sqnorm(case.grads, 0, n, case.sq, case.ws)           # warm up outside capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        gs.gs_grad_sqnorm(case.grads, 0, n, case.sq, case.ws)
+        gs.gs_accum_adamw(p, m, v, w, case.grads, 0, n, HP, case.sq)
+    torch.cuda.synchronize()
+    eager = case.clone_states()
+    for it in range(3):
+        g.replay()
+        torch.cuda.synchronize()
+        gs.gs_grad_sqnorm(case.grads, 0, n, case.sq, case.ws)       # eager work between replays
+        gs.gs_accum_adamw(*eager, case.grads, 0, n, HP, case.sq)
+        torch.cuda.synchronize()
+        for a, b in zip((p, m, v, w), eager):
+            assert torch.equal(a, b), f"replay {it}"
+    ora = case.oracle_step(HP, O.clip_coef(O.grad_sqnorm(case.h_g), HP.max_grad_norm))
+    # first replay == one oracle step from the original states
+    case2 = DeviceCase(n, 8, seed=170)
+    st = case2.clone_states()
+    case2.gpu_sqnorm()
+    run_gpu_step(case2, HP, states=st)
+    compare_states(st, ora, "graph reference")
