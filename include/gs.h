@@ -79,8 +79,16 @@ typedef struct {
  * optimizer waits for it).
  * ------------------------------------------------------------------------------------------ */
 
-/* Bytes of device workspace gs_grad_sqnorm needs; a constant independent of n and k. */
+/* Bytes of device workspace the norm-reducing calls need at least; a constant independent of n
+ * and k (about 2 MB). */
 size_t gs_sqnorm_workspace_bytes(void);
+
+/* Workspace size with which gs_grad_accum_sqnorm and gs_accum_adamw_spec run in their fastest
+ * shape on a range of `range_elems` elements (one partial per 512-element tile: about
+ * range_elems/64 bytes; never less than gs_sqnorm_workspace_bytes()).  Those two calls accept any
+ * workspace of at least the minimum size and pick the shape that fits; results do not depend on
+ * it beyond fp64 summation order.  gs_grad_sqnorm itself gains nothing from a larger workspace. */
+size_t gs_sqnorm_workspace_bytes_for(int64_t range_elems);
 
 /*
  * S = sum over i in [begin,end) of a_i^2, where a_i = sum_{j<k} float(grads[j][i]) is the

@@ -70,6 +70,15 @@ extern "C" {
 
 size_t gs_sqnorm_workspace_bytes(void) { return (size_t)(GS_SQNORM_MAX_BLOCKS + GS_FINAL_SLICES) * sizeof(double); }
 
+size_t gs_sqnorm_workspace_bytes_for(int64_t range_elems)
+{
+    const size_t base = gs_sqnorm_workspace_bytes();
+    if (range_elems <= 0) return base;
+    // one partial per 512-element tile (+2 for ragged ends) and the folding slices
+    const size_t want = ((size_t)(range_elems / (GS_STEP_BLOCK * 4)) + 2 + GS_FINAL_SLICES) * sizeof(double);
+    return want > base ? want : base;
+}
+
 static gs_status sqnorm_impl(const uint16_t *const *grads, int k, int64_t begin, int64_t end, float *acc,
                              double *d_sqnorm, int accumulate, void *d_workspace, size_t workspace_bytes,
                              void *stream)
@@ -90,7 +99,7 @@ static gs_status sqnorm_impl(const uint16_t *const *grads, int k, int64_t begin,
     A.end = end;
     A.partials = static_cast<double *>(d_workspace);
     A.acc = acc;
-    hipError_t e = launch_grad_sqnorm(A, d_sqnorm, accumulate, static_cast<hipStream_t>(stream));
+    hipError_t e = launch_grad_sqnorm(A, workspace_bytes, d_sqnorm, accumulate, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e, "gs_grad_sqnorm launch");
     return GS_OK;
 }
@@ -176,7 +185,7 @@ static gs_status adamw_impl(const float *p, const float *m, const float *v, floa
     A.d_sqnorm = d_sqnorm;
     hipError_t e;
     if (spec_norm_out)
-        e = launch_accum_adamw_spec(A, static_cast<double *>(d_workspace), spec_norm_out, accumulate,
+        e = launch_accum_adamw_spec(A, static_cast<double *>(d_workspace), workspace_bytes, spec_norm_out, accumulate,
                                     static_cast<hipStream_t>(stream));
     else
         e = launch_accum_adamw(A, static_cast<hipStream_t>(stream));

@@ -50,8 +50,10 @@ struct SqnormArgs {
 };
 
 hipError_t launch_accum_adamw(const StepArgs &A, hipStream_t stream);
-hipError_t launch_accum_adamw_spec(const StepArgs &A, double *partials, double *d_out, int accumulate, hipStream_t stream);
-hipError_t launch_grad_sqnorm(const SqnormArgs &A, double *d_out, int accumulate, hipStream_t stream);
+hipError_t launch_accum_adamw_spec(const StepArgs &A, double *partials, size_t workspace_bytes, double *d_out,
+                                   int accumulate, hipStream_t stream);
+hipError_t launch_grad_sqnorm(const SqnormArgs &A, size_t workspace_bytes, double *d_out, int accumulate,
+                              hipStream_t stream);
 
 // host side (gs_api.hip)
 gs_status validate_hparams(const gs_adamw_hparams *hp);

@@ -96,61 +96,64 @@ __device__ __forceinline__ void adamw_element(float a, float c, const StepConsts
 
 // k-way accumulation of one 4-element group, j ascending from +0 (Sec. 2.1: micro-batch
 // gradients are accumulated in full precision).  K > 0: compile-time count; K == 0: runtime.
-// WIDE: all loads of a group in flight at once (compile-time K) or four and two at a time
-// (runtime k) -- what the read-only norm kernels want; the step kernels, which mix 19 read with 4
-// write streams, do better with one gradient load in flight per wave.
-template <int K, bool WIDE = false>
+// DEPTH is how many gradient loads a wave keeps in flight:
+//   0  all of them (compile-time K) or four and two at a time (runtime k) -- what the read-only
+//      norm kernel wants;
+//   1  one: each load is consumed before the next is issued -- the kernels that mix many read
+//      streams with the four write streams of a step do best with shallow memory queues;
+//   2  two at a time -- the optimum measured for the staged norm kernel (k reads + one write).
+__device__ __forceinline__ void add_pair(float (&a)[4], u32x2 g)
+{
+    a[0] += bf16_lo(g.x); a[1] += bf16_hi(g.x);
+    a[2] += bf16_lo(g.y); a[3] += bf16_hi(g.y);
+}
+
+template <int K, int DEPTH>
 __device__ __forceinline__ void accumulate_group(const GradTable &gt, int k, int64_t lo, float (&a)[4])
 {
 #pragma unroll
     for (int e = 0; e < 4; ++e) a[e] = 0.0f;
-    if constexpr (K > 0 && WIDE) {
+    if constexpr (K > 0 && DEPTH == 0) {
         u32x2 gv[K];
 #pragma unroll
         for (int j = 0; j < K; ++j) gv[j] = ld_stream(reinterpret_cast<const u32x2 *>(gt.g[j] + lo));
 #pragma unroll
-        for (int j = 0; j < K; ++j) {
-            a[0] += bf16_lo(gv[j].x); a[1] += bf16_hi(gv[j].x);
-            a[2] += bf16_lo(gv[j].y); a[3] += bf16_hi(gv[j].y);
-        }
+        for (int j = 0; j < K; ++j) add_pair(a, gv[j]);
     } else if constexpr (K > 0) {
-        // one gradient load in flight per wave: each load is consumed before the next is issued.
-        // With 19 read and 4 write streams, keeping the memory queues shallow is worth ~5 % on
-        // MI355X over issuing all K loads at once (the runtime-k loop below behaves the same way).
 #pragma unroll
-        for (int j = 0; j < K; ++j) {
-            u32x2 gv = ld_stream(reinterpret_cast<const u32x2 *>(gt.g[j] + lo));
-            a[0] += bf16_lo(gv.x); a[1] += bf16_hi(gv.x);
-            a[2] += bf16_lo(gv.y); a[3] += bf16_hi(gv.y);
+        for (int j = 0; j < K; j += DEPTH) {
+            u32x2 gv[DEPTH];
+#pragma unroll
+            for (int q = 0; q < DEPTH; ++q)
+                if (j + q < K) gv[q] = ld_stream(reinterpret_cast<const u32x2 *>(gt.g[j + q] + lo));
+#pragma unroll
+            for (int q = 0; q < DEPTH; ++q)
+                if (j + q < K) add_pair(a, gv[q]);
             __builtin_amdgcn_sched_barrier(0);
         }
     } else {
         // runtime k; the adds stay in ascending order of j
         int j = 0;
-        if constexpr (WIDE) {
+        if constexpr (DEPTH == 0) {
             for (; j + 4 <= k; j += 4) {
                 u32x2 gv[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) gv[q] = ld_stream(reinterpret_cast<const u32x2 *>(gt.g[j + q] + lo));
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    a[0] += bf16_lo(gv[q].x); a[1] += bf16_hi(gv[q].x);
-                    a[2] += bf16_lo(gv[q].y); a[3] += bf16_hi(gv[q].y);
-                }
+                for (int q = 0; q < 4; ++q) add_pair(a, gv[q]);
             }
-            if (j + 2 <= k) {
+        }
+        if constexpr (DEPTH == 0 || DEPTH == 2) {
+#pragma unroll 1
+            for (; j + 2 <= k; j += 2) {
                 u32x2 g0 = ld_stream(reinterpret_cast<const u32x2 *>(gt.g[j] + lo));
                 u32x2 g1 = ld_stream(reinterpret_cast<const u32x2 *>(gt.g[j + 1] + lo));
-                a[0] += bf16_lo(g0.x); a[1] += bf16_hi(g0.x); a[2] += bf16_lo(g0.y); a[3] += bf16_hi(g0.y);
-                a[0] += bf16_lo(g1.x); a[1] += bf16_hi(g1.x); a[2] += bf16_lo(g1.y); a[3] += bf16_hi(g1.y);
-                j += 2;
+                add_pair(a, g0);
+                add_pair(a, g1);
             }
         }
-        for (; j < k; ++j) {
-            u32x2 gv = ld_stream(reinterpret_cast<const u32x2 *>(gt.g[j] + lo));
-            a[0] += bf16_lo(gv.x); a[1] += bf16_hi(gv.x);
-            a[2] += bf16_lo(gv.y); a[3] += bf16_hi(gv.y);
-        }
+#pragma unroll 1
+        for (; j < k; ++j) add_pair(a, ld_stream(reinterpret_cast<const u32x2 *>(gt.g[j] + lo)));
     }
 }
 
@@ -193,7 +196,7 @@ __device__ __forceinline__ double block_sum(double x, double *lds)
 // group lies inside [begin,end), per-element path for ragged range ends -- same arithmetic.
 // States are read from A.p/m/v and written to A.po/mo/vo (the same arrays for the in-place
 // entry points).  NORM: also add the squares of the accumulated gradients to acc0/acc1.
-template <int K, bool NORM, bool WIDE = false>
+template <int K, bool NORM, int DEPTH = 1>
 __device__ __forceinline__ void step_group(const StepArgs &A, int k, int64_t lo, float c, const StepConsts &s,
                                            double &acc0, double &acc1)
 {
@@ -207,7 +210,7 @@ __device__ __forceinline__ void step_group(const StepArgs &A, int k, int64_t lo,
             f32x4 av = ld_stream(reinterpret_cast<const f32x4 *>(A.acc + lo));
             a[0] = av.x; a[1] = av.y; a[2] = av.z; a[3] = av.w;
         } else {
-            accumulate_group<K, WIDE>(A.gt, k, lo, a);
+            accumulate_group<K, DEPTH>(A.gt, k, lo, a);
         }
         float P[4] = {p.x, p.y, p.z, p.w};
         float M[4] = {m.x, m.y, m.z, m.w};
@@ -223,7 +226,7 @@ __device__ __forceinline__ void step_group(const StepArgs &A, int k, int64_t lo,
         u32x2 wv;
         wv.x = f32_to_bf16_bits(P[0]) | (f32_to_bf16_bits(P[1]) << 16);
         wv.y = f32_to_bf16_bits(P[2]) | (f32_to_bf16_bits(P[3]) << 16);
-        if constexpr (WIDE) {
+        if constexpr (DEPTH == 0) {
             st_stream(reinterpret_cast<f32x4 *>(A.po + lo), f32x4{P[0], P[1], P[2], P[3]});
             st_stream(reinterpret_cast<f32x4 *>(A.mo + lo), f32x4{M[0], M[1], M[2], M[3]});
             st_stream(reinterpret_cast<f32x4 *>(A.vo + lo), f32x4{V[0], V[1], V[2], V[3]});
@@ -277,13 +280,15 @@ __global__ __launch_bounds__(GS_STEP_BLOCK) void k_accum_adamw(StepArgs A)
 // Speculative single pass (Sec. 2.1 of the paper: prior work steps before the global norm is
 // known because clipping rarely changes the gradients): the step is applied with c = 1 and the
 // squared norm of the same accumulated gradients is reduced on the way, so the gradients are
-// read once.  Needs per-workgroup partials, hence the same 4096-element tiles / span logic as
-// the staged norm kernel.
-template <int K>
-__global__ __launch_bounds__(GS_STAGE_BLOCK) void k_accum_adamw_spec(StepArgs A, double *partials, int span)
+// read once.  Every workgroup leaves a partial.  Fast shape: the step kernel's own 512-element
+// tiles, one per workgroup, shallow queues (needs a workspace of one double per tile);
+// fallback for the fixed-size workspace: 4096-element tiles, all loads in flight, `span` tiles
+// per workgroup.
+template <int K, int BLOCK, int DEPTH>
+__global__ __launch_bounds__(BLOCK) void k_accum_adamw_spec(StepArgs A, double *partials, int span)
 {
-    constexpr int TILE = GS_STAGE_BLOCK * 4;
-    __shared__ double lds[GS_STAGE_BLOCK / 64];
+    constexpr int TILE = BLOCK * 4;
+    __shared__ double lds[BLOCK / 64];
     const int k = (K > 0) ? K : A.k;
     const int64_t first = (A.begin / TILE + (int64_t)blockIdx.x * span) * TILE + (int64_t)threadIdx.x * 4;
     double acc0 = 0.0, acc1 = 0.0;
@@ -291,9 +296,9 @@ __global__ __launch_bounds__(GS_STAGE_BLOCK) void k_accum_adamw_spec(StepArgs A,
         const int64_t lo = first + (int64_t)it * TILE;
         if (lo >= A.end) break;
         if (lo + 4 <= A.begin) continue;
-        step_group<K, true, true>(A, k, lo, 1.0f, A.c, acc0, acc1);   // 1024-lane workgroups: all loads in flight
+        step_group<K, true, DEPTH>(A, k, lo, 1.0f, A.c, acc0, acc1);
     }
-    double t = block_sum<GS_STAGE_BLOCK>(acc0 + acc1, lds);
+    double t = block_sum<BLOCK>(acc0 + acc1, lds);
     if (threadIdx.x == 0) partials[blockIdx.x] = t;
 }
 
@@ -306,7 +311,7 @@ __global__ __launch_bounds__(GS_STAGE_BLOCK) void k_accum_adamw_spec(StepArgs A,
 // of tiles per workgroup cost bandwidth again (stores want in-order, one-tile workgroups), so
 // the staged kernel uses 1024-lane workgroups (4096-element tiles) and a span of 1 wherever the
 // partials still fit the workspace.
-template <int K, bool STAGE, int BLOCK>
+template <int K, bool STAGE, int BLOCK, int DEPTH>
 __global__ __launch_bounds__(BLOCK) void k_grad_sqnorm(SqnormArgs A, int span)
 {
     constexpr int TILE = BLOCK * 4;
@@ -320,7 +325,7 @@ __global__ __launch_bounds__(BLOCK) void k_grad_sqnorm(SqnormArgs A, int span)
         if (lo + 4 <= A.begin) continue;
         if (lo >= A.begin && lo + 4 <= A.end) {
             float a[4];
-            accumulate_group<K, true>(A.gt, k, lo, a);
+            accumulate_group<K, DEPTH>(A.gt, k, lo, a);
             if constexpr (STAGE) st_stream(reinterpret_cast<f32x4 *>(A.acc + lo), f32x4{a[0], a[1], a[2], a[3]});
             acc0 = fma((double)a[0], (double)a[0], acc0);
             acc1 = fma((double)a[1], (double)a[1], acc1);
@@ -364,10 +369,10 @@ __global__ __launch_bounds__(GS_FINAL_BLOCK) void k_sqnorm_finalize(const double
     if (threadIdx.x == 0) *out = accumulate ? (*out + t) : t;
 }
 
-static hipError_t launch_fold(double *partials, int nparts, double *d_out, int accumulate, hipStream_t stream)
+static hipError_t launch_fold(double *partials, int64_t cap, int nparts, double *d_out, int accumulate, hipStream_t stream)
 {
     if (nparts > GS_FINAL_DIRECT_MAX) {
-        double *slices = partials + GS_SQNORM_MAX_BLOCKS;
+        double *slices = partials + cap;          // the last GS_FINAL_SLICES doubles of the workspace
         k_sqnorm_fold_slices<<<GS_FINAL_SLICES, GS_FINAL_BLOCK, 0, stream>>>(partials, nparts, slices);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -405,42 +410,74 @@ hipError_t launch_accum_adamw(const StepArgs &A, hipStream_t stream)
     return hipGetLastError();
 }
 
-hipError_t launch_accum_adamw_spec(const StepArgs &A, double *partials, double *d_out, int accumulate, hipStream_t stream)
+// Partials the workspace can hold (its last GS_FINAL_SLICES doubles serve the folding stage).
+static int64_t partial_capacity(size_t workspace_bytes)
 {
-    int64_t tiles = tiles_of(A.begin, A.end, (int64_t)GS_STAGE_BLOCK * 4);
+    return (int64_t)(workspace_bytes / sizeof(double)) - GS_FINAL_SLICES;
+}
+
+hipError_t launch_accum_adamw_spec(const StepArgs &A, double *partials, size_t workspace_bytes, double *d_out,
+                                   int accumulate, hipStream_t stream)
+{
+    const int64_t cap = partial_capacity(workspace_bytes);
+    int64_t tiles = tiles_of(A.begin, A.end, (int64_t)GS_STEP_BLOCK * 4);
+    if (tiles < 1) tiles = 1;
+    if (tiles <= cap && tiles <= 0x7fffffff) {
+        // one 512-element tile per workgroup, runtime gradient loop, shallow queues
+        const int grid = (int)tiles;
+        k_accum_adamw_spec<0, GS_STEP_BLOCK, 1><<<grid, GS_STEP_BLOCK, 0, stream>>>(A, partials, 1);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        return launch_fold(partials, cap, grid, d_out, accumulate, stream);
+    }
+    tiles = tiles_of(A.begin, A.end, (int64_t)GS_STAGE_BLOCK * 4);
     if (tiles < 1) tiles = 1;
     int64_t span = 1;
-    if (tiles > GS_SQNORM_MAX_BLOCKS) span = (tiles + GS_SQNORM_MAX_BLOCKS - 1) / GS_SQNORM_MAX_BLOCKS;
+    if (tiles > cap) span = (tiles + cap - 1) / cap;
     if (span > 0x7fffffff) return hipErrorInvalidValue;
     const int grid = (int)((tiles + span - 1) / span);
     const int sp = (int)span;
     switch (A.k) {
-    case 1: k_accum_adamw_spec<1><<<grid, GS_STAGE_BLOCK, 0, stream>>>(A, partials, sp); break;
-    case 2: k_accum_adamw_spec<2><<<grid, GS_STAGE_BLOCK, 0, stream>>>(A, partials, sp); break;
-    case 4: k_accum_adamw_spec<4><<<grid, GS_STAGE_BLOCK, 0, stream>>>(A, partials, sp); break;
-    case 8: k_accum_adamw_spec<8><<<grid, GS_STAGE_BLOCK, 0, stream>>>(A, partials, sp); break;
-    case 16: k_accum_adamw_spec<16><<<grid, GS_STAGE_BLOCK, 0, stream>>>(A, partials, sp); break;
-    default: k_accum_adamw_spec<0><<<grid, GS_STAGE_BLOCK, 0, stream>>>(A, partials, sp); break;
+    case 1: k_accum_adamw_spec<1, GS_STAGE_BLOCK, 0><<<grid, GS_STAGE_BLOCK, 0, stream>>>(A, partials, sp); break;
+    case 2: k_accum_adamw_spec<2, GS_STAGE_BLOCK, 0><<<grid, GS_STAGE_BLOCK, 0, stream>>>(A, partials, sp); break;
+    case 4: k_accum_adamw_spec<4, GS_STAGE_BLOCK, 0><<<grid, GS_STAGE_BLOCK, 0, stream>>>(A, partials, sp); break;
+    case 8: k_accum_adamw_spec<8, GS_STAGE_BLOCK, 0><<<grid, GS_STAGE_BLOCK, 0, stream>>>(A, partials, sp); break;
+    case 16: k_accum_adamw_spec<16, GS_STAGE_BLOCK, 0><<<grid, GS_STAGE_BLOCK, 0, stream>>>(A, partials, sp); break;
+    default: k_accum_adamw_spec<0, GS_STAGE_BLOCK, 0><<<grid, GS_STAGE_BLOCK, 0, stream>>>(A, partials, sp); break;
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return launch_fold(partials, grid, d_out, accumulate, stream);
+    return launch_fold(partials, cap, grid, d_out, accumulate, stream);
 }
 
-hipError_t launch_grad_sqnorm(const SqnormArgs &A, double *d_out, int accumulate, hipStream_t stream)
+hipError_t launch_grad_sqnorm(const SqnormArgs &A, size_t workspace_bytes, double *d_out, int accumulate,
+                              hipStream_t stream)
 {
+    const int64_t cap = partial_capacity(workspace_bytes);
     const bool stage = A.acc != nullptr;
+    if (stage) {
+        // staged norm, fast shape: one 512-element tile per workgroup, two gradient loads in flight
+        int64_t t128 = tiles_of(A.begin, A.end, (int64_t)GS_STEP_BLOCK * 4);
+        if (t128 < 1) t128 = 1;
+        if (t128 <= cap && t128 <= 0x7fffffff) {
+            const int grid = (int)t128;
+            k_grad_sqnorm<0, true, GS_STEP_BLOCK, 2><<<grid, GS_STEP_BLOCK, 0, stream>>>(A, 1);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            return launch_fold(A.partials, cap, grid, d_out, accumulate, stream);
+        }
+    }
     const int block = stage ? GS_STAGE_BLOCK : GS_BLOCK;
     int64_t tiles = tiles_of(A.begin, A.end, (int64_t)block * 4);
     if (tiles < 1) tiles = 1;
     int64_t span = stage ? 1 : GS_NORM_SPAN;
-    if ((tiles + span - 1) / span > GS_SQNORM_MAX_BLOCKS) span = (tiles + GS_SQNORM_MAX_BLOCKS - 1) / GS_SQNORM_MAX_BLOCKS;
+    if ((tiles + span - 1) / span > cap) span = (tiles + cap - 1) / cap;
     if (span > 0x7fffffff) return hipErrorInvalidValue;
     const int grid = (int)((tiles + span - 1) / span);
     const int sp = (int)span;
-#define GS_NORM_CASE(KK)                                                                              \
-    if (stage) k_grad_sqnorm<KK, true, GS_STAGE_BLOCK><<<grid, GS_STAGE_BLOCK, 0, stream>>>(A, sp);   \
-    else k_grad_sqnorm<KK, false, GS_BLOCK><<<grid, GS_BLOCK, 0, stream>>>(A, sp);                    \
+#define GS_NORM_CASE(KK)                                                                                 \
+    if (stage) k_grad_sqnorm<KK, true, GS_STAGE_BLOCK, 0><<<grid, GS_STAGE_BLOCK, 0, stream>>>(A, sp);   \
+    else k_grad_sqnorm<KK, false, GS_BLOCK, 0><<<grid, GS_BLOCK, 0, stream>>>(A, sp);                    \
     break
     switch (A.k) {
     case 1: GS_NORM_CASE(1);
@@ -453,7 +490,7 @@ hipError_t launch_grad_sqnorm(const SqnormArgs &A, double *d_out, int accumulate
 #undef GS_NORM_CASE
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return launch_fold(A.partials, grid, d_out, accumulate, stream);
+    return launch_fold(A.partials, cap, grid, d_out, accumulate, stream);
 }
 
 }  // namespace gs

@@ -64,6 +64,8 @@ _pp = ctypes.POINTER(ctypes.c_void_p)
 
 _lib.gs_sqnorm_workspace_bytes.argtypes = []
 _lib.gs_sqnorm_workspace_bytes.restype = ctypes.c_size_t
+_lib.gs_sqnorm_workspace_bytes_for.argtypes = [_i64]
+_lib.gs_sqnorm_workspace_bytes_for.restype = ctypes.c_size_t
 _lib.gs_grad_sqnorm.argtypes = [_pp, ctypes.c_int, _i64, _i64, _vp, ctypes.c_int, _vp, ctypes.c_size_t, _vp]
 _lib.gs_grad_sqnorm.restype = ctypes.c_int
 _lib.gs_accum_adamw.argtypes = [_vp, _vp, _vp, _vp, _pp, ctypes.c_int, _i64, _i64,
@@ -168,6 +170,10 @@ def gs_last_hip_error() -> str:
 
 def gs_sqnorm_workspace_bytes() -> int:
     return int(_lib.gs_sqnorm_workspace_bytes())
+
+
+def gs_sqnorm_workspace_bytes_for(range_elems: int) -> int:
+    return int(_lib.gs_sqnorm_workspace_bytes_for(int(range_elems)))
 
 
 def gs_grad_sqnorm(grads, begin: int, end: int, d_sqnorm, d_workspace, workspace_bytes: int | None = None,

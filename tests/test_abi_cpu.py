@@ -28,7 +28,7 @@ def test_header_symbols_all_exported():
             "gs_stream_ctx_create", "gs_stream_ctx_destroy", "gs_stream_ctx_sync", "gs_pinned_alloc",
             "gs_pinned_free", "gs_strerror", "gs_last_hip_error", "gs_grad_accum_sqnorm", "gs_adamw_from_acc",
             "gs_cu_stream_create", "gs_cu_stream_destroy", "gs_accum_adamw_oop", "gs_accum_adamw_spec",
-            "gs_clip_coefficient"} <= set(names)
+            "gs_clip_coefficient", "gs_sqnorm_workspace_bytes_for"} <= set(names)
     lib = ctypes.CDLL(gs.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in gs.h but not exported"
@@ -165,6 +165,15 @@ def test_host_clip_coefficient_matches_oracle():
     for S, mx in ((0.0, 1.0), (0.25, 1.0), (1.0, 1.0), (4.0, 1.0), (3221.8, 1.0), (1e12, 0.5), (7.0, 0.0), (7.0, -1.0),
                   (float("inf"), 1.0), (float("nan"), 1.0), (1e-30, 1e-3), (0.99999, 1.0), (1.00001, 1.0)):
         assert gs.gs_clip_coefficient(S, mx) == O.clip_coef(S, mx), (S, mx)
+
+
+def test_workspace_size_for_range():
+    base = gs.gs_sqnorm_workspace_bytes()
+    assert gs.gs_sqnorm_workspace_bytes_for(0) == base and gs.gs_sqnorm_workspace_bytes_for(-5) == base
+    assert gs.gs_sqnorm_workspace_bytes_for(1 << 20) == base
+    big = gs.gs_sqnorm_workspace_bytes_for(805_412_864)
+    assert big > base and big % 8 == 0 and 805_412_864 // 64 <= big <= 805_412_864 // 64 + 4096
+    assert gs.gs_sqnorm_workspace_bytes_for(1 << 34) > big
 
 
 def test_cu_stream_rejects_without_gpu():

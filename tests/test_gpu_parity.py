@@ -503,3 +503,45 @@ def test_norm_and_step_replay_from_a_hip_graph():
     case2.gpu_sqnorm()
     run_gpu_step(case2, HP, states=st)
     compare_states(st, ora, "graph reference")
+
+
+# ----------------------------------------------------------------------------- large-workspace shapes
+@pytest.mark.parametrize("k", [1, 2, 5, 16])
+def test_staged_and_speculative_fast_shapes_with_large_workspace(k):
+    """With a workspace of gs_sqnorm_workspace_bytes_for(n) the staged norm and the speculative
+    step run as one 512-element tile per workgroup; results must not change (beyond the fp64
+    summation order of the norm)."""
+    n = 512 * 700 + 261
+    case = DeviceCase(n, k, seed=180 + k)
+    big = torch.empty(gs.gs_sqnorm_workspace_bytes_for(n) + 64, dtype=torch.uint8, device=DEV)
+    assert big.numel() >= gs.gs_sqnorm_workspace_bytes()
+    S_ref = case.gpu_sqnorm()
+    So = O.grad_sqnorm(case.h_g)
+    # staged norm
+    acc = torch.full((n,), float("nan"), dtype=torch.float32, device=DEV)
+    sq = torch.zeros(1, dtype=torch.float64, device=DEV)
+    for b, e in ((0, n), (3, n - 5), (513, 514), (0, 0)):
+        acc.fill_(float("nan"))
+        gs.gs_grad_accum_sqnorm(case.grads, b, e, acc, sq, big)
+        torch.cuda.synchronize()
+        want = O.grad_sqnorm(case.h_g, b, e)
+        assert abs(float(sq.item()) - want) <= 1e-12 * max(want, 1e-300)
+        got = np_f32(acc)
+        assert np.array_equal(got[b:e], O.accumulate(case.h_g, b, e)[b:e])
+        assert np.isnan(got[:b]).all() and np.isnan(got[e:]).all()
+    # speculative step
+    po, mo, vo = (torch.full_like(case.p, float("nan")) for _ in range(3))
+    w = torch.zeros_like(case.w)
+    gs.gs_accum_adamw_spec(case.p, case.m, case.v, po, mo, vo, w, case.grads, 0, n, HP, sq, big)
+    torch.cuda.synchronize()
+    assert abs(float(sq.item()) - So) <= 1e-12 * So and abs(float(sq.item()) - S_ref) <= 1e-12 * S_ref
+    compare_states((po, mo, vo, w), case.oracle_step(HP, 1.0), f"spec-fast k={k}")
+    # ragged sub-range, accumulating into the same scalar
+    po2, mo2, vo2 = case.p.clone(), case.m.clone(), case.v.clone()
+    w2 = torch.zeros_like(case.w)
+    gs.gs_accum_adamw_spec(case.p, case.m, case.v, po2, mo2, vo2, w2, case.grads, 0, 1027, HP, sq, big)
+    gs.gs_accum_adamw_spec(case.p, case.m, case.v, po2, mo2, vo2, w2, case.grads, 1027, n, HP, sq, big, accumulate=True)
+    torch.cuda.synchronize()
+    assert abs(float(sq.item()) - So) <= 1e-12 * So
+    for a, b in zip((po, mo, vo, w), (po2, mo2, vo2, w2)):
+        assert torch.equal(a, b)
