@@ -138,6 +138,55 @@ def test_h8192_k16_headline_sampled():
 
 
 @pytest.mark.timeout(600)
+def test_h8192_k16_staged_and_speculative_at_full_size():
+    """The widened entry points at the headline size, in the shapes bench.py times (large
+    workspace): staged two-pass == fused bit for bit; speculative pass == oracle with c = 1 on
+    sampled windows, inputs untouched, its norm equal to gs_grad_sqnorm's."""
+    wl = I.WORKLOADS["gpt65b_layer_h8192_k16"]
+    n, k = wl.n, wl.k
+    print(f"[h8192 staged/spec] n={n} k={k}", flush=True)
+    p, m, v, grads = I.make_workload_tensors(wl, DEV)
+    p0, m0, v0 = p.clone(), m.clone(), v.clone()
+    w = torch.zeros(n, dtype=torch.bfloat16, device=DEV)
+    sq = torch.zeros(1, dtype=torch.float64, device=DEV)
+    sq2 = torch.zeros(1, dtype=torch.float64, device=DEV)
+    ws = torch.empty(gs.gs_sqnorm_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    big = torch.empty(gs.gs_sqnorm_workspace_bytes_for(n), dtype=torch.uint8, device=DEV)
+    hp = hp_of(wl)
+    gs.gs_grad_sqnorm(grads, 0, n, sq, ws)
+    gs.gs_accum_adamw(p, m, v, w, grads, 0, n, hp, sq)                    # fused reference
+    torch.cuda.synchronize()
+    S = float(sq.item())
+    # speculative pass from the untouched originals
+    wins = windows(n, 16, 5000, seed=3)
+    before = {lo: grab((p0, m0, v0), lo, hi) for lo, hi in wins}
+    po, mo, vo = torch.empty_like(p0), torch.empty_like(m0), torch.empty_like(v0)
+    w_s = torch.zeros_like(w)
+    gs.gs_accum_adamw_spec(p0, m0, v0, po, mo, vo, w_s, grads, 0, n, hp, sq2, big)
+    torch.cuda.synchronize()
+    assert abs(float(sq2.item()) - S) <= 1e-12 * S
+    after = {lo: grab((po, mo, vo), lo, hi) + [np_bf16(w_s[lo:hi])] for lo, hi in wins}
+    check_windows(wins, before, after, grads, hp, 1.0, "spec")
+    for lo, hi in wins[:4]:
+        for a, b in zip(grab((p0, m0, v0), lo, hi), before[lo]):
+            assert np.array_equal(a, b)                                   # inputs untouched
+    assert gs.gs_clip_coefficient(S, hp.max_grad_norm) < 1.0              # the guess fails on this workload
+    del po, mo, vo, w_s
+    # staged two-pass on the originals, in place: must equal the fused result bit for bit
+    acc = torch.empty(n, dtype=torch.float32, device=DEV)
+    w2 = torch.zeros_like(w)
+    gs.gs_grad_accum_sqnorm(grads, 0, n, acc, sq2, big)
+    gs.gs_adamw_from_acc(p0, m0, v0, w2, acc, 0, n, hp, sq)               # same norm scalar as the fused run
+    torch.cuda.synchronize()
+    assert abs(float(sq2.item()) - S) <= 1e-12 * S
+    for a, b, nm in ((p, p0, "p"), (m, m0, "m"), (v, v0, "v"), (w, w2, "w")):
+        assert torch.equal(a, b), f"staged != fused in {nm}"
+    lo, hi = wins[3]
+    assert np.array_equal(np_f32(acc[lo:hi]), O.accumulate([np_bf16(g[lo:hi]) for g in grads]))
+    print(f"[h8192 staged/spec] S={S:.6e}; staged == fused bitwise; spec windows ok", flush=True)
+
+
+@pytest.mark.timeout(600)
 def test_h12288_k8_split_equals_full_and_sampled():
     wl = I.WORKLOADS["gpt175b_layer_h12288_k8_split"]
     n, k = wl.n, wl.k
