@@ -27,6 +27,11 @@
  *   - All device work is enqueued on `stream` and the call returns without waiting.
  *   - Every argument is validated before the first HIP call; a rejected call has touched
  *     nothing.  Functions return a gs_status; nothing throws or aborts.
+ *   - Device work runs on the current HIP device; pointers, streams and contexts passed to a
+ *     call must belong to it.  The stateless entry points may be called from several host threads
+ *     at once; a gs_stream_ctx must be used by one thread at a time.
+ *   - Input and output arrays of one call must not overlap each other, except where a call
+ *     states that an output may be its own input.
  *   - Results do not depend on how a range is partitioned: applying the step to [a,b) and
  *     then to [b,c) gives bit-identical p, m, v, w to applying it to [a,c) (Sec. 6.5 requires
  *     results that are reproducible across partition ratios).
@@ -244,7 +249,8 @@ gs_status gs_stream_ctx_destroy(gs_stream_ctx *ctx); /* waits for pending work, 
  *   producer_stream stream on which the gradients and *d_sqnorm were produced; work already
  *                   enqueued there is waited for before the first kernel (NULL = null stream)
  * The call enqueues everything and returns; host buffers must stay untouched until
- * gs_stream_ctx_sync.  Several layers may be enqueued back to back on one context.
+ * gs_stream_ctx_sync.  Several layers may be enqueued back to back on one context.  Must be
+ * called with the device current on which the context was created (else GS_ERR_INVALID_ARG).
  */
 gs_status gs_stream_layer_step(gs_stream_ctx *ctx, float *h_p, float *h_m, float *h_v,
                                uint16_t *d_w_bf16, const uint16_t *const *d_grads, int k, int64_t n,

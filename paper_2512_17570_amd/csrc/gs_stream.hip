@@ -144,6 +144,10 @@ gs_status gs_stream_layer_step(gs_stream_ctx *c, float *h_p, float *h_m, float *
     if (d_sqnorm && (reinterpret_cast<uintptr_t>(d_sqnorm) & 7u)) return GS_ERR_INVALID_ARG;
     if (n == 0) return GS_OK;
 
+    int cur = -1;
+    GS_TRY(hipGetDevice(&cur), "hipGetDevice");
+    if (cur != c->device) return GS_ERR_INVALID_ARG;   // the context's streams and slots live on another GPU
+
     // gradients and the norm come from the caller's stream
     GS_TRY(hipEventRecord(c->ev_producer, static_cast<hipStream_t>(producer_stream)), "hipEventRecord(producer)");
     GS_TRY(hipStreamWaitEvent(c->s_comp, c->ev_producer, 0), "hipStreamWaitEvent(producer)");
