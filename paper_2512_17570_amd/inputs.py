@@ -71,6 +71,8 @@ WORKLOADS = {
     "gpt_h4096_k8": Workload("gpt_h4096_k8", h=4096, k=8, grad_sigma=1e-3, step=100, outlier_frac=1e-3),
     # headline bandwidth workload: one GPT-65B-shaped layer
     "gpt65b_layer_h8192_k16": Workload("gpt65b_layer_h8192_k16", h=8192, k=16, grad_sigma=5e-4, step=100),
+    # one GPT-30B-shaped layer (Table 2: hidden 7168), second resident workload
+    "gpt30b_layer_h7168_k16": Workload("gpt30b_layer_h7168_k16", h=7168, k=16, grad_sigma=5e-4, step=100),
     # GPT-175B-shaped layer, split step (40 % immediate / 60 % deferred)
     "gpt175b_layer_h12288_k8_split": Workload("gpt175b_layer_h12288_k8_split", h=12288, k=8, grad_sigma=5e-4,
                                               step=100, extra={"immediate_frac": 0.4, "gemm_tokens": 4096}),

@@ -33,6 +33,7 @@ def test_layer_numel_matches_paper_figures():
         assert abs(layers * I.layer_numel(h) / total - 1) < 0.03
     assert I.WORKLOADS["gpt65b_layer_h8192_k16"].h == h65
     assert I.WORKLOADS["gpt175b_layer_h12288_k8_split"].h == models["175B"][2]
+    assert I.WORKLOADS["gpt30b_layer_h7168_k16"].h == models["30B"][2]
 
 
 def test_layer_numel_values_and_segments():
