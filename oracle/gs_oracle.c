@@ -79,6 +79,23 @@ void gs_oracle_accumulate(const uint16_t *const *grads, int k, int64_t begin, in
         out[i] = accumulate_f32(grads, k, i);
 }
 
+/* a1 as the paper runs it (Sec. 3.4, Sec. 4.3: one full-precision accumulation buffer per layer
+ * on the GPU; each micro-batch's backward adds its gradient into it):
+ *   acc[i] = (first ? +0 : acc[i]) + widen(grad[i])   for i in [begin,end).
+ * Returns the squared L2 norm (double) of the updated acc over the range. */
+double gs_oracle_accum_add(float *acc, const uint16_t *grad, int first, int64_t begin, int64_t end)
+{
+    double S = 0.0;
+    for (int64_t i = begin; i < end; ++i) {
+        float base = first ? 0.0f : acc[i];
+        float a = base + gs_oracle_bf16_to_f32(grad[i]);
+        acc[i] = a;
+        double ad = (double)a;
+        S += ad * ad;
+    }
+    return S;
+}
+
 /* ---- a2: squared L2 norm of the accumulated gradient over [begin,end) ------------------ */
 /* (Sec. 2.1: clipping needs the global L2 norm.)  Each square is exact in double. */
 double gs_oracle_grad_sqnorm(const uint16_t *const *grads, int k, int64_t begin, int64_t end)

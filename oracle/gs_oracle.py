@@ -68,6 +68,8 @@ def lib():
         L.gs_oracle_grad_sqnorm.restype = ctypes.c_double
         L.gs_oracle_accumulate.argtypes = [u16pp, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p]
         L.gs_oracle_accumulate.restype = None
+        L.gs_oracle_accum_add.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64]
+        L.gs_oracle_accum_add.restype = ctypes.c_double
         L.gs_oracle_clip_coef.argtypes = [ctypes.c_double, ctypes.c_float]
         L.gs_oracle_clip_coef.restype = ctypes.c_float
         L.gs_oracle_accum_adamw.argtypes = [ctypes.c_void_p] * 4 + [
@@ -119,6 +121,16 @@ def accumulate(grads, begin: int = 0, end: int | None = None) -> np.ndarray:
     out = np.zeros(n, np.float32)
     lib().gs_oracle_accumulate(tab, k, begin, end, out.ctypes.data)
     return out
+
+
+def accum_add(acc: np.ndarray, grad: np.ndarray, first: bool, begin: int = 0, end: int | None = None) -> float:
+    """acc[i] = (first ? +0 : acc[i]) + grad[i] over [begin,end), in place; returns the squared
+    L2 norm of the updated range."""
+    _check(acc, np.float32, "acc")
+    _check(grad, np.uint16, "grad")
+    end = len(grad) if end is None else end
+    assert 0 <= begin <= end <= len(grad) and len(acc) >= end
+    return float(lib().gs_oracle_accum_add(acc.ctypes.data, grad.ctypes.data, int(bool(first)), begin, end))
 
 
 def clip_coef(sqnorm_total: float, max_norm: float) -> float:

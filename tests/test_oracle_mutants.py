@@ -33,6 +33,9 @@ MUTANTS = [
     ("w_from_old_p", "w[i] = gs_oracle_f32_to_bf16(pn);", "w[i] = gs_oracle_f32_to_bf16(t5);"),
     ("truth_vhat_uses_bc1", "double vhat = vn / bc2;", "double vhat = vn / bc1;"),
     ("truth_no_clip", "if (c > 1.0) c = 1.0;", "c = 1.0;"),
+    ("add_forgets_buffer", "float base = first ? 0.0f : acc[i];", "float base = 0.0f;"),
+    ("add_first_keeps_old", "float base = first ? 0.0f : acc[i];", "float base = acc[i];"),
+    ("add_norm_before_update", "double ad = (double)a;", "double ad = (double)base;"),
     ("bf16_decode_shift", "uint32_t u = (uint32_t)h << 16;", "uint32_t u = (uint32_t)h << 15;"),
 ]
 

@@ -350,6 +350,35 @@ def test_accumulate_matches_sequential_float32_adds_and_exact_sum():
     assert math.isclose(float(np.dot(got.astype(np.float64), got.astype(np.float64))), O.grad_sqnorm(g), rel_tol=1e-12)
 
 
+def test_accum_add_one_micro_batch_at_a_time():
+    """As-you-go accumulation: each call equals a numpy float32 add of the widened buffer
+    (library arithmetic); k calls in order reproduce the k-way sum; the returned value is the
+    squared norm of the updated range; `first` ignores what the buffer held; elements outside
+    the range are untouched."""
+    n, k = 5_000, 5
+    _, _, _, g = rand_case(n, k, seed=71, sigma=1e-2)
+    acc = np.full(n, np.float32(np.nan))            # garbage that `first` must ignore
+    want = np.zeros(n, np.float32)
+    for j, b in enumerate(g):
+        S = O.accum_add(acc, b, first=(j == 0))
+        want = (want + bf16_bits_to_f64(b).astype(np.float32)).astype(np.float32)
+        assert np.array_equal(acc, want)
+        assert math.isclose(S, float(np.dot(want.astype(np.float64), want.astype(np.float64))), rel_tol=1e-12)
+    assert np.array_equal(acc, O.accumulate(g))
+    # a range: only [lo,hi) moves, and the returned norm covers only that range
+    before = acc.copy()
+    S = O.accum_add(acc, g[0], first=False, begin=123, end=457)
+    assert np.array_equal(acc[:123], before[:123]) and np.array_equal(acc[457:], before[457:])
+    mid = (before[123:457] + bf16_bits_to_f64(g[0][123:457]).astype(np.float32)).astype(np.float32)
+    assert np.array_equal(acc[123:457], mid)
+    assert math.isclose(S, float(np.dot(mid.astype(np.float64), mid.astype(np.float64))), rel_tol=1e-12)
+    # -0 inputs: +0 + (-0) is +0, so the buffer never holds a negative zero after `first`
+    z = np.zeros(4, np.float32)
+    O.accum_add(z, np.full(4, 0x8000, np.uint16), first=True)
+    assert not np.signbit(z).any()
+    assert O.accum_add(z, np.zeros(4, np.uint16), first=True, begin=2, end=2) == 0.0
+
+
 def test_sum_not_mean():
     n = 256
     one = np.full(n, 0x3C00, dtype=np.uint16)       # 2^-7
