@@ -420,6 +420,22 @@ def main():
     staged_elapsed = time.perf_counter() - t1
     st_norm_ms = sum(e[0].elapsed_time(e[1]) for e in ev2) / args.steps
     st_step_ms = sum(e[1].elapsed_time(e[2]) for e in ev2) / args.steps
+
+    # accumulate as you go: one micro-batch added into the resident fp32 buffer per call, the
+    # last call also reducing the norm; then the step from the buffer
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+    add_first_ms = timed(lambda: gs.gs_accum_add(acc, grads[0], True, 0, n), args.steps)
+    add_ms = timed(lambda: gs.gs_accum_add(acc, grads[1 % k], False, 0, n), args.steps)
+    add_norm_ms = timed(lambda: gs.gs_accum_add(acc, grads[k - 1], False, 0, n, sq, ws_big), args.steps)
     del acc
 
     # speculative single pass (c = 1 step + norm in one read of the gradients), out of place with
@@ -478,6 +494,13 @@ def main():
             "gs_adamw_from_acc": {"avg_ms": st_step_ms, "bytes_per_param": 30,
                                   "GBps": n * 30 / (st_step_ms * 1e-3) / 1e9},
             "note": "same results bit for bit; (2k+4)+30 B/param in total instead of 2k+(2k+26)"},
+        "accumulate_as_you_go": {
+            "gs_accum_add_first": {"avg_ms": add_first_ms, "bytes_per_param": 6,
+                                   "GBps": n * 6 / (add_first_ms * 1e-3) / 1e9},
+            "gs_accum_add": {"avg_ms": add_ms, "bytes_per_param": 10, "GBps": n * 10 / (add_ms * 1e-3) / 1e9},
+            "gs_accum_add_with_norm": {"avg_ms": add_norm_ms, "bytes_per_param": 10,
+                                       "GBps": n * 10 / (add_norm_ms * 1e-3) / 1e9},
+            "note": "one call per micro-batch into the resident fp32 buffer; the step then runs gs_adamw_from_acc"},
         "speculative_single_pass": {"avg_ms": spec_ms, "bytes_per_param": 2 * k + 26,
                                     "GBps": step_bytes / (spec_ms * 1e-3) / 1e9, "params_per_s": n / (spec_ms * 1e-3),
                                     "note": "gs_accum_adamw_spec, out of place, step with c=1 plus squared norm; "

@@ -156,6 +156,25 @@ gs_status gs_grad_accum_sqnorm(const uint16_t *const *grads, int k, int64_t begi
                                void *d_workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Accumulate as you go (Sec. 3.4, Sec. 4.3: each micro-batch's backward adds its gradient into
+ * the layer's full-precision buffer on the GPU).  For i in [begin,end):
+ *     acc_f32[i] = (first ? +0 : acc_f32[i]) + widen(grad_bf16[i])
+ * so k calls in micro-batch order (first != 0 on the first only) leave exactly the sum that
+ * gs_grad_accum_sqnorm writes for the same k buffers.
+ *   acc_f32    device fp32, >= end elements, 16-byte aligned; with first != 0 its old contents
+ *              are ignored (no clearing pass needed).
+ *   grad_bf16  device bf16 bit patterns, >= end elements, 16-byte aligned, read only.
+ *   d_sqnorm   NULL, or device fp64 scalar that receives the squared L2 norm of the UPDATED
+ *              acc over [begin,end) (normally asked for on the last micro-batch only);
+ *              accumulate as in gs_grad_sqnorm.  With NULL the workspace arguments are ignored;
+ *              otherwise they follow gs_grad_sqnorm's rules.
+ * Asynchronous on `stream`; elements outside [begin,end) are not touched.
+ */
+gs_status gs_accum_add(float *acc_f32, const uint16_t *grad_bf16, int first, int64_t begin, int64_t end,
+                       double *d_sqnorm, int accumulate,
+                       void *d_workspace, size_t workspace_bytes, void *stream);
+
+/*
  * gs_accum_adamw with the gradient sum taken from acc_f32 (as written by gs_grad_accum_sqnorm)
  * instead of k bf16 buffers.  p, m, v, w come out bit-identical to gs_accum_adamw on the
  * same gradients, and the same partition independence holds.

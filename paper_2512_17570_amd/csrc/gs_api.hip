@@ -119,6 +119,31 @@ gs_status gs_grad_accum_sqnorm(const uint16_t *const *grads, int k, int64_t begi
     return sqnorm_impl(grads, k, begin, end, acc_f32, d_sqnorm, accumulate, d_workspace, workspace_bytes, stream);
 }
 
+gs_status gs_accum_add(float *acc_f32, const uint16_t *grad_bf16, int first, int64_t begin, int64_t end,
+                       double *d_sqnorm, int accumulate,
+                       void *d_workspace, size_t workspace_bytes, void *stream)
+{
+    if (!acc_f32 || !grad_bf16 || !aligned16(acc_f32) || !aligned16(grad_bf16)) return GS_ERR_INVALID_ARG;
+    if (begin < 0 || end < begin) return GS_ERR_INVALID_ARG;
+    if (d_sqnorm) {
+        if (reinterpret_cast<uintptr_t>(d_sqnorm) & 7u) return GS_ERR_INVALID_ARG;
+        if (!d_workspace || workspace_bytes < gs_sqnorm_workspace_bytes()) return GS_ERR_WORKSPACE;
+        if (reinterpret_cast<uintptr_t>(d_workspace) & 7u) return GS_ERR_WORKSPACE;
+    }
+    if (begin == end && (!d_sqnorm || accumulate)) return GS_OK;
+
+    AccumAddArgs A;
+    memset(&A, 0, sizeof A);
+    A.acc = acc_f32;
+    A.g = grad_bf16;
+    A.begin = begin;
+    A.end = end;
+    A.partials = d_sqnorm ? static_cast<double *>(d_workspace) : nullptr;
+    hipError_t e = launch_accum_add(A, first != 0, workspace_bytes, d_sqnorm, accumulate, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "gs_accum_add launch");
+    return GS_OK;
+}
+
 // host mirror of the kernels' clip coefficient
 static float clip_coefficient_host(double sqnorm_total, float max_norm)
 {

@@ -49,11 +49,22 @@ struct SqnormArgs {
     float *acc;         // non-null: also write the fp32 gradient sum here
 };
 
+struct AccumAddArgs {
+    float *acc;
+    const uint16_t *g;
+    int64_t begin, end;
+    double *partials;   // used only when a norm is asked for
+};
+
 hipError_t launch_accum_adamw(const StepArgs &A, hipStream_t stream);
 hipError_t launch_accum_adamw_spec(const StepArgs &A, double *partials, size_t workspace_bytes, double *d_out,
                                    int accumulate, hipStream_t stream);
 hipError_t launch_grad_sqnorm(const SqnormArgs &A, size_t workspace_bytes, double *d_out, int accumulate,
                               hipStream_t stream);
+
+// d_out == nullptr: no norm (then the workspace is not touched)
+hipError_t launch_accum_add(const AccumAddArgs &A, int first, size_t workspace_bytes, double *d_out, int accumulate,
+                            hipStream_t stream);
 
 // host side (gs_api.hip)
 gs_status validate_hparams(const gs_adamw_hparams *hp);

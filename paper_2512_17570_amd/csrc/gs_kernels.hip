@@ -345,6 +345,52 @@ __global__ __launch_bounds__(BLOCK) void k_grad_sqnorm(SqnormArgs A, int span)
     if (threadIdx.x == 0) A.partials[blockIdx.x] = t;
 }
 
+// ---- accumulate as you go ------------------------------------------------------------------
+// The paper's GPU keeps one full-precision accumulation buffer per layer and each micro-batch's
+// backward adds its gradient into it (Sec. 3.4, Sec. 4.3).  acc = (FIRST ? +0 : acc) + widen(g):
+// 2 + 4 bytes read and 4 written per element (2 + 4 for the first micro-batch).  NORM: the call
+// that adds the last micro-batch also reduces the squared norm of the finished sum.
+template <bool FIRST, bool NORM, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void k_accum_add(AccumAddArgs A, int span)
+{
+    constexpr int TILE = BLOCK * 4;
+    __shared__ double lds[BLOCK / 64];
+    const int64_t first = (A.begin / TILE + (int64_t)blockIdx.x * span) * TILE + (int64_t)threadIdx.x * 4;
+    double acc0 = 0.0, acc1 = 0.0;
+    for (int it = 0; it < span; ++it) {
+        const int64_t lo = first + (int64_t)it * TILE;
+        if (lo >= A.end) break;
+        if (lo + 4 <= A.begin) continue;
+        if (lo >= A.begin && lo + 4 <= A.end) {
+            const u32x2 g = ld_stream(reinterpret_cast<const u32x2 *>(A.g + lo));
+            f32x4 a = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            if constexpr (!FIRST) a = ld_stream(reinterpret_cast<const f32x4 *>(A.acc + lo));
+            a.x += bf16_lo(g.x); a.y += bf16_hi(g.x);
+            a.z += bf16_lo(g.y); a.w += bf16_hi(g.y);
+            st_stream(reinterpret_cast<f32x4 *>(A.acc + lo), a);
+            if constexpr (NORM) {
+                acc0 = fma((double)a.x, (double)a.x, acc0);
+                acc1 = fma((double)a.y, (double)a.y, acc1);
+                acc0 = fma((double)a.z, (double)a.z, acc0);
+                acc1 = fma((double)a.w, (double)a.w, acc1);
+            }
+        } else {
+            const int64_t i0 = lo > A.begin ? lo : A.begin;
+            const int64_t i1 = lo + 4 < A.end ? lo + 4 : A.end;
+            for (int64_t i = i0; i < i1; ++i) {
+                float a = FIRST ? 0.0f : A.acc[i];
+                a += __uint_as_float((uint32_t)A.g[i] << 16);
+                A.acc[i] = a;
+                if constexpr (NORM) acc0 = fma((double)a, (double)a, acc0);
+            }
+        }
+    }
+    if constexpr (NORM) {
+        double t = block_sum<BLOCK>(acc0 + acc1, lds);
+        if (threadIdx.x == 0) A.partials[blockIdx.x] = t;
+    }
+}
+
 // Folding the workgroup partials, in a fixed order (deterministic).  Up to 262144 partials are too
 // many for one workgroup to read quickly, so large counts go through GS_FINAL_SLICES workgroups
 // that each fold a contiguous slice into the tail of the workspace, then one workgroup folds those.
@@ -488,6 +534,40 @@ hipError_t launch_grad_sqnorm(const SqnormArgs &A, size_t workspace_bytes, doubl
     default: GS_NORM_CASE(0);
     }
 #undef GS_NORM_CASE
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_fold(A.partials, cap, grid, d_out, accumulate, stream);
+}
+
+hipError_t launch_accum_add(const AccumAddArgs &A, int first, size_t workspace_bytes, double *d_out, int accumulate,
+                            hipStream_t stream)
+{
+    int64_t tiles = tiles_of(A.begin, A.end, (int64_t)GS_STEP_BLOCK * 4);
+    if (tiles < 1) tiles = 1;
+    if (!d_out) {
+        if (tiles > 0x7fffffff) return hipErrorInvalidValue;
+        const int grid = (int)tiles;
+        if (first) k_accum_add<true, false, GS_STEP_BLOCK><<<grid, GS_STEP_BLOCK, 0, stream>>>(A, 1);
+        else k_accum_add<false, false, GS_STEP_BLOCK><<<grid, GS_STEP_BLOCK, 0, stream>>>(A, 1);
+        return hipGetLastError();
+    }
+    const int64_t cap = partial_capacity(workspace_bytes);
+    int grid;
+    if (tiles <= cap && tiles <= 0x7fffffff) {
+        grid = (int)tiles;
+        if (first) k_accum_add<true, true, GS_STEP_BLOCK><<<grid, GS_STEP_BLOCK, 0, stream>>>(A, 1);
+        else k_accum_add<false, true, GS_STEP_BLOCK><<<grid, GS_STEP_BLOCK, 0, stream>>>(A, 1);
+    } else {
+        tiles = tiles_of(A.begin, A.end, (int64_t)GS_STAGE_BLOCK * 4);
+        if (tiles < 1) tiles = 1;
+        int64_t span = 1;
+        if (tiles > cap) span = (tiles + cap - 1) / cap;
+        if (span > 0x7fffffff) return hipErrorInvalidValue;
+        grid = (int)((tiles + span - 1) / span);
+        const int sp = (int)span;
+        if (first) k_accum_add<true, true, GS_STAGE_BLOCK><<<grid, GS_STAGE_BLOCK, 0, stream>>>(A, sp);
+        else k_accum_add<false, true, GS_STAGE_BLOCK><<<grid, GS_STAGE_BLOCK, 0, stream>>>(A, sp);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_fold(A.partials, cap, grid, d_out, accumulate, stream);

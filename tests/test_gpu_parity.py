@@ -390,6 +390,84 @@ def test_staged_variant_ranges_and_split():
         assert torch.equal(a, c)
 
 
+# ----------------------------------------------------------------------------- accumulate as you go
+@pytest.mark.parametrize("k", [1, 2, 5, 16])
+def test_accum_add_equals_oracle_and_k_way_sum(k):
+    """One micro-batch at a time into the fp32 buffer: bit-exact against the oracle after every
+    call, equal to the staged k-way sum at the end, norm of the finished sum on the last call;
+    the finished buffer then drives the same step as the fused kernel."""
+    n = 512 * 300 + 7
+    case = DeviceCase(n, k, seed=140 + k)
+    acc = torch.full((n,), float("nan"), dtype=torch.float32, device=DEV)   # `first` must ignore this
+    sq = torch.full((1,), -1.0, dtype=torch.float64, device=DEV)
+    h_acc = np.full(n, np.float32(np.nan))
+    for j in range(k):
+        last = j == k - 1
+        gs.gs_accum_add(acc, case.grads[j], j == 0, 0, n, sq if last else None, case.ws if last else None)
+        S_o = O.accum_add(h_acc, case.h_g[j], j == 0)
+        torch.cuda.synchronize()
+        assert np.array_equal(np_f32(acc), h_acc), f"micro-batch {j}"
+    assert abs(float(sq.item()) - S_o) <= 1e-12 * S_o
+    assert np.array_equal(h_acc, O.accumulate(case.h_g))
+    S = case.gpu_sqnorm()
+    assert abs(float(sq.item()) - S) <= 1e-12 * S
+    fused = run_gpu_step(case, HP)
+    st = case.clone_states()
+    gs.gs_adamw_from_acc(*st, acc, 0, n, HP, case.sq)
+    torch.cuda.synchronize()
+    for a, b in zip(fused, st):
+        assert torch.equal(a, b)
+
+
+def test_accum_add_ranges_norm_accumulate_and_large_workspace():
+    n = 512 * 200 + 133
+    case = DeviceCase(n, 3, seed=150)
+    big = torch.empty(gs.gs_sqnorm_workspace_bytes_for(n) + 64, dtype=torch.uint8, device=DEV)
+    for ws in (case.ws, big):
+        acc = torch.full((n,), 7.0, dtype=torch.float32, device=DEV)
+        h_acc = np.full(n, np.float32(7.0))
+        sq = torch.zeros(1, dtype=torch.float64, device=DEV)
+        b, e = 1021, n - 1030
+        # ragged range, first: outside stays 7
+        gs.gs_accum_add(acc, case.grads[0], True, b, e, sq, ws)
+        S0 = O.accum_add(h_acc, case.h_g[0], True, b, e)
+        torch.cuda.synchronize()
+        assert np.array_equal(np_f32(acc), h_acc) and abs(float(sq.item()) - S0) <= 1e-12 * S0
+        # second micro-batch over three ranges, norm accumulated across them
+        S1 = 0.0
+        for i, (lo, hi) in enumerate(((b, 2048), (2048, 2049), (2049, e))):
+            gs.gs_accum_add(acc, case.grads[1], False, lo, hi, sq, ws, accumulate=(i > 0))
+            S1 += O.accum_add(h_acc, case.h_g[1], False, lo, hi)
+        torch.cuda.synchronize()
+        assert np.array_equal(np_f32(acc), h_acc) and abs(float(sq.item()) - S1) <= 1e-12 * S1
+        # empty range with a norm asked for: the scalar is set to zero
+        gs.gs_accum_add(acc, case.grads[2], False, 77, 77, sq, ws)
+        torch.cuda.synchronize()
+        assert float(sq.item()) == 0.0 and np.array_equal(np_f32(acc), h_acc)
+
+
+def test_accum_add_special_values():
+    """Inf, NaN, -0 and cancelling gradients go through the add like through the oracle."""
+    pats = np.array([0x7F80, 0xFF80, 0x7FC0, 0x8000, 0x0000, 0x3F80, 0xBF80, 0x0001, 0x7F7F, 0xFF7F], np.uint16)
+    n = 512 * 3 + 5
+    rng = np.random.default_rng(9)
+    g0 = pats[rng.integers(0, len(pats), n)]
+    g1 = pats[rng.integers(0, len(pats), n)]
+    d0 = torch.from_numpy(g0.view(np.int16)).to(DEV).view(torch.bfloat16)
+    d1 = torch.from_numpy(g1.view(np.int16)).to(DEV).view(torch.bfloat16)
+    acc = torch.empty(n, dtype=torch.float32, device=DEV)
+    h = np.empty(n, np.float32)
+    gs.gs_accum_add(acc, d0, True, 0, n)
+    gs.gs_accum_add(acc, d1, False, 0, n)
+    O.accum_add(h, g0, True)
+    O.accum_add(h, g1, False)
+    torch.cuda.synchronize()
+    got = np_f32(acc)
+    assert np.array_equal(np.isnan(got), np.isnan(h))
+    ok = ~np.isnan(h)
+    assert np.array_equal(got[ok].view(np.uint32), h[ok].view(np.uint32))
+
+
 # ----------------------------------------------------------------------------- CU-budgeted stream
 def test_cu_budget_stream_gives_same_result():
     n = 2048 * 400 + 3
