@@ -29,7 +29,7 @@
  *     nothing.  Functions return a gs_status; nothing throws or aborts.
  *   - Device work runs on the current HIP device; pointers, streams and contexts passed to a
  *     call must belong to it.  The stateless entry points may be called from several host threads
- *     at once; a gs_stream_ctx must be used by one thread at a time.
+ *     at once; a gs_stream_ctx or gs_tier_ctx must be used by one thread at a time.
  *   - Input and output arrays of one call must not overlap each other, except where a call
  *     states that an output may be its own input.
  *   - Results do not depend on how a range is partitioned: applying the step to [a,b) and
@@ -51,7 +51,8 @@ typedef enum {
     GS_ERR_INVALID_ARG = -1, /* null pointer, bad range, k out of [1,GS_MAX_K], bad hyper-parameter, misalignment */
     GS_ERR_WORKSPACE = -2,   /* workspace missing or smaller than gs_sqnorm_workspace_bytes() */
     GS_ERR_HIP = -3,         /* a HIP runtime call failed; see gs_last_hip_error() */
-    GS_ERR_NOMEM = -4        /* host or device allocation failed */
+    GS_ERR_NOMEM = -4,       /* host or device allocation failed */
+    GS_ERR_IO = -5           /* a file read or write of the file tier failed; see gs_tier_ctx_error() */
 } gs_status;
 
 /* Largest number of micro-batch gradient buffers one call accepts. */
@@ -278,6 +279,61 @@ gs_status gs_stream_layer_step(gs_stream_ctx *ctx, float *h_p, float *h_m, float
 
 /* Blocks until everything enqueued on the context has finished (including the downloads). */
 gs_status gs_stream_ctx_sync(gs_stream_ctx *ctx);
+
+/* ------------------------------------------------------------------------------------------
+ * Three-tier step: file (SSD) <-> pinned host <-> device.  The paper keeps optimizer states on
+ * SSD and pipelines, per layer, states SSD->CPU | step | states CPU->SSD (Sec. 4.3), with a
+ * storage ratio deciding which share of the states stays in CPU memory instead (Sec. 4.5).
+ * A layer's fp32 p, m, v are split at element n_host: [0,n_host) in pinned host memory,
+ * [n_host,n) in three files.  n_host = n is gs_stream_layer_step; n_host = 0 keeps everything
+ * in the files.
+ * ------------------------------------------------------------------------------------------ */
+
+typedef struct gs_tier_ctx gs_tier_ctx;
+
+typedef struct {
+    float *h_p, *h_m, *h_v;            /* pinned host fp32, elements [0,n_host); may be NULL if n_host == 0 */
+    int64_t n_host;                    /* 0 <= n_host <= n */
+    int fd_p, fd_m, fd_v;              /* open descriptors (read+write); ignored if n_host == n */
+    int64_t off_p, off_m, off_v;       /* byte offset of element n_host in each file; element i >= n_host
+                                          is the float at off + 4*(i - n_host) */
+} gs_tier_layer;
+
+/*
+ * Creates a context: a gs_stream_ctx (three streams, `slots` device staging slots of
+ * 3 x chunk_elems fp32), `slots` bounce slots of the same size in pinned host memory (each array
+ * starts on a 4 KB boundary), and one writer thread.  Same argument limits as
+ * gs_stream_ctx_create; GS_ERR_NOMEM if device or pinned memory cannot be had.
+ */
+gs_status gs_tier_ctx_create(gs_tier_ctx **out, int64_t chunk_elems, int slots);
+
+/*
+ * Applies the same update as gs_accum_adamw to all n elements of the layer described by *L.
+ * The host share is enqueued like gs_stream_layer_step.  The file share is walked in chunks of
+ * chunk_elems: the CALLING thread reads p/m/v of a chunk into a bounce slot (waiting, if need
+ * be, until the writer has released that slot), enqueues upload -> kernel -> download, and the
+ * writer thread writes the slot back to the same file offsets once the download has finished.
+ * The call returns when the last chunk has been read and enqueued -- not when it has been
+ * written; host arrays, files and device tensors must stay untouched until gs_tier_ctx_sync.
+ * Results are bit-identical to gs_accum_adamw on a device copy of the same states, for every
+ * n_host and chunk size.  Other arguments as for gs_stream_layer_step.  The files must hold the
+ * whole range (a short file is GS_ERR_IO).  Descriptors opened with O_DIRECT are the caller's
+ * business: offsets, n_host*4, chunk_elems*4 and (n-n_host)*4 then have to be multiples of the
+ * device's block size.  The descriptors are not closed.
+ * One thread at a time per context.  After any failure of the file tier the context stays
+ * failed: this call and gs_tier_ctx_sync return that status, gs_tier_ctx_error its text.
+ */
+gs_status gs_tier_layer_step(gs_tier_ctx *ctx, const gs_tier_layer *L, uint16_t *d_w_bf16,
+                             const uint16_t *const *d_grads, int k, int64_t n,
+                             const gs_adamw_hparams *hp, const double *d_sqnorm, void *producer_stream);
+
+/* Blocks until every enqueued chunk has been computed, downloaded and written to its file
+ * (the page cache counts as written; fsync is the caller's call). */
+gs_status gs_tier_ctx_sync(gs_tier_ctx *ctx);
+gs_status gs_tier_ctx_destroy(gs_tier_ctx *ctx); /* syncs, stops the writer, frees everything */
+/* Text of the context's first file-tier failure ("" if none), e.g. "pwrite(m): No space left on
+ * device".  The pointer is valid until the calling thread's next call of this function. */
+const char *gs_tier_ctx_error(gs_tier_ctx *ctx);
 
 /* Page-locked host memory without power-of-two padding (Sec. 5 notes that a framework's
  * pinned allocator may round each buffer up to a power of two; host-resident optimizer

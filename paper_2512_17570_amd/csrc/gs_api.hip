@@ -321,6 +321,7 @@ const char *gs_strerror(gs_status s)
     case GS_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case GS_ERR_HIP: return "HIP runtime error";
     case GS_ERR_NOMEM: return "out of memory";
+    case GS_ERR_IO: return "file read or write failed";
     }
     return "unknown status";
 }

@@ -18,21 +18,10 @@
 #include <vector>
 
 #include "gs_internal.h"
+#include "gs_stream_internal.h"
 
 using namespace gs;
 
-struct gs_stream_ctx {
-    int device = 0;
-    int64_t chunk = 0;
-    int slots = 0;
-    int64_t slot_elems = 0;                 // chunk + 8 (room for the (b mod 8) offset)
-    hipStream_t s_h2d = nullptr, s_comp = nullptr, s_d2h = nullptr;
-    float *pool = nullptr;                  // slots * 3 * slot_elems floats
-    std::vector<hipEvent_t> ev_h2d, ev_comp, ev_d2h;
-    std::vector<char> used;                 // slot has a pending/finished download recorded
-    hipEvent_t ev_producer = nullptr;
-    int64_t next_chunk = 0;                 // running chunk counter across calls -> slot rotation
-};
 
 static void destroy_partial(gs_stream_ctx *c)
 {
@@ -56,6 +45,90 @@ static void destroy_partial(gs_stream_ctx *c)
             return s_;                             \
         }                                          \
     } while (0)
+
+namespace gs {
+
+gs_status stream_validate(const gs_stream_ctx *c, const uint16_t *d_w_bf16, const uint16_t *const *d_grads, int k,
+                          int64_t n, const gs_adamw_hparams *hp, const double *d_sqnorm)
+{
+    if (!c || !d_w_bf16) return GS_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(d_w_bf16) & 15u) return GS_ERR_INVALID_ARG;
+    gs_status st = validate_grads(d_grads, k);
+    if (st != GS_OK) return st;
+    if (n < 0) return GS_ERR_INVALID_ARG;
+    st = validate_hparams(hp);
+    if (st != GS_OK) return st;
+    if (d_sqnorm && (reinterpret_cast<uintptr_t>(d_sqnorm) & 7u)) return GS_ERR_INVALID_ARG;
+    return GS_OK;
+}
+
+gs_status stream_begin_layer(gs_stream_ctx *c, StepArgs &A, uint16_t *d_w_bf16, const uint16_t *const *d_grads, int k,
+                             const gs_adamw_hparams *hp, const double *d_sqnorm, void *producer_stream)
+{
+    int cur = -1;
+    GS_TRY(hipGetDevice(&cur), "hipGetDevice");
+    if (cur != c->device) return GS_ERR_INVALID_ARG;   // the context's streams and slots live on another GPU
+
+    // gradients and the norm come from the caller's stream
+    GS_TRY(hipEventRecord(c->ev_producer, static_cast<hipStream_t>(producer_stream)), "hipEventRecord(producer)");
+    GS_TRY(hipStreamWaitEvent(c->s_comp, c->ev_producer, 0), "hipStreamWaitEvent(producer)");
+
+    memset(&A, 0, sizeof A);
+    A.w = d_w_bf16;
+    for (int j = 0; j < k; ++j) A.gt.g[j] = d_grads[j];
+    A.k = k;
+    A.c = make_consts(*hp);
+    A.max_norm = hp->max_grad_norm;
+    A.d_sqnorm = d_sqnorm;
+    return GS_OK;
+}
+
+gs_status stream_chunk(gs_stream_ctx *c, StepArgs &A, float *src_p, float *src_m, float *src_v, int64_t b, int64_t e,
+                       int *slot_out)
+{
+    const int64_t len = e - b;
+    const int slot = (int)(c->next_chunk % c->slots);
+    c->next_chunk++;
+    if (slot_out) *slot_out = slot;
+    const int64_t pad = b & 7;
+    float *sp = c->pool + (size_t)slot * 3u * (size_t)c->slot_elems;
+    float *sm = sp + c->slot_elems;
+    float *sv = sm + c->slot_elems;
+    const size_t bytes = (size_t)len * sizeof(float);
+
+    // upload: wait until the slot's previous download has drained
+    if (c->used[slot]) GS_TRY(hipStreamWaitEvent(c->s_h2d, c->ev_d2h[slot], 0), "hipStreamWaitEvent(slot free)");
+    GS_TRY(hipMemcpyAsync(sp + pad, src_p, bytes, hipMemcpyHostToDevice, c->s_h2d), "hipMemcpyAsync(H2D p)");
+    GS_TRY(hipMemcpyAsync(sm + pad, src_m, bytes, hipMemcpyHostToDevice, c->s_h2d), "hipMemcpyAsync(H2D m)");
+    GS_TRY(hipMemcpyAsync(sv + pad, src_v, bytes, hipMemcpyHostToDevice, c->s_h2d), "hipMemcpyAsync(H2D v)");
+    GS_TRY(hipEventRecord(c->ev_h2d[slot], c->s_h2d), "hipEventRecord(h2d)");
+
+    // compute: base pointers chosen so that base[i] is element i of the layer
+    GS_TRY(hipStreamWaitEvent(c->s_comp, c->ev_h2d[slot], 0), "hipStreamWaitEvent(h2d)");
+    const intptr_t shift = (intptr_t)(pad - b) * (intptr_t)sizeof(float);
+    A.po = reinterpret_cast<float *>(reinterpret_cast<intptr_t>(sp) + shift);
+    A.mo = reinterpret_cast<float *>(reinterpret_cast<intptr_t>(sm) + shift);
+    A.vo = reinterpret_cast<float *>(reinterpret_cast<intptr_t>(sv) + shift);
+    A.p = A.po;
+    A.m = A.mo;
+    A.v = A.vo;
+    A.begin = b;
+    A.end = e;
+    hipError_t le = launch_accum_adamw(A, c->s_comp);
+    if (le != hipSuccess) return hip_fail(le, "streamed step launch");
+    GS_TRY(hipEventRecord(c->ev_comp[slot], c->s_comp), "hipEventRecord(compute)");
+
+    // download
+    GS_TRY(hipStreamWaitEvent(c->s_d2h, c->ev_comp[slot], 0), "hipStreamWaitEvent(compute)");
+    GS_TRY(hipMemcpyAsync(src_p, sp + pad, bytes, hipMemcpyDeviceToHost, c->s_d2h), "hipMemcpyAsync(D2H p)");
+    GS_TRY(hipMemcpyAsync(src_m, sm + pad, bytes, hipMemcpyDeviceToHost, c->s_d2h), "hipMemcpyAsync(D2H m)");
+    GS_TRY(hipMemcpyAsync(src_v, sv + pad, bytes, hipMemcpyDeviceToHost, c->s_d2h), "hipMemcpyAsync(D2H v)");
+    GS_TRY(hipEventRecord(c->ev_d2h[slot], c->s_d2h), "hipEventRecord(d2h)");
+    c->used[slot] = 1;
+    return GS_OK;
+}
+
+}  // namespace gs
 
 extern "C" {
 
@@ -132,75 +205,20 @@ gs_status gs_stream_layer_step(gs_stream_ctx *c, float *h_p, float *h_m, float *
                                const gs_adamw_hparams *hp, const double *d_sqnorm,
                                void *producer_stream)
 {
-    if (!c || !h_p || !h_m || !h_v || !d_w_bf16) return GS_ERR_INVALID_ARG;
+    if (!c || !h_p || !h_m || !h_v) return GS_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(h_p) | reinterpret_cast<uintptr_t>(h_m) | reinterpret_cast<uintptr_t>(h_v)) & 3u)
         return GS_ERR_INVALID_ARG;
-    if (reinterpret_cast<uintptr_t>(d_w_bf16) & 15u) return GS_ERR_INVALID_ARG;
-    gs_status st = validate_grads(d_grads, k);
+    gs_status st = stream_validate(c, d_w_bf16, d_grads, k, n, hp, d_sqnorm);
     if (st != GS_OK) return st;
-    if (n < 0) return GS_ERR_INVALID_ARG;
-    st = validate_hparams(hp);
-    if (st != GS_OK) return st;
-    if (d_sqnorm && (reinterpret_cast<uintptr_t>(d_sqnorm) & 7u)) return GS_ERR_INVALID_ARG;
     if (n == 0) return GS_OK;
 
-    int cur = -1;
-    GS_TRY(hipGetDevice(&cur), "hipGetDevice");
-    if (cur != c->device) return GS_ERR_INVALID_ARG;   // the context's streams and slots live on another GPU
-
-    // gradients and the norm come from the caller's stream
-    GS_TRY(hipEventRecord(c->ev_producer, static_cast<hipStream_t>(producer_stream)), "hipEventRecord(producer)");
-    GS_TRY(hipStreamWaitEvent(c->s_comp, c->ev_producer, 0), "hipStreamWaitEvent(producer)");
-
     StepArgs A;
-    memset(&A, 0, sizeof A);
-    A.w = d_w_bf16;
-    for (int j = 0; j < k; ++j) A.gt.g[j] = d_grads[j];
-    A.k = k;
-    A.c = make_consts(*hp);
-    A.max_norm = hp->max_grad_norm;
-    A.d_sqnorm = d_sqnorm;
-
+    st = stream_begin_layer(c, A, d_w_bf16, d_grads, k, hp, d_sqnorm, producer_stream);
+    if (st != GS_OK) return st;
     for (int64_t b = 0; b < n; b += c->chunk) {
         const int64_t e = (b + c->chunk < n) ? b + c->chunk : n;
-        const int64_t len = e - b;
-        const int slot = (int)(c->next_chunk % c->slots);
-        c->next_chunk++;
-        const int64_t pad = b & 7;
-        float *sp = c->pool + (size_t)slot * 3u * (size_t)c->slot_elems;
-        float *sm = sp + c->slot_elems;
-        float *sv = sm + c->slot_elems;
-        const size_t bytes = (size_t)len * sizeof(float);
-
-        // upload: wait until the slot's previous download has drained
-        if (c->used[slot]) GS_TRY(hipStreamWaitEvent(c->s_h2d, c->ev_d2h[slot], 0), "hipStreamWaitEvent(slot free)");
-        GS_TRY(hipMemcpyAsync(sp + pad, h_p + b, bytes, hipMemcpyHostToDevice, c->s_h2d), "hipMemcpyAsync(H2D p)");
-        GS_TRY(hipMemcpyAsync(sm + pad, h_m + b, bytes, hipMemcpyHostToDevice, c->s_h2d), "hipMemcpyAsync(H2D m)");
-        GS_TRY(hipMemcpyAsync(sv + pad, h_v + b, bytes, hipMemcpyHostToDevice, c->s_h2d), "hipMemcpyAsync(H2D v)");
-        GS_TRY(hipEventRecord(c->ev_h2d[slot], c->s_h2d), "hipEventRecord(h2d)");
-
-        // compute: base pointers chosen so that base[i] is element i of the layer
-        GS_TRY(hipStreamWaitEvent(c->s_comp, c->ev_h2d[slot], 0), "hipStreamWaitEvent(h2d)");
-        const intptr_t shift = (intptr_t)(pad - b) * (intptr_t)sizeof(float);
-        A.po = reinterpret_cast<float *>(reinterpret_cast<intptr_t>(sp) + shift);
-        A.mo = reinterpret_cast<float *>(reinterpret_cast<intptr_t>(sm) + shift);
-        A.vo = reinterpret_cast<float *>(reinterpret_cast<intptr_t>(sv) + shift);
-        A.p = A.po;
-        A.m = A.mo;
-        A.v = A.vo;
-        A.begin = b;
-        A.end = e;
-        hipError_t le = launch_accum_adamw(A, c->s_comp);
-        if (le != hipSuccess) return hip_fail(le, "gs_stream_layer_step launch");
-        GS_TRY(hipEventRecord(c->ev_comp[slot], c->s_comp), "hipEventRecord(compute)");
-
-        // download
-        GS_TRY(hipStreamWaitEvent(c->s_d2h, c->ev_comp[slot], 0), "hipStreamWaitEvent(compute)");
-        GS_TRY(hipMemcpyAsync(h_p + b, sp + pad, bytes, hipMemcpyDeviceToHost, c->s_d2h), "hipMemcpyAsync(D2H p)");
-        GS_TRY(hipMemcpyAsync(h_m + b, sm + pad, bytes, hipMemcpyDeviceToHost, c->s_d2h), "hipMemcpyAsync(D2H m)");
-        GS_TRY(hipMemcpyAsync(h_v + b, sv + pad, bytes, hipMemcpyDeviceToHost, c->s_d2h), "hipMemcpyAsync(D2H v)");
-        GS_TRY(hipEventRecord(c->ev_d2h[slot], c->s_d2h), "hipEventRecord(d2h)");
-        c->used[slot] = 1;
+        st = stream_chunk(c, A, h_p + b, h_m + b, h_v + b, b, e, nullptr);
+        if (st != GS_OK) return st;
     }
     return GS_OK;
 }

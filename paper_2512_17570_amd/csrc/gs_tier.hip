@@ -1,0 +1,373 @@
+// gs_tier.hip -- three-tier step: file (SSD) <-> pinned host <-> HBM.
+//
+// The paper keeps optimizer states on SSD and, per layer, runs: states SSD->CPU, step, states
+// CPU->SSD, each stage overlapped with its neighbours (Sec. 4.3); a storage ratio decides which
+// share of the states stays in CPU memory instead (Sec. 4.5).  Here a layer's fp32 p/m/v are
+// split the same way: elements [0,n_host) in pinned host memory, elements [n_host,n) in files.
+// The host share goes through the host<->HBM pipeline directly.  The file share is walked in
+// chunks; for chunk c the calling thread reads p/m/v into a pinned bounce slot and enqueues
+// upload -> step kernel -> download on the pipeline's three streams, and a writer thread waits
+// for the download's event and writes the slot back to the files.  Reading chunk c+1 overlaps
+// the GPU work of chunk c and the write-back of chunk c-1.
+//
+// Every element goes through the same kernel with the same absolute-index grouping as the
+// resident step, so the result is bit-identical for any n_host and chunk size.
+#include <hip/hip_runtime.h>
+
+#include <cerrno>
+#include <condition_variable>
+#include <cstdio>
+#include <cstring>
+#include <deque>
+#include <mutex>
+#include <new>
+#include <string>
+#include <thread>
+#include <unistd.h>
+#include <vector>
+
+#include "gs_internal.h"
+#include "gs_stream_internal.h"
+
+using namespace gs;
+
+namespace {
+
+struct WriteJob {
+    int slot;
+    int64_t len;            // elements
+    int fd[3];
+    int64_t off[3];         // byte offsets
+};
+
+// Whole-buffer pread / pwrite (short transfers are continued; EOF on read is an error).
+bool read_all(int fd, void *buf, size_t bytes, int64_t off, int *err)
+{
+    char *p = static_cast<char *>(buf);
+    while (bytes > 0) {
+        ssize_t r = pread(fd, p, bytes, (off_t)off);
+        if (r < 0) {
+            if (errno == EINTR) continue;
+            *err = errno;
+            return false;
+        }
+        if (r == 0) {
+            *err = ENODATA;   // file shorter than the layer
+            return false;
+        }
+        p += r;
+        off += r;
+        bytes -= (size_t)r;
+    }
+    return true;
+}
+
+bool write_all(int fd, const void *buf, size_t bytes, int64_t off, int *err)
+{
+    const char *p = static_cast<const char *>(buf);
+    while (bytes > 0) {
+        ssize_t r = pwrite(fd, p, bytes, (off_t)off);
+        if (r < 0) {
+            if (errno == EINTR) continue;
+            *err = errno;
+            return false;
+        }
+        if (r == 0) {
+            *err = EIO;
+            return false;
+        }
+        p += r;
+        off += r;
+        bytes -= (size_t)r;
+    }
+    return true;
+}
+
+// p, m and v of one chunk move concurrently (two helper threads + the caller); if a thread cannot
+// be started its transfer runs on the caller instead.  Returns the index of the first array that
+// failed (errno in *err), or -1.
+int move3(bool write, const int fd[3], float *const buf[3], size_t bytes, const int64_t off[3], int *err)
+{
+    int e[3] = {0, 0, 0};
+    bool ok[3] = {true, true, true};
+    auto one = [&](int a) {
+        ok[a] = write ? write_all(fd[a], buf[a], bytes, off[a], &e[a]) : read_all(fd[a], buf[a], bytes, off[a], &e[a]);
+    };
+    std::thread th[2];
+    bool started[2] = {false, false};
+    for (int a = 0; a < 2; ++a) {
+        try {
+            th[a] = std::thread(one, a + 1);
+            started[a] = true;
+        } catch (...) {
+            started[a] = false;
+        }
+    }
+    one(0);
+    for (int a = 0; a < 2; ++a) {
+        if (started[a]) th[a].join();
+        else one(a + 1);
+    }
+    for (int a = 0; a < 3; ++a)
+        if (!ok[a]) {
+            *err = e[a];
+            return a;
+        }
+    return -1;
+}
+
+}  // namespace
+
+struct gs_tier_ctx {
+    gs_stream_ctx *sc = nullptr;
+    int device = 0;
+    int slots = 0;
+    int64_t chunk = 0;
+    int64_t bounce_elems = 0;               // per-array stride of a bounce slot (multiple of 1024 floats)
+    float *bounce = nullptr;                // pinned host: slots * 3 * bounce_elems floats
+    std::vector<hipEvent_t> ev_done;        // per bounce slot: its chunk's download has finished
+
+    std::mutex mu;
+    std::condition_variable cv;
+    std::deque<WriteJob> jobs;              // guarded by mu
+    std::vector<char> busy;                 // bounce slot holds data not yet written back (guarded by mu)
+    bool writer_active = false;             // the writer is inside a job (guarded by mu)
+    bool stop = false;                      // guarded by mu
+    gs_status err = GS_OK;                  // first failure of the file tier (guarded by mu)
+    std::string err_text;                   // guarded by mu
+    std::thread writer;
+    bool writer_started = false;
+
+    float *slot_ptr(int slot, int which) const
+    {
+        return bounce + ((size_t)slot * 3u + (size_t)which) * (size_t)bounce_elems;
+    }
+    void fail(gs_status st, const char *what, int err_no)
+    {
+        std::lock_guard<std::mutex> g(mu);
+        if (err == GS_OK) {
+            err = st;
+            err_text = what;
+            if (err_no) {
+                err_text += ": ";
+                err_text += strerror(err_no);
+            }
+        }
+    }
+};
+
+static void writer_main(gs_tier_ctx *t)
+{
+    (void)hipSetDevice(t->device);
+    for (;;) {
+        WriteJob j;
+        {
+            std::unique_lock<std::mutex> lk(t->mu);
+            t->cv.wait(lk, [&] { return t->stop || !t->jobs.empty(); });
+            if (t->jobs.empty()) return;    // stop requested and nothing left
+            j = t->jobs.front();
+            t->jobs.pop_front();
+            t->writer_active = true;
+        }
+        // recorded on the download stream before the job was queued; nobody records it again
+        // until this job has released the slot
+        hipError_t e = hipEventSynchronize(t->ev_done[j.slot]);
+        if (e != hipSuccess) {
+            t->fail(GS_ERR_HIP, hipGetErrorString(e), 0);
+        } else {
+            float *const buf[3] = {t->slot_ptr(j.slot, 0), t->slot_ptr(j.slot, 1), t->slot_ptr(j.slot, 2)};
+            int werr = 0;
+            const int bad = move3(true, j.fd, buf, (size_t)j.len * sizeof(float), j.off, &werr);
+            static const char *const names[3] = {"pwrite(p)", "pwrite(m)", "pwrite(v)"};
+            if (bad >= 0) t->fail(GS_ERR_IO, names[bad], werr);
+        }
+        {
+            std::lock_guard<std::mutex> g(t->mu);
+            t->busy[j.slot] = 0;
+            t->writer_active = false;
+        }
+        t->cv.notify_all();
+    }
+}
+
+static void tier_free(gs_tier_ctx *t)
+{
+    if (!t) return;
+    if (t->writer_started) {
+        {
+            std::lock_guard<std::mutex> g(t->mu);
+            t->stop = true;
+        }
+        t->cv.notify_all();
+        t->writer.join();
+    }
+    if (t->sc) (void)gs_stream_ctx_destroy(t->sc);
+    for (auto e : t->ev_done)
+        if (e) (void)hipEventDestroy(e);
+    if (t->bounce) (void)hipHostFree(t->bounce);
+    delete t;
+}
+
+extern "C" {
+
+gs_status gs_tier_ctx_create(gs_tier_ctx **out, int64_t chunk_elems, int slots)
+{
+    if (!out) return GS_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (chunk_elems < 1 || slots < 2 || slots > 64) return GS_ERR_INVALID_ARG;
+    if (chunk_elems > ((int64_t)1 << 34)) return GS_ERR_INVALID_ARG;
+
+    gs_tier_ctx *t = new (std::nothrow) gs_tier_ctx();
+    if (!t) return GS_ERR_NOMEM;
+    gs_status st = gs_stream_ctx_create(&t->sc, chunk_elems, slots);
+    if (st != GS_OK) {
+        t->sc = nullptr;
+        tier_free(t);
+        return st;
+    }
+    t->device = t->sc->device;
+    t->slots = slots;
+    t->chunk = chunk_elems;
+    t->bounce_elems = ((chunk_elems + 1023) / 1024) * 1024;   // every array starts on a 4 KB boundary
+    t->busy.assign(slots, 0);
+    const size_t bytes = (size_t)slots * 3u * (size_t)t->bounce_elems * sizeof(float);
+    t->bounce = static_cast<float *>(gs_pinned_alloc(bytes));
+    if (!t->bounce) {
+        tier_free(t);
+        return GS_ERR_NOMEM;
+    }
+    t->ev_done.assign(slots, nullptr);
+    for (int i = 0; i < slots; ++i) {
+        hipError_t e = hipEventCreateWithFlags(&t->ev_done[i], hipEventDisableTiming);
+        if (e != hipSuccess) {
+            t->ev_done[i] = nullptr;
+            tier_free(t);
+            return hip_fail(e, "hipEventCreateWithFlags");
+        }
+    }
+    try {
+        t->writer = std::thread(writer_main, t);
+        t->writer_started = true;
+    } catch (...) {
+        tier_free(t);
+        return GS_ERR_NOMEM;
+    }
+    *out = t;
+    return GS_OK;
+}
+
+gs_status gs_tier_ctx_sync(gs_tier_ctx *t)
+{
+    if (!t) return GS_ERR_INVALID_ARG;
+    {
+        std::unique_lock<std::mutex> lk(t->mu);
+        t->cv.wait(lk, [&] { return t->jobs.empty() && !t->writer_active; });
+    }
+    gs_status st = gs_stream_ctx_sync(t->sc);
+    std::lock_guard<std::mutex> g(t->mu);
+    return t->err != GS_OK ? t->err : st;
+}
+
+gs_status gs_tier_ctx_destroy(gs_tier_ctx *t)
+{
+    if (!t) return GS_ERR_INVALID_ARG;
+    gs_status st = gs_tier_ctx_sync(t);
+    tier_free(t);
+    return st;
+}
+
+const char *gs_tier_ctx_error(gs_tier_ctx *t)
+{
+    static thread_local std::string copy;
+    if (!t) return "";
+    std::lock_guard<std::mutex> g(t->mu);
+    copy = t->err_text;
+    return copy.c_str();
+}
+
+gs_status gs_tier_layer_step(gs_tier_ctx *t, const gs_tier_layer *L, uint16_t *d_w_bf16,
+                             const uint16_t *const *d_grads, int k, int64_t n,
+                             const gs_adamw_hparams *hp, const double *d_sqnorm, void *producer_stream)
+{
+    if (!t || !L) return GS_ERR_INVALID_ARG;
+    if (n < 0 || L->n_host < 0 || L->n_host > n) return GS_ERR_INVALID_ARG;
+    if (L->n_host > 0) {
+        if (!L->h_p || !L->h_m || !L->h_v) return GS_ERR_INVALID_ARG;
+        if ((reinterpret_cast<uintptr_t>(L->h_p) | reinterpret_cast<uintptr_t>(L->h_m) |
+             reinterpret_cast<uintptr_t>(L->h_v)) & 3u)
+            return GS_ERR_INVALID_ARG;
+    }
+    if (L->n_host < n) {
+        if (L->fd_p < 0 || L->fd_m < 0 || L->fd_v < 0) return GS_ERR_INVALID_ARG;
+        if (L->off_p < 0 || L->off_m < 0 || L->off_v < 0) return GS_ERR_INVALID_ARG;
+    }
+    gs_status st = stream_validate(t->sc, d_w_bf16, d_grads, k, n, hp, d_sqnorm);
+    if (st != GS_OK) return st;
+    {
+        std::lock_guard<std::mutex> g(t->mu);
+        if (t->err != GS_OK) return t->err;     // a failed context stays failed
+    }
+    if (n == 0) return GS_OK;
+
+    gs_stream_ctx *c = t->sc;
+    StepArgs A;
+    st = stream_begin_layer(c, A, d_w_bf16, d_grads, k, hp, d_sqnorm, producer_stream);
+    if (st != GS_OK) return st;
+
+    // host share: straight through the host<->HBM pipeline (nothing here blocks)
+    for (int64_t b = 0; b < L->n_host; b += c->chunk) {
+        const int64_t e = (b + c->chunk < L->n_host) ? b + c->chunk : L->n_host;
+        st = stream_chunk(c, A, L->h_p + b, L->h_m + b, L->h_v + b, b, e, nullptr);
+        if (st != GS_OK) return st;
+    }
+
+    // file share
+    const int fd[3] = {L->fd_p, L->fd_m, L->fd_v};
+    const int64_t base[3] = {L->off_p, L->off_m, L->off_v};
+    for (int64_t b = L->n_host; b < n; b += c->chunk) {
+        const int64_t e = (b + c->chunk < n) ? b + c->chunk : n;
+        const int64_t len = e - b;
+        const int slot = (int)(c->next_chunk % c->slots);    // the slot stream_chunk is about to take
+        {
+            std::unique_lock<std::mutex> lk(t->mu);
+            t->cv.wait(lk, [&] { return !t->busy[slot]; });
+            if (t->err != GS_OK) return t->err;
+        }
+        int64_t off[3];
+        for (int a = 0; a < 3; ++a) off[a] = base[a] + (b - L->n_host) * (int64_t)sizeof(float);
+        float *const buf[3] = {t->slot_ptr(slot, 0), t->slot_ptr(slot, 1), t->slot_ptr(slot, 2)};
+        int rerr = 0;
+        const int bad = move3(false, fd, buf, (size_t)len * sizeof(float), off, &rerr);
+        if (bad >= 0) {
+            static const char *const names[3] = {"pread(p)", "pread(m)", "pread(v)"};
+            t->fail(GS_ERR_IO, names[bad], rerr);
+            return GS_ERR_IO;
+        }
+        int got = -1;
+        st = stream_chunk(c, A, buf[0], buf[1], buf[2], b, e, &got);
+        if (st == GS_OK) {
+            hipError_t he = hipEventRecord(t->ev_done[got], c->s_d2h);
+            if (he != hipSuccess) st = hip_fail(he, "hipEventRecord(bounce slot)");
+        }
+        if (st != GS_OK) {
+            t->fail(st, "enqueue of a file chunk failed", 0);
+            return st;
+        }
+        WriteJob j;
+        j.slot = got;
+        j.len = len;
+        for (int a = 0; a < 3; ++a) {
+            j.fd[a] = fd[a];
+            j.off[a] = off[a];
+        }
+        {
+            std::lock_guard<std::mutex> g(t->mu);
+            t->busy[got] = 1;
+            t->jobs.push_back(j);
+        }
+        t->cv.notify_all();
+    }
+    return GS_OK;
+}
+
+}  // extern "C"

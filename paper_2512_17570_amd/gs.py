@@ -22,6 +22,7 @@ GS_ERR_INVALID_ARG = -1
 GS_ERR_WORKSPACE = -2
 GS_ERR_HIP = -3
 GS_ERR_NOMEM = -4
+GS_ERR_IO = -5
 GS_MAX_K = 32
 
 if not os.path.exists(LIB_PATH):
@@ -313,6 +314,65 @@ def gs_stream_layer_step(ctx, h_p, h_m, h_v, d_w_bf16, d_grads, n: int, hp, d_sq
     st = _lib.gs_stream_layer_step(ctx, _addr(h_p), _addr(h_m), _addr(h_v), _addr(d_w_bf16), tab,
                                    kk if k is None else k, n, _hp(hp), _addr(d_sqnorm), _stream(producer_stream))
     return _check(st, "gs_stream_layer_step", check)
+
+
+class gs_tier_layer(ctypes.Structure):
+    _fields_ = [("h_p", ctypes.c_void_p), ("h_m", ctypes.c_void_p), ("h_v", ctypes.c_void_p),
+                ("n_host", ctypes.c_int64),
+                ("fd_p", ctypes.c_int), ("fd_m", ctypes.c_int), ("fd_v", ctypes.c_int),
+                ("off_p", ctypes.c_int64), ("off_m", ctypes.c_int64), ("off_v", ctypes.c_int64)]
+
+
+_lib.gs_tier_ctx_create.argtypes = [ctypes.POINTER(ctypes.c_void_p), _i64, ctypes.c_int]
+_lib.gs_tier_ctx_create.restype = ctypes.c_int
+_lib.gs_tier_ctx_destroy.argtypes = [_vp]
+_lib.gs_tier_ctx_destroy.restype = ctypes.c_int
+_lib.gs_tier_ctx_sync.argtypes = [_vp]
+_lib.gs_tier_ctx_sync.restype = ctypes.c_int
+_lib.gs_tier_ctx_error.argtypes = [_vp]
+_lib.gs_tier_ctx_error.restype = ctypes.c_char_p
+_lib.gs_tier_layer_step.argtypes = [_vp, ctypes.POINTER(gs_tier_layer), _vp, _pp, ctypes.c_int, _i64, _vp, _vp, _vp]
+_lib.gs_tier_layer_step.restype = ctypes.c_int
+
+
+def gs_tier_ctx_create(chunk_elems: int, slots: int = 3, check: bool = True):
+    out = ctypes.c_void_p()
+    st = _lib.gs_tier_ctx_create(ctypes.byref(out), chunk_elems, slots)
+    if check:
+        _check(st, "gs_tier_ctx_create", True)
+        return out.value
+    return st, out.value
+
+
+def gs_tier_ctx_destroy(ctx, check: bool = True) -> int:
+    return _check(_lib.gs_tier_ctx_destroy(ctx), "gs_tier_ctx_destroy", check)
+
+
+def gs_tier_ctx_sync(ctx, check: bool = True) -> int:
+    return _check(_lib.gs_tier_ctx_sync(ctx), "gs_tier_ctx_sync", check)
+
+
+def gs_tier_ctx_error(ctx) -> str:
+    return (_lib.gs_tier_ctx_error(ctx) or b"").decode()
+
+
+def gs_tier_layer_step(ctx, h_p, h_m, h_v, n_host: int, fds, offsets, d_w_bf16, d_grads, n: int, hp,
+                       d_sqnorm=None, producer_stream=None, check: bool = True, k: int | None = None,
+                       layer: "gs_tier_layer | None" = None) -> int:
+    """fds = (fd_p, fd_m, fd_v) and offsets = (off_p, off_m, off_v) in bytes; `layer` passes a
+    ready-made descriptor (or None with check=False to exercise the rejection)."""
+    tab, kk = _table(d_grads) if d_grads is not None else (None, 0)
+    for j, g in enumerate(d_grads or ()):
+        _need(g, n, 2, f"d_grads[{j}]")
+    _need(d_w_bf16, n, 2, "d_w_bf16")
+    if layer is None and fds is not None:
+        for x, nm in ((h_p, "h_p"), (h_m, "h_m"), (h_v, "h_v")):
+            _need(x, n_host, 4, nm)
+        layer = gs_tier_layer(_addr(h_p), _addr(h_m), _addr(h_v), n_host, fds[0], fds[1], fds[2],
+                              offsets[0], offsets[1], offsets[2])
+    st = _lib.gs_tier_layer_step(ctx, ctypes.byref(layer) if layer is not None else None, _addr(d_w_bf16), tab,
+                                 kk if k is None else k, n, _hp(hp), _addr(d_sqnorm), _stream(producer_stream))
+    return _check(st, "gs_tier_layer_step", check)
 
 
 def gs_pinned_alloc(nbytes: int) -> int | None:

@@ -1,0 +1,174 @@
+// Implementation of the host-only HIP stand-in (see hip/hip_runtime_api.h in this folder).
+#include <hip/hip_runtime_api.h>
+
+#include <atomic>
+#include <chrono>
+#include <condition_variable>
+#include <cstdlib>
+#include <cstring>
+#include <deque>
+#include <mutex>
+#include <thread>
+
+struct hipmock_stream {
+    std::mutex mu;
+    std::condition_variable cv;
+    std::deque<std::function<void()>> q;
+    bool running = false, stop = false;
+    std::thread th;
+
+    hipmock_stream() : th([this] { loop(); }) {}
+    ~hipmock_stream()
+    {
+        {
+            std::lock_guard<std::mutex> g(mu);
+            stop = true;
+        }
+        cv.notify_all();
+        th.join();
+    }
+    void loop()
+    {
+        for (;;) {
+            std::function<void()> fn;
+            {
+                std::unique_lock<std::mutex> lk(mu);
+                cv.wait(lk, [&] { return stop || !q.empty(); });
+                if (q.empty()) return;
+                fn = std::move(q.front());
+                q.pop_front();
+                running = true;
+            }
+            fn();
+            {
+                std::lock_guard<std::mutex> g(mu);
+                running = false;
+            }
+            cv.notify_all();
+        }
+    }
+    void push(std::function<void()> fn)
+    {
+        {
+            std::lock_guard<std::mutex> g(mu);
+            q.push_back(std::move(fn));
+        }
+        cv.notify_all();
+    }
+    void drain()
+    {
+        std::unique_lock<std::mutex> lk(mu);
+        cv.wait(lk, [&] { return q.empty() && !running; });
+    }
+};
+
+struct hipmock_event {
+    std::mutex mu;
+    std::condition_variable cv;
+    uint64_t recorded = 0, completed = 0;
+    void wait_for(uint64_t target)
+    {
+        std::unique_lock<std::mutex> lk(mu);
+        cv.wait(lk, [&] { return completed >= target; });
+    }
+};
+
+static std::atomic<uint64_t> g_copies{0};
+static std::atomic<int> g_delay_us{0};
+
+void hipmock_enqueue(hipStream_t s, std::function<void()> fn)
+{
+    if (!s) {
+        fn();   // the null stream runs in place
+        return;
+    }
+    s->push(std::move(fn));
+}
+
+extern "C" {
+
+uint64_t hipmock_copy_count(void) { return g_copies.load(); }
+void hipmock_set_copy_delay_us(int us) { g_delay_us.store(us); }
+
+const char *hipGetErrorString(hipError_t e) { return e == hipSuccess ? "no error" : "mock error"; }
+hipError_t hipGetLastError(void) { return hipSuccess; }
+hipError_t hipGetDevice(int *dev) { *dev = 0; return hipSuccess; }
+hipError_t hipSetDevice(int) { return hipSuccess; }
+hipError_t hipDeviceGetAttribute(int *value, hipDeviceAttribute_t, int) { *value = 256; return hipSuccess; }
+
+hipError_t hipMalloc(void **ptr, size_t bytes)
+{
+    *ptr = aligned_alloc(256, (bytes + 255) / 256 * 256);
+    return *ptr ? hipSuccess : hipErrorOutOfMemory;
+}
+hipError_t hipFree(void *ptr) { free(ptr); return hipSuccess; }
+hipError_t hipHostMalloc(void **ptr, size_t bytes, unsigned)
+{
+    *ptr = aligned_alloc(4096, (bytes + 4095) / 4096 * 4096);
+    return *ptr ? hipSuccess : hipErrorOutOfMemory;
+}
+hipError_t hipHostFree(void *ptr) { free(ptr); return hipSuccess; }
+
+hipError_t hipStreamCreateWithFlags(hipStream_t *s, unsigned) { *s = new hipmock_stream(); return hipSuccess; }
+hipError_t hipExtStreamCreateWithCUMask(hipStream_t *s, uint32_t, const uint32_t *) { *s = new hipmock_stream(); return hipSuccess; }
+hipError_t hipStreamDestroy(hipStream_t s) { delete s; return hipSuccess; }
+hipError_t hipStreamSynchronize(hipStream_t s)
+{
+    if (s) s->drain();
+    return hipSuccess;
+}
+
+hipError_t hipEventCreateWithFlags(hipEvent_t *e, unsigned) { *e = new hipmock_event(); return hipSuccess; }
+hipError_t hipEventDestroy(hipEvent_t e) { delete e; return hipSuccess; }
+
+hipError_t hipEventRecord(hipEvent_t e, hipStream_t s)
+{
+    uint64_t seq;
+    {
+        std::lock_guard<std::mutex> g(e->mu);
+        seq = ++e->recorded;
+    }
+    hipmock_enqueue(s, [e, seq] {
+        {
+            std::lock_guard<std::mutex> g(e->mu);
+            if (e->completed < seq) e->completed = seq;
+        }
+        e->cv.notify_all();
+    });
+    return hipSuccess;
+}
+
+hipError_t hipStreamWaitEvent(hipStream_t s, hipEvent_t e, unsigned)
+{
+    uint64_t target;
+    {
+        std::lock_guard<std::mutex> g(e->mu);
+        target = e->recorded;   // the record that is current NOW, as HIP defines it
+    }
+    hipmock_enqueue(s, [e, target] { e->wait_for(target); });
+    return hipSuccess;
+}
+
+hipError_t hipEventSynchronize(hipEvent_t e)
+{
+    uint64_t target;
+    {
+        std::lock_guard<std::mutex> g(e->mu);
+        target = e->recorded;
+    }
+    e->wait_for(target);
+    return hipSuccess;
+}
+
+hipError_t hipMemcpyAsync(void *dst, const void *src, size_t bytes, hipMemcpyKind, hipStream_t s)
+{
+    hipmock_enqueue(s, [=] {
+        int d = g_delay_us.load();
+        if (d > 0) std::this_thread::sleep_for(std::chrono::microseconds(d));
+        memcpy(dst, src, bytes);
+        g_copies.fetch_add(1);
+    });
+    return hipSuccess;
+}
+
+}  // extern "C"

@@ -1,0 +1,286 @@
+// Host-only exercise of the streaming and file-tier pipelines against the HIP stand-in.
+// The step kernel is replaced by a trivial element-wise stand-in (the real arithmetic needs a GPU
+// and is checked by the GPU parity tests); what is checked here is the plumbing: every element
+// goes up, through the "kernel" exactly once and back to where it came from -- host array or file
+// offset -- for any chunk size, slot count and host/file split, and failures of the file tier
+// surface as GS_ERR_IO instead of a hang.  Built with -fsanitize=thread by the test that runs it.
+#include <hip/hip_runtime_api.h>
+
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <fcntl.h>
+#include <string>
+#include <unistd.h>
+#include <vector>
+
+#include "gs_internal.h"
+
+namespace gs {
+
+// stand-in "kernel": p' = p + 1, m' = 2 m, v' = v + g_0, w = low 16 bits of (i + k)
+hipError_t launch_accum_adamw(const StepArgs &A, hipStream_t stream)
+{
+    StepArgs a = A;
+    hipmock_enqueue(stream, [a] {
+        for (int64_t i = a.begin; i < a.end; ++i) {
+            a.po[i] = a.p[i] + 1.0f;
+            a.mo[i] = a.m[i] * 2.0f;
+            a.vo[i] = a.v[i] + (float)a.gt.g[0][i];
+            a.w[i] = (uint16_t)((i + a.k) & 0xffff);
+        }
+    });
+    return hipSuccess;
+}
+hipError_t launch_accum_adamw_spec(const StepArgs &, double *, size_t, double *, int, hipStream_t) { return hipErrorUnknown; }
+hipError_t launch_grad_sqnorm(const SqnormArgs &, size_t, double *, int, hipStream_t) { return hipErrorUnknown; }
+hipError_t launch_accum_add(const AccumAddArgs &, int, size_t, double *, int, hipStream_t) { return hipErrorUnknown; }
+
+}  // namespace gs
+
+static int g_fail = 0;
+#define CHECK(cond, ...)                                   \
+    do {                                                   \
+        if (!(cond)) {                                     \
+            printf("FAIL %s:%d: ", __FILE__, __LINE__);    \
+            printf(__VA_ARGS__);                           \
+            printf("\n");                                  \
+            ++g_fail;                                      \
+        }                                                  \
+    } while (0)
+
+static const gs_adamw_hparams HP = {1e-3f, 0.9f, 0.999f, 1e-8f, 0.01f, 1.0f, 3};
+
+struct Layer {
+    int64_t n;
+    std::vector<float> p0, m0, v0;          // initial states
+    std::vector<uint16_t> g, w;
+    explicit Layer(int64_t n_, unsigned seed) : n(n_), p0(n_), m0(n_), v0(n_), g(n_), w(n_, 0xdead)
+    {
+        srand(seed);
+        for (int64_t i = 0; i < n; ++i) {
+            p0[i] = (float)(rand() % 1000);
+            m0[i] = (float)(rand() % 1000);
+            v0[i] = (float)(rand() % 1000);
+            g[i] = (uint16_t)(rand() & 0x3ff);
+        }
+    }
+    // compares the states after `steps` applications of the stand-in
+    void check(const float *p, const float *m, const float *v, int64_t lo, int64_t hi, int64_t src_off, int steps,
+               const char *what) const
+    {
+        int64_t bad = 0;
+        for (int64_t i = lo; i < hi; ++i) {
+            float pe = p0[i], me = m0[i], ve = v0[i];
+            for (int s = 0; s < steps; ++s) {
+                pe += 1.0f;
+                me *= 2.0f;
+                ve += (float)g[i];
+            }
+            if (p[i - src_off] != pe || m[i - src_off] != me || v[i - src_off] != ve) ++bad;
+        }
+        CHECK(bad == 0, "%s: %lld of %lld elements wrong", what, (long long)bad, (long long)(hi - lo));
+    }
+    void check_w(int k, const char *what) const
+    {
+        int64_t bad = 0;
+        for (int64_t i = 0; i < n; ++i)
+            if (w[i] != (uint16_t)((i + k) & 0xffff)) ++bad;
+        CHECK(bad == 0, "%s: %lld working weights wrong", what, (long long)bad);
+    }
+};
+
+static void test_stream(int64_t n, int64_t chunk, int slots)
+{
+    Layer A(n, 1), B(n / 2 + 3, 2);
+    gs_stream_ctx *ctx = nullptr;
+    CHECK(gs_stream_ctx_create(&ctx, chunk, slots) == GS_OK, "create");
+    float *hp_[2][3];
+    Layer *Ls[2] = {&A, &B};
+    for (int l = 0; l < 2; ++l) {
+        const std::vector<float> *src[3] = {&Ls[l]->p0, &Ls[l]->m0, &Ls[l]->v0};
+        for (int a = 0; a < 3; ++a) {
+            hp_[l][a] = (float *)gs_pinned_alloc((size_t)Ls[l]->n * 4);
+            memcpy(hp_[l][a], src[a]->data(), (size_t)Ls[l]->n * 4);
+        }
+    }
+    for (int step = 1; step <= 2; ++step) {
+        for (int l = 0; l < 2; ++l) {
+            const uint16_t *gt[1] = {Ls[l]->g.data()};
+            CHECK(gs_stream_layer_step(ctx, hp_[l][0], hp_[l][1], hp_[l][2], Ls[l]->w.data(), gt, 1, Ls[l]->n, &HP, nullptr,
+                                       nullptr) == GS_OK, "layer step");
+        }
+        CHECK(gs_stream_ctx_sync(ctx) == GS_OK, "sync");
+        for (int l = 0; l < 2; ++l) {
+            Ls[l]->check(hp_[l][0], hp_[l][1], hp_[l][2], 0, Ls[l]->n, 0, step, "streamed");
+            Ls[l]->check_w(1, "streamed");
+        }
+    }
+    CHECK(gs_stream_ctx_destroy(ctx) == GS_OK, "destroy");
+    for (int l = 0; l < 2; ++l)
+        for (int a = 0; a < 3; ++a) gs_pinned_free(hp_[l][a]);
+}
+
+struct Files {
+    std::string path[3];
+    int fd[3];
+    Files(const std::string &dir, const char *tag, const Layer &L, int64_t n_host, int64_t header_bytes, int flags = O_RDWR)
+    {
+        const std::vector<float> *src[3] = {&L.p0, &L.m0, &L.v0};
+        for (int a = 0; a < 3; ++a) {
+            path[a] = dir + "/" + tag + "_" + "pmv"[a] + ".bin";
+            FILE *f = fopen(path[a].c_str(), "wb");
+            std::vector<char> hdr((size_t)header_bytes, (char)0x5a);
+            fwrite(hdr.data(), 1, hdr.size(), f);
+            fwrite(src[a]->data() + n_host, 4, (size_t)(L.n - n_host), f);
+            fwrite("TAIL", 1, 4, f);
+            fclose(f);
+            fd[a] = open(path[a].c_str(), flags);
+        }
+    }
+    ~Files()
+    {
+        for (int a = 0; a < 3; ++a) {
+            if (fd[a] >= 0) close(fd[a]);
+            unlink(path[a].c_str());
+        }
+    }
+    std::vector<float> load(int a, int64_t header_bytes, int64_t count, bool *frame_ok) const
+    {
+        std::vector<char> raw;
+        FILE *f = fopen(path[a].c_str(), "rb");
+        fseek(f, 0, SEEK_END);
+        raw.resize((size_t)ftell(f));
+        fseek(f, 0, SEEK_SET);
+        size_t got = fread(raw.data(), 1, raw.size(), f);
+        fclose(f);
+        *frame_ok = got == (size_t)(header_bytes + count * 4 + 4);
+        for (int64_t i = 0; i < header_bytes && *frame_ok; ++i) *frame_ok = raw[(size_t)i] == (char)0x5a;
+        if (*frame_ok) *frame_ok = memcmp(raw.data() + header_bytes + count * 4, "TAIL", 4) == 0;
+        std::vector<float> out((size_t)count);
+        if (*frame_ok) memcpy(out.data(), raw.data() + header_bytes, (size_t)count * 4);
+        return out;
+    }
+};
+
+static void test_tier(const std::string &dir, int64_t n, int64_t n_host, int64_t chunk, int slots)
+{
+    const int64_t header = 12;     // files start with bytes that must survive
+    Layer A(n, 11), B(n / 3 + 5, 12);
+    Layer *Ls[2] = {&A, &B};
+    int64_t nh[2] = {n_host, n_host > B.n ? B.n : n_host / 2};
+    gs_tier_ctx *ctx = nullptr;
+    CHECK(gs_tier_ctx_create(&ctx, chunk, slots) == GS_OK, "tier create");
+    float *host[2][3] = {{nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr}};
+    Files *files[2];
+    gs_tier_layer desc[2];
+    for (int l = 0; l < 2; ++l) {
+        const std::vector<float> *src[3] = {&Ls[l]->p0, &Ls[l]->m0, &Ls[l]->v0};
+        for (int a = 0; a < 3 && nh[l] > 0; ++a) {
+            host[l][a] = (float *)gs_pinned_alloc((size_t)nh[l] * 4);
+            memcpy(host[l][a], src[a]->data(), (size_t)nh[l] * 4);
+        }
+        files[l] = new Files(dir, l ? "B" : "A", *Ls[l], nh[l], header);
+        desc[l] = gs_tier_layer{host[l][0], host[l][1], host[l][2], nh[l], files[l]->fd[0], files[l]->fd[1],
+                                files[l]->fd[2], header, header, header};
+    }
+    for (int step = 1; step <= 2; ++step) {
+        for (int l = 0; l < 2; ++l) {
+            const uint16_t *gt[2] = {Ls[l]->g.data(), Ls[l]->g.data()};
+            CHECK(gs_tier_layer_step(ctx, &desc[l], Ls[l]->w.data(), gt, 2, Ls[l]->n, &HP, nullptr, nullptr) == GS_OK,
+                  "tier layer step: %s", gs_tier_ctx_error(ctx));
+        }
+        CHECK(gs_tier_ctx_sync(ctx) == GS_OK, "tier sync: %s", gs_tier_ctx_error(ctx));
+        for (int l = 0; l < 2; ++l) {
+            if (nh[l] > 0) Ls[l]->check(host[l][0], host[l][1], host[l][2], 0, nh[l], 0, step, "tier host share");
+            bool ok[3];
+            std::vector<float> fp = files[l]->load(0, header, Ls[l]->n - nh[l], &ok[0]);
+            std::vector<float> fm = files[l]->load(1, header, Ls[l]->n - nh[l], &ok[1]);
+            std::vector<float> fv = files[l]->load(2, header, Ls[l]->n - nh[l], &ok[2]);
+            CHECK(ok[0] && ok[1] && ok[2], "file framing (header / length / trailer) damaged");
+            if (ok[0] && ok[1] && ok[2])
+                Ls[l]->check(fp.data(), fm.data(), fv.data(), nh[l], Ls[l]->n, nh[l], step, "tier file share");
+            Ls[l]->check_w(2, "tier");
+        }
+    }
+    CHECK(gs_tier_ctx_destroy(ctx) == GS_OK, "tier destroy");
+    for (int l = 0; l < 2; ++l) {
+        delete files[l];
+        for (int a = 0; a < 3; ++a) gs_pinned_free(host[l][a]);
+    }
+}
+
+static void test_tier_failures(const std::string &dir)
+{
+    Layer A(5000, 21);
+    const uint16_t *gt[1] = {A.g.data()};
+    // a file shorter than the layer: the read fails, nothing hangs, the context stays failed
+    {
+        Layer shortL(3000, 21);
+        Files f(dir, "short", shortL, 0, 0);
+        gs_tier_ctx *ctx = nullptr;
+        CHECK(gs_tier_ctx_create(&ctx, 1024, 2) == GS_OK, "create");
+        gs_tier_layer d{nullptr, nullptr, nullptr, 0, f.fd[0], f.fd[1], f.fd[2], 0, 0, 0};
+        CHECK(gs_tier_layer_step(ctx, &d, A.w.data(), gt, 1, A.n, &HP, nullptr, nullptr) == GS_ERR_IO, "short file accepted");
+        CHECK(strstr(gs_tier_ctx_error(ctx), "pread") != nullptr, "error text: '%s'", gs_tier_ctx_error(ctx));
+        CHECK(gs_tier_ctx_sync(ctx) == GS_ERR_IO, "sync after failure");
+        CHECK(gs_tier_layer_step(ctx, &d, A.w.data(), gt, 1, 10, &HP, nullptr, nullptr) == GS_ERR_IO, "failed context reused");
+        CHECK(gs_tier_ctx_destroy(ctx) == GS_ERR_IO, "destroy after failure");
+    }
+    // descriptors that cannot be written: the writer thread reports it through sync
+    {
+        Files f(dir, "ro", A, 0, 0, O_RDONLY);
+        gs_tier_ctx *ctx = nullptr;
+        CHECK(gs_tier_ctx_create(&ctx, 1024, 2) == GS_OK, "create");
+        gs_tier_layer d{nullptr, nullptr, nullptr, 0, f.fd[0], f.fd[1], f.fd[2], 0, 0, 0};
+        gs_status st = gs_tier_layer_step(ctx, &d, A.w.data(), gt, 1, A.n, &HP, nullptr, nullptr);
+        CHECK(st == GS_OK || st == GS_ERR_IO, "unexpected status %d", (int)st);
+        CHECK(gs_tier_ctx_sync(ctx) == GS_ERR_IO, "write failure not reported");
+        CHECK(strstr(gs_tier_ctx_error(ctx), "pwrite") != nullptr, "error text: '%s'", gs_tier_ctx_error(ctx));
+        CHECK(gs_tier_ctx_destroy(ctx) == GS_ERR_IO, "destroy after failure");
+    }
+    // argument checks that need a live context
+    {
+        Files f(dir, "args", A, 0, 0);
+        gs_tier_ctx *ctx = nullptr;
+        CHECK(gs_tier_ctx_create(&ctx, 1024, 2) == GS_OK, "create");
+        gs_tier_layer d{nullptr, nullptr, nullptr, 0, f.fd[0], f.fd[1], f.fd[2], 0, 0, 0};
+        gs_tier_layer bad = d;
+        bad.n_host = A.n + 1;
+        CHECK(gs_tier_layer_step(ctx, &bad, A.w.data(), gt, 1, A.n, &HP, nullptr, nullptr) == GS_ERR_INVALID_ARG, "n_host > n");
+        bad = d;
+        bad.n_host = 10;   // host share without host pointers
+        CHECK(gs_tier_layer_step(ctx, &bad, A.w.data(), gt, 1, A.n, &HP, nullptr, nullptr) == GS_ERR_INVALID_ARG, "null host");
+        bad = d;
+        bad.fd_m = -1;
+        CHECK(gs_tier_layer_step(ctx, &bad, A.w.data(), gt, 1, A.n, &HP, nullptr, nullptr) == GS_ERR_INVALID_ARG, "bad fd");
+        bad = d;
+        bad.off_v = -4;
+        CHECK(gs_tier_layer_step(ctx, &bad, A.w.data(), gt, 1, A.n, &HP, nullptr, nullptr) == GS_ERR_INVALID_ARG, "bad offset");
+        CHECK(gs_tier_layer_step(ctx, &d, A.w.data(), gt, 0, A.n, &HP, nullptr, nullptr) == GS_ERR_INVALID_ARG, "k = 0");
+        CHECK(gs_tier_layer_step(ctx, &d, A.w.data(), gt, 1, 0, &HP, nullptr, nullptr) == GS_OK, "n = 0");
+        CHECK(gs_tier_ctx_sync(ctx) == GS_OK, "sync of an idle context");
+        CHECK(gs_tier_ctx_destroy(ctx) == GS_OK, "destroy");
+    }
+}
+
+int main(int argc, char **argv)
+{
+    if (argc < 2) {
+        printf("usage: %s <scratch dir>\n", argv[0]);
+        return 2;
+    }
+    const std::string dir = argv[1];
+    hipmock_set_copy_delay_us(50);   // let the three streams really overlap
+    test_stream(20000, 4096, 2);
+    test_stream(20000, 3001, 3);
+    test_stream(777, 100000, 2);
+    test_tier(dir, 30000, 0, 4096, 2);
+    test_tier(dir, 30000, 9999, 3001, 3);
+    test_tier(dir, 30000, 30000, 4096, 2);
+    test_tier(dir, 5000, 1, 100000, 2);
+    test_tier(dir, 30000, 29999, 1024, 4);
+    test_tier_failures(dir);
+    printf(g_fail ? "FAILED (%d)\n" : "PIPELINE OK\n", g_fail);
+    return g_fail ? 1 : 0;
+}

@@ -28,7 +28,8 @@ def test_header_symbols_all_exported():
             "gs_stream_ctx_create", "gs_stream_ctx_destroy", "gs_stream_ctx_sync", "gs_pinned_alloc",
             "gs_pinned_free", "gs_strerror", "gs_last_hip_error", "gs_grad_accum_sqnorm", "gs_adamw_from_acc",
             "gs_cu_stream_create", "gs_cu_stream_destroy", "gs_accum_adamw_oop", "gs_accum_adamw_spec",
-            "gs_clip_coefficient", "gs_sqnorm_workspace_bytes_for", "gs_accum_add"} <= set(names)
+            "gs_clip_coefficient", "gs_sqnorm_workspace_bytes_for", "gs_accum_add",
+            "gs_tier_ctx_create", "gs_tier_ctx_destroy", "gs_tier_ctx_sync", "gs_tier_ctx_error", "gs_tier_layer_step"} <= set(names)
     lib = ctypes.CDLL(gs.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in gs.h but not exported"
@@ -122,6 +123,18 @@ def test_stream_api_rejects_without_gpu():
     assert gs.gs_stream_layer_step(None, FAKE, FAKE, FAKE, FAKE, [FAKE], 10, GOOD_HP, check=False) == gs.GS_ERR_INVALID_ARG
     assert gs.gs_pinned_alloc(0) is None
     gs.gs_pinned_free(None)
+
+
+def test_tier_api_rejects_without_gpu():
+    for chunk, slots in ((0, 2), (1024, 1), (1024, 65), (-5, 3), ((1 << 34) + 1, 2)):
+        st, ctx = gs.gs_tier_ctx_create(chunk, slots, check=False)
+        assert st == gs.GS_ERR_INVALID_ARG and not ctx
+    assert gs.gs_tier_ctx_sync(None, check=False) == gs.GS_ERR_INVALID_ARG
+    assert gs.gs_tier_ctx_destroy(None, check=False) == gs.GS_ERR_INVALID_ARG
+    assert gs.gs_tier_ctx_error(None) == ""
+    assert gs.gs_tier_layer_step(None, FAKE, FAKE, FAKE, 4, (3, 4, 5), (0, 0, 0), FAKE, [FAKE], 10, GOOD_HP,
+                                 check=False) == gs.GS_ERR_INVALID_ARG
+    assert gs.gs_strerror(gs.GS_ERR_IO) == "file read or write failed"
 
 
 def test_accum_add_rejects_without_gpu():

@@ -2,6 +2,8 @@
 element, on the same seeded inputs.  Sizes span many launch tiles (a workgroup handles 1024
 elements; a norm workgroup a run of 8 such tiles) and ragged tails; full workload sizes are in
 test_gpu_fullsize.py."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -339,6 +341,91 @@ def test_streamed_two_layers_back_to_back_with_poisoned_slots():
         for bufs in held:
             for t, ptr in bufs:
                 gs.gs_pinned_free(ptr)
+
+
+# ----------------------------------------------------------------------------- file tier
+def _write_states(tmp_path, tag, arrays, n_host, header):
+    """p/m/v[n_host:] into three files, each behind `header` bytes that must survive."""
+    fds, paths = [], []
+    for name, a in zip("pmv", arrays):
+        path = str(tmp_path / f"{tag}_{name}.bin")
+        with open(path, "wb") as f:
+            f.write(b"\x5a" * header)
+            f.write(a[n_host:].tobytes())
+            f.write(b"TAIL")
+        paths.append(path)
+        fds.append(os.open(path, os.O_RDWR))
+    return fds, paths
+
+
+def _read_states(paths, count, header):
+    out = []
+    for path in paths:
+        raw = open(path, "rb").read()
+        assert len(raw) == header + 4 * count + 4 and raw[:header] == b"\x5a" * header and raw[-4:] == b"TAIL"
+        out.append(np.frombuffer(raw, dtype=np.float32, count=count, offset=header).copy())
+    return out
+
+
+@pytest.mark.parametrize("x,chunk,slots", [(0.0, 100_003, 2), (0.37, 65_536, 3), (1.0, 100_003, 2), (0.5, 10**7, 2)])
+def test_tiered_equals_resident_and_oracle(tmp_path, x, chunk, slots):
+    """States split between pinned host memory (share x, the storage ratio) and files: two steps
+    in a row give bit for bit what the resident step gives, and the first matches the oracle."""
+    n, k, header = 512 * 900 + 77, 4, 24
+    case = DeviceCase(n, k, seed=95)
+    n_host = int(round(x * n))
+    init = [np_f32(t) for t in (case.p, case.m, case.v)]
+    fds, paths = _write_states(tmp_path, "L", init, n_host, header)
+    bufs = [gs.pinned_f32(max(n_host, 1)) for _ in range(3)]
+    ctx = gs.gs_tier_ctx_create(chunk, slots)
+    try:
+        for (tn, _), a in zip(bufs, init):
+            tn[:n_host].copy_(torch.from_numpy(a[:n_host]))
+        ref = case.clone_states()
+        for step in (1, 2):
+            hp = gs.HParams(**{**HP.__dict__, "step": HP.step + step - 1})
+            case.gpu_sqnorm()
+            w = torch.zeros_like(case.w)
+            gs.gs_tier_layer_step(ctx, bufs[0][1], bufs[1][1], bufs[2][1], n_host, fds, (header,) * 3,
+                                  w, case.grads, n, hp, case.sq)
+            gs.gs_tier_ctx_sync(ctx)
+            assert gs.gs_tier_ctx_error(ctx) == ""
+            gs.gs_accum_adamw(*ref, case.grads, 0, n, hp, case.sq)
+            torch.cuda.synchronize()
+            tail = _read_states(paths, n - n_host, header)
+            for (tn, _), fl, r in zip(bufs, tail, ref[:3]):
+                want = np_f32(r)
+                assert np.array_equal(tn[:n_host].numpy(), want[:n_host])
+                assert np.array_equal(fl, want[n_host:])
+            assert torch.equal(w, ref[3])
+            if step == 1:
+                compare_states(ref, case.oracle_step(HP, O.clip_coef(O.grad_sqnorm(case.h_g), HP.max_grad_norm)),
+                               f"tiered x={x}")
+    finally:
+        gs.gs_tier_ctx_destroy(ctx)
+        for fd in fds:
+            os.close(fd)
+        for _, ptr in bufs:
+            gs.gs_pinned_free(ptr)
+
+
+def test_tiered_short_file_is_an_error_not_a_hang(tmp_path):
+    n = 50_000
+    case = DeviceCase(n, 1, seed=96)
+    init = [np_f32(t)[: n // 2] for t in (case.p, case.m, case.v)]      # files hold half the layer
+    fds, _ = _write_states(tmp_path, "S", init, 0, 0)
+    for fd in fds:
+        os.ftruncate(fd, 4 * (n // 2))
+    ctx = gs.gs_tier_ctx_create(8192, 2)
+    try:
+        st = gs.gs_tier_layer_step(ctx, None, None, None, 0, fds, (0, 0, 0), case.w, case.grads, n, HP, None, check=False)
+        assert st == gs.GS_ERR_IO and "pread" in gs.gs_tier_ctx_error(ctx)
+        assert gs.gs_tier_ctx_sync(ctx, check=False) == gs.GS_ERR_IO
+    finally:
+        assert gs.gs_tier_ctx_destroy(ctx, check=False) == gs.GS_ERR_IO
+        for fd in fds:
+            os.close(fd)
+    torch.cuda.synchronize()
 
 
 # ----------------------------------------------------------------------------- staged two-pass variant
