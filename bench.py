@@ -46,6 +46,7 @@ def parse():
                          "timed region, as the known-size reference for rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     ap.add_argument("--cpu-sample", type=int, default=1 << 27, help="elements of the workload the oracle is timed on")
     ap.add_argument("--slots", type=int, default=3, help="staging slots of the streamed workload")
+    ap.add_argument("--tier-dir", default=None, help="directory for the file tier's state files (default: the system temp dir)")
     return ap.parse_args()
 
 
@@ -323,6 +324,151 @@ def bench_streamed(args, wl):
         gs.gs_pinned_free(ptr)
 
 
+def bench_tiered(args, wl):
+    """Three-tier step (Sec. 4.3 pipeline with the SSD leg, Sec. 4.5 storage ratio): a share x of
+    every layer's fp32 p/m/v lives in pinned host memory, the rest in files under --tier-dir; file
+    chunks are read into pinned bounce slots, go through the host<->HBM pipeline and are written
+    back by a writer thread.  Reports params/s and the file tier's GB/s per direction against raw
+    pread/pwrite of the same files measured here (three threads, like the pipeline's)."""
+    import shutil
+    import tempfile
+    import threading
+
+    import numpy as np
+    import torch
+
+    from paper_2512_17570_amd import gs
+    from paper_2512_17570_amd import inputs as I
+
+    dev = "cuda:0"
+    props = torch.cuda.get_device_properties(0)
+    chunk, x = wl.extra["chunk_elems"], wl.extra["host_share"]
+    layers, nl, k = wl.layers, I.layer_numel(wl.h), wl.k
+    n_host = int(round(x * nl))
+    n_file = nl - n_host
+    root = tempfile.mkdtemp(prefix="gs_tier_", dir=args.tier_dir)
+    free = shutil.disk_usage(root).free
+    while layers > 1 and layers * n_file * 12 > 0.8 * free:
+        layers -= 1
+    hosts, fds, grads_l, w_l = [], [], [], []
+    try:
+        for L in range(layers):
+            pd, md, vd = I.make_states(nl, wl.seed + L, dev)
+            bufs = gs.pinned_f32_set(max(n_host, 1), 3)
+            if bufs is None:
+                print("bench.py: cannot pin the host share", file=sys.stderr)
+                sys.exit(1)
+            hosts.append(bufs)
+            lf = []
+            for name, (t, _), src in zip("pmv", bufs, (pd, md, vd)):
+                t[:n_host].copy_(src[:n_host])
+                path = os.path.join(root, f"L{L}_{name}.bin")
+                src[n_host:].cpu().numpy().tofile(path)
+                lf.append(os.open(path, os.O_RDWR))
+            fds.append(lf)
+            del pd, md, vd
+            grads_l.append(I.make_grads(nl, k, wl.grad_sigma, wl.seed + L, dev))
+            w_l.append(torch.zeros(nl, dtype=torch.bfloat16, device=dev))
+        sq = torch.zeros(1, dtype=torch.float64, device=dev)
+        ws = torch.empty(gs.gs_sqnorm_workspace_bytes(), dtype=torch.uint8, device=dev)
+        for L in range(layers):
+            gs.gs_grad_sqnorm(grads_l[L], 0, nl, sq, ws, accumulate=(L > 0))
+        torch.cuda.synchronize()
+
+        # raw file ceilings: p/m/v of every layer read (then written) chunk by chunk by three threads
+        scratch = [np.empty(chunk, np.float32) for _ in range(3)]
+
+        def sweep(write):
+            def worker(a):
+                buf = memoryview(scratch[a]).cast("B")
+                for L in range(layers):
+                    for off in range(0, n_file * 4, chunk * 4):
+                        ln = min(chunk * 4, n_file * 4 - off)
+                        if write:
+                            os.pwrite(fds[L][a], buf[:ln], off)
+                        else:
+                            os.preadv(fds[L][a], [buf[:ln]], off)
+            ths = [threading.Thread(target=worker, args=(a,)) for a in range(3)]
+            t0 = time.perf_counter()
+            for t in ths:
+                t.start()
+            for t in ths:
+                t.join()
+            return layers * n_file * 12 / (time.perf_counter() - t0) / 1e9
+
+        print(f"[tiered] {layers} layers staged under {root}, {layers * n_file * 12 / 1e9:.1f} GB in files", file=sys.stderr, flush=True)
+        sweep(False)
+        read_gbs = sweep(False)
+        print(f"[tiered] raw pread {read_gbs:.2f} GB/s", file=sys.stderr, flush=True)
+        write_gbs = None
+        if n_file:
+            # write back what was just read, so the files keep their contents
+            def rw_worker(a, out):
+                buf = memoryview(scratch[a]).cast("B")
+                t_w = 0.0
+                for L in range(layers):
+                    for off in range(0, n_file * 4, chunk * 4):
+                        ln = min(chunk * 4, n_file * 4 - off)
+                        os.preadv(fds[L][a], [buf[:ln]], off)
+                        t0 = time.perf_counter()
+                        os.pwrite(fds[L][a], buf[:ln], off)
+                        t_w += time.perf_counter() - t0
+                out[a] = t_w
+            out = [0.0] * 3
+            ths = [threading.Thread(target=rw_worker, args=(a, out)) for a in range(3)]
+            for t in ths:
+                t.start()
+            for t in ths:
+                t.join()
+            write_gbs = layers * n_file * 12 / max(out) / 1e9
+
+        ctx = gs.gs_tier_ctx_create(chunk, args.slots)
+        cur = torch.cuda.current_stream()
+
+        def one_pass(i):
+            hp = _hp_of(gs, wl, i)
+            for L in range(layers):
+                (_, pp), (_, pm), (_, pv) = hosts[L]
+                gs.gs_tier_layer_step(ctx, pp, pm, pv, n_host, fds[L], (0, 0, 0), w_l[L], grads_l[L], nl, hp, sq,
+                                      producer_stream=cur)
+            gs.gs_tier_ctx_sync(ctx)
+
+        print(f"[tiered] raw pwrite {write_gbs} GB/s; timing", file=sys.stderr, flush=True)
+        for i in range(args.warmup):
+            one_pass(i)
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            one_pass(args.warmup + i)
+            print(f"[tiered] pass {i + 1}/{args.steps} at {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
+        elapsed = time.perf_counter() - t0
+        gs.gs_tier_ctx_destroy(ctx)
+        per = elapsed / args.steps
+        n = layers * nl
+        rec = _base_record(wl, props, n / per, args.steps, args.warmup, per * 1e3,
+                           {"layers": layers, "n_params": n, "chunk_elems": chunk, "slots": args.slots,
+                            "host_share_x": x, "file_bytes": layers * n_file * 12, "host_pinned_bytes": layers * n_host * 12,
+                            "tier_dir_fs_free_bytes": free})
+        file_dir = layers * n_file * 12 / per / 1e9
+        peak = min(read_gbs, write_gbs) if write_gbs else read_gbs
+        rec["roofline"] = {"bound": "file", "kernel": "gs_tier_layer_step (file share: 12 B read + 12 B written per parameter)",
+                           "achieved": file_dir, "peak": peak, "unit": "GB/s per direction", "frac": file_dir / peak,
+                           "traffic": None,
+                           "peak_source": "measured here on the same files: chunked pread / pwrite by three threads "
+                                          "(page cache included, as in the timed run; no fsync)",
+                           "pread_GBps": read_gbs, "pwrite_GBps": write_gbs,
+                           "pcie_GBps_per_direction": 12 * n / per / 1e9}
+        rec["cpu_baseline"] = None
+        print(json.dumps(rec))
+    finally:
+        for lf in fds:
+            for fd in lf:
+                os.close(fd)
+        shutil.rmtree(root, ignore_errors=True)
+        for bufs in hosts:
+            for _, ptr in bufs:
+                gs.gs_pinned_free(ptr)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -346,6 +492,8 @@ def main():
     torch.cuda.set_device(0)
     if "immediate_frac" in wl.extra:
         return bench_split(args, wl)
+    if "host_share" in wl.extra:
+        return bench_tiered(args, wl)
     if "chunk_elems" in wl.extra:
         return bench_streamed(args, wl)
     props = torch.cuda.get_device_properties(0)

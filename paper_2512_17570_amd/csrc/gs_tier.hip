@@ -5,10 +5,10 @@
 // share of the states stays in CPU memory instead (Sec. 4.5).  Here a layer's fp32 p/m/v are
 // split the same way: elements [0,n_host) in pinned host memory, elements [n_host,n) in files.
 // The host share goes through the host<->HBM pipeline directly.  The file share is walked in
-// chunks; for chunk c the calling thread reads p/m/v into a pinned bounce slot and enqueues
-// upload -> step kernel -> download on the pipeline's three streams, and a writer thread waits
-// for the download's event and writes the slot back to the files.  Reading chunk c+1 overlaps
-// the GPU work of chunk c and the write-back of chunk c-1.
+// chunks, interleaved with the host share's; for file chunk c the calling thread reads p/m/v
+// into a pinned bounce slot and enqueues upload -> step kernel -> download on the pipeline's
+// three streams, and a writer thread, woken by a host function that follows the download on its
+// stream, writes the slot back to the files.  Reading chunk c+1 overlaps the GPU work of chunk c and the write-back of chunk c-1.
 //
 // Every element goes through the same kernel with the same absolute-index grouping as the
 // resident step, so the result is bit-identical for any n_host and chunk size.
@@ -125,7 +125,12 @@ struct gs_tier_ctx {
     int64_t chunk = 0;
     int64_t bounce_elems = 0;               // per-array stride of a bounce slot (multiple of 1024 floats)
     float *bounce = nullptr;                // pinned host: slots * 3 * bounce_elems floats
-    std::vector<hipEvent_t> ev_done;        // per bounce slot: its chunk's download has finished
+    struct Note {                           // argument of the host function that follows a download
+        gs_tier_ctx *ctx;
+        int slot;
+    };
+    std::vector<Note> notes;                // one per bounce slot, addresses stable after create
+    std::vector<char> downloaded;           // the slot's chunk is back in the bounce slot (guarded by mu)
 
     std::mutex mu;
     std::condition_variable cv;
@@ -156,9 +161,20 @@ struct gs_tier_ctx {
     }
 };
 
+// Runs on a runtime thread when the download stream reaches it: flag the slot and wake the writer.
+static void on_download_done(void *arg)
+{
+    gs_tier_ctx::Note *note = static_cast<gs_tier_ctx::Note *>(arg);
+    gs_tier_ctx *t = note->ctx;
+    {
+        std::lock_guard<std::mutex> g(t->mu);
+        t->downloaded[note->slot] = 1;
+    }
+    t->cv.notify_all();
+}
+
 static void writer_main(gs_tier_ctx *t)
 {
-    (void)hipSetDevice(t->device);
     for (;;) {
         WriteJob j;
         {
@@ -169,12 +185,15 @@ static void writer_main(gs_tier_ctx *t)
             t->jobs.pop_front();
             t->writer_active = true;
         }
-        // recorded on the download stream before the job was queued; nobody records it again
-        // until this job has released the slot
-        hipError_t e = hipEventSynchronize(t->ev_done[j.slot]);
-        if (e != hipSuccess) {
-            t->fail(GS_ERR_HIP, hipGetErrorString(e), 0);
-        } else {
+        // The download's completion is announced by a host function enqueued behind it on the
+        // download stream; this thread makes no HIP call, so it cannot get in the way of the
+        // caller's enqueues.
+        {
+            std::unique_lock<std::mutex> lk(t->mu);
+            t->cv.wait(lk, [&] { return t->downloaded[j.slot] != 0; });
+            t->downloaded[j.slot] = 0;
+        }
+        {
             float *const buf[3] = {t->slot_ptr(j.slot, 0), t->slot_ptr(j.slot, 1), t->slot_ptr(j.slot, 2)};
             int werr = 0;
             const int bad = move3(true, j.fd, buf, (size_t)j.len * sizeof(float), j.off, &werr);
@@ -202,8 +221,6 @@ static void tier_free(gs_tier_ctx *t)
         t->writer.join();
     }
     if (t->sc) (void)gs_stream_ctx_destroy(t->sc);
-    for (auto e : t->ev_done)
-        if (e) (void)hipEventDestroy(e);
     if (t->bounce) (void)hipHostFree(t->bounce);
     delete t;
 }
@@ -236,15 +253,9 @@ gs_status gs_tier_ctx_create(gs_tier_ctx **out, int64_t chunk_elems, int slots)
         tier_free(t);
         return GS_ERR_NOMEM;
     }
-    t->ev_done.assign(slots, nullptr);
-    for (int i = 0; i < slots; ++i) {
-        hipError_t e = hipEventCreateWithFlags(&t->ev_done[i], hipEventDisableTiming);
-        if (e != hipSuccess) {
-            t->ev_done[i] = nullptr;
-            tier_free(t);
-            return hip_fail(e, "hipEventCreateWithFlags");
-        }
-    }
+    t->downloaded.assign(slots, 0);
+    t->notes.resize(slots);
+    for (int i = 0; i < slots; ++i) t->notes[i] = gs_tier_ctx::Note{t, i};
     try {
         t->writer = std::thread(writer_main, t);
         t->writer_started = true;
@@ -314,18 +325,29 @@ gs_status gs_tier_layer_step(gs_tier_ctx *t, const gs_tier_layer *L, uint16_t *d
     st = stream_begin_layer(c, A, d_w_bf16, d_grads, k, hp, d_sqnorm, producer_stream);
     if (st != GS_OK) return st;
 
-    // host share: straight through the host<->HBM pipeline (nothing here blocks)
-    for (int64_t b = 0; b < L->n_host; b += c->chunk) {
-        const int64_t e = (b + c->chunk < L->n_host) ? b + c->chunk : L->n_host;
-        st = stream_chunk(c, A, L->h_p + b, L->h_m + b, L->h_v + b, b, e, nullptr);
-        if (st != GS_OK) return st;
-    }
-
-    // file share
+    // The two shares are walked together, each in proportion to its size, so that file reads and
+    // write-backs run alongside the host share's PCIe traffic instead of after it.  (The update
+    // is element-wise: the order of chunks does not change any result.)
     const int fd[3] = {L->fd_p, L->fd_m, L->fd_v};
     const int64_t base[3] = {L->off_p, L->off_m, L->off_v};
-    for (int64_t b = L->n_host; b < n; b += c->chunk) {
+    const int64_t host_chunks = (L->n_host + c->chunk - 1) / c->chunk;
+    const int64_t file_chunks = (n - L->n_host + c->chunk - 1) / c->chunk;
+    int64_t hi = 0, fi = 0;
+    while (hi < host_chunks || fi < file_chunks) {
+        // next: the share that is further behind (fi/file_chunks < hi/host_chunks); ties go to the file share,
+        // whose read takes host time
+        const bool take_file = fi < file_chunks && (hi >= host_chunks || fi * host_chunks <= hi * file_chunks);
+        if (!take_file) {
+            const int64_t b = hi * c->chunk;
+            const int64_t e = (b + c->chunk < L->n_host) ? b + c->chunk : L->n_host;
+            ++hi;
+            st = stream_chunk(c, A, L->h_p + b, L->h_m + b, L->h_v + b, b, e, nullptr);
+            if (st != GS_OK) return st;
+            continue;
+        }
+        const int64_t b = L->n_host + fi * c->chunk;
         const int64_t e = (b + c->chunk < n) ? b + c->chunk : n;
+        ++fi;
         const int64_t len = e - b;
         const int slot = (int)(c->next_chunk % c->slots);    // the slot stream_chunk is about to take
         {
@@ -346,8 +368,8 @@ gs_status gs_tier_layer_step(gs_tier_ctx *t, const gs_tier_layer *L, uint16_t *d
         int got = -1;
         st = stream_chunk(c, A, buf[0], buf[1], buf[2], b, e, &got);
         if (st == GS_OK) {
-            hipError_t he = hipEventRecord(t->ev_done[got], c->s_d2h);
-            if (he != hipSuccess) st = hip_fail(he, "hipEventRecord(bounce slot)");
+            hipError_t he = hipLaunchHostFunc(c->s_d2h, on_download_done, &t->notes[got]);
+            if (he != hipSuccess) st = hip_fail(he, "hipLaunchHostFunc(download done)");
         }
         if (st != GS_OK) {
             t->fail(st, "enqueue of a file chunk failed", 0);

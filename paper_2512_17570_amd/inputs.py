@@ -79,6 +79,9 @@ WORKLOADS = {
     # eight GPT-65B layers with host-resident states, streamed in 2^26-element chunks
     "gpt65b_8layers_streamed_k8": Workload("gpt65b_8layers_streamed_k8", h=8192, k=8, grad_sigma=1e-3, step=100,
                                            layers=8, extra={"chunk_elems": 1 << 26}),
+    # two GPT-65B layers, half of each layer's states in pinned host memory and half in files
+    "gpt65b_2layers_tiered_k8": Workload("gpt65b_2layers_tiered_k8", h=8192, k=8, grad_sigma=1e-3, step=100,
+                                         layers=2, extra={"chunk_elems": 1 << 24, "host_share": 0.5}),
 }
 
 _CHUNK = 1 << 24

@@ -44,6 +44,8 @@ hipError_t hipEventCreateWithFlags(hipEvent_t *e, unsigned flags);
 hipError_t hipEventDestroy(hipEvent_t e);
 hipError_t hipEventRecord(hipEvent_t e, hipStream_t s);
 hipError_t hipEventSynchronize(hipEvent_t e);
+typedef void (*hipHostFn_t)(void *userData);
+hipError_t hipLaunchHostFunc(hipStream_t s, hipHostFn_t fn, void *userData);
 hipError_t hipMemcpyAsync(void *dst, const void *src, size_t bytes, hipMemcpyKind kind, hipStream_t s);
 
 #ifdef __cplusplus

@@ -160,6 +160,12 @@ hipError_t hipEventSynchronize(hipEvent_t e)
     return hipSuccess;
 }
 
+hipError_t hipLaunchHostFunc(hipStream_t s, hipHostFn_t fn, void *userData)
+{
+    hipmock_enqueue(s, [fn, userData] { fn(userData); });
+    return hipSuccess;
+}
+
 hipError_t hipMemcpyAsync(void *dst, const void *src, size_t bytes, hipMemcpyKind, hipStream_t s)
 {
     hipmock_enqueue(s, [=] {
