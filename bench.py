@@ -45,7 +45,9 @@ def parse():
                     help="also run a plain elementwise copy of 2^28 floats (1 GiB in, 1 GiB out) three times before the "
                          "timed region, as the known-size reference for rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     ap.add_argument("--cpu-sample", type=int, default=1 << 27, help="elements of the workload the oracle is timed on")
-    ap.add_argument("--slots", type=int, default=3, help="staging slots of the streamed workload")
+    ap.add_argument("--slots", type=int, default=3, help="bounce slots of the tiered workload")
+    ap.add_argument("--stream-cus", type=int, default=32,
+                    help="compute units the host-resident step may use in the streamed and tiered workloads (0 = all)")
     ap.add_argument("--tier-dir", default=None, help="directory for the file tier's state files (default: the system temp dir)")
     return ap.parse_args()
 
@@ -218,10 +220,11 @@ def bench_split(args, wl):
 
 
 def bench_streamed(args, wl):
-    """Streamed step (Sec. 2.2 chunk loop / Sec. 4.3 pipeline of the paper, with host<->HBM PCIe as
-    the slow link): fp32 p/m/v of all layers live in pinned host memory and are processed in
-    2^26-element chunks, upload | kernel | download overlapped on three streams.  Reports params/s
-    against the measured duplex pinned-copy ceiling (12 B up + 12 B down per parameter)."""
+    """Host-resident step (Sec. 2.2 chunk loop / Sec. 4.3 pipeline of the paper, with host<->GPU
+    PCIe as the slow link): fp32 p/m/v of all layers live in pinned host memory and the kernel steps
+    them in place over the link (12 B read + 12 B written per parameter), on a stream limited to
+    --stream-cus compute units.  Reports params/s against the one-directional pinned-copy rate of
+    this host, measured after the timed region with raw hipMemcpyAsync."""
     import torch
 
     from paper_2512_17570_amd import gs
@@ -257,7 +260,27 @@ def bench_streamed(args, wl):
         gs.gs_grad_sqnorm(grads_l[L], 0, nl, sq, ws, accumulate=(L > 0))
     torch.cuda.synchronize()
 
-    # duplex pinned-copy ceiling with the same chunk size: raw hipMemcpyAsync both ways at once
+    ctx = gs.gs_stream_ctx_create(args.stream_cus)
+    cur = torch.cuda.current_stream()
+
+    def one_pass(i):
+        hp = _hp_of(gs, wl, i)
+        for L in range(layers):
+            o = L * nl * 4
+            gs.gs_stream_layer_step(ctx, hp_p + o, hm_p + o, hv_p + o, w_l[L], grads_l[L], nl, hp, sq, producer_stream=cur)
+        gs.gs_stream_ctx_sync(ctx)
+
+    for i in range(args.warmup):
+        one_pass(i)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        one_pass(args.warmup + i)
+    elapsed = time.perf_counter() - t0
+    gs.gs_stream_ctx_destroy(ctx)
+    per = elapsed / args.steps
+
+    # the link's ceilings, measured afterwards: raw pinned hipMemcpyAsync of 2^26-element pieces,
+    # one way at a time and both ways at once
     import ctypes
     hip = ctypes.CDLL(os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so"))
     hip.hipMemcpyAsync.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
@@ -284,39 +307,21 @@ def bench_streamed(args, wl):
     h2d_only_gbs = copy_pass(32, True, False)
     d2h_only_gbs = copy_pass(32, False, True)
     duplex_dir_gbs = copy_pass(48, True, True)
-    hm_t[:].copy_(hp_t)         # the probe overwrote parts of m: restore finite values (timing only)
     del stage
 
-    ctx = gs.gs_stream_ctx_create(chunk, args.slots)
-    cur = torch.cuda.current_stream()
-
-    def one_pass(i):
-        hp = _hp_of(gs, wl, i)
-        for L in range(layers):
-            o = L * nl * 4
-            gs.gs_stream_layer_step(ctx, hp_p + o, hm_p + o, hv_p + o, w_l[L], grads_l[L], nl, hp, sq, producer_stream=cur)
-        gs.gs_stream_ctx_sync(ctx)
-
-    for i in range(args.warmup):
-        one_pass(i)
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        one_pass(args.warmup + i)
-    elapsed = time.perf_counter() - t0
-    gs.gs_stream_ctx_destroy(ctx)
-    per = elapsed / args.steps
     rec = _base_record(wl, props, n / per, args.steps, args.warmup, per * 1e3,
-                       {"layers_pinned": layers, "n_params": n, "chunk_elems": chunk, "slots": args.slots,
-                        "host_pinned_bytes": 12 * n})
+                       {"layers_pinned": layers, "n_params": n, "stream_cus": args.stream_cus,
+                        "host_pinned_bytes": 12 * n, "device_staging_bytes": 0})
     pcie_dir = 12 * n / per / 1e9
     link = min(h2d_only_gbs, d2h_only_gbs)
-    rec["roofline"] = {"bound": "pcie", "kernel": "gs_stream_layer_step (H2D 12 B + D2H 12 B per parameter)",
+    rec["roofline"] = {"bound": "pcie", "kernel": "gs_stream_layer_step (k_accum_adamw in place on pinned host states: "
+                                                  "12 B read + 12 B written over the link per parameter)",
                        "achieved": pcie_dir, "peak": link, "unit": "GB/s per direction",
                        "frac": pcie_dir / link, "traffic": None,
-                       "peak_source": "measured on this host: one-directional pinned hipMemcpyAsync of the same chunk "
-                                      "size (the slower of H2D and D2H); a full-duplex link would sustain it both ways",
+                       "peak_source": "measured on this host after the timed region: one-directional pinned hipMemcpyAsync "
+                                      "(the slower of H2D and D2H); a full-duplex link would sustain it both ways",
                        "h2d_only_GBps": h2d_only_gbs, "d2h_only_GBps": d2h_only_gbs,
-                       "duplex_probe_GBps_per_direction": duplex_dir_gbs,
+                       "duplex_copy_probe_GBps_per_direction": duplex_dir_gbs,
                        "params_per_s_bound": link * 1e9 / 12}
     rec["cpu_baseline"] = None
     print(json.dumps(rec))
@@ -422,7 +427,7 @@ def bench_tiered(args, wl):
                 t.join()
             write_gbs = layers * n_file * 12 / max(out) / 1e9
 
-        ctx = gs.gs_tier_ctx_create(chunk, args.slots)
+        ctx = gs.gs_tier_ctx_create(chunk, args.slots, args.stream_cus)
         cur = torch.cuda.current_stream()
 
         def one_pass(i):

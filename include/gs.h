@@ -239,36 +239,38 @@ gs_status gs_cu_stream_create(void **stream, int num_cus);
 gs_status gs_cu_stream_destroy(void *stream);
 
 /* ------------------------------------------------------------------------------------------
- * Streamed step for states that live in pinned host memory (Sec. 2.2: for each parameter
- * chunk, load gradients + master parameters + optimizer states, step, write back; Sec. 4.3
- * the five optimizer-step stages of the backward pipeline -- here the slow link is
- * host<->device PCIe instead of SSD<->host).
+ * Step for states that live in pinned host memory (Sec. 2.2: for each parameter chunk, load
+ * gradients + master parameters + optimizer states, step, write back; Sec. 4.3 the optimizer
+ * stages of the backward pipeline -- here the slow link is host<->device PCIe instead of
+ * SSD<->host).  The kernel runs in place on the host arrays: each wave loads its tile of p, m, v
+ * over the link, updates it and stores it back; nothing is staged in device memory and no copy
+ * engine is used, so the rate does not depend on the runtime's choice of copy path.
  * ------------------------------------------------------------------------------------------ */
 
 typedef struct gs_stream_ctx gs_stream_ctx;
 
 /*
- * Creates a context that owns one H2D copy stream, one compute stream, one D2H copy stream,
- * `slots` (>= 2) staging slots of 3 x chunk_elems fp32 in device memory, and the events that
- * order them.  chunk_elems >= 1.  Returns GS_ERR_NOMEM if the slots cannot be allocated.
+ * Creates a context that owns the stream the host-resident steps run on.  num_cus = 0: an
+ * ordinary stream; num_cus >= 1: a stream confined to that many compute units, as from
+ * gs_cu_stream_create (the link, not the CU count, bounds this step: 16 CUs sustain the full rate
+ * and leave the rest of the GPU to other work).  num_cus < 0 or above the device's count is
+ * GS_ERR_INVALID_ARG.
  */
-gs_status gs_stream_ctx_create(gs_stream_ctx **out, int64_t chunk_elems, int slots);
+gs_status gs_stream_ctx_create(gs_stream_ctx **out, int num_cus);
 gs_status gs_stream_ctx_destroy(gs_stream_ctx *ctx); /* waits for pending work, frees everything */
 
 /*
  * Applies the same update as gs_accum_adamw to all n elements of a layer whose p, m, v are in
- * PINNED host memory, chunk by chunk: chunk c is copied host->slot on the H2D stream, updated
- * by the fused kernel on the compute stream (gradients and w are device-resident and indexed
- * by absolute element), and copied slot->host on the D2H stream; chunk c+1's upload and chunk
- * c-1's download overlap chunk c's kernel.  Results are bit-identical to gs_accum_adamw on a
- * device copy of the same states, for every chunk size.
- *   h_p, h_m, h_v   pinned host fp32, n elements each, updated in place
+ * PINNED host memory, in place, on the context's stream.  Results are bit-identical to
+ * gs_accum_adamw on a device copy of the same states.
+ *   h_p, h_m, h_v   pinned host fp32 (device-accessible, as hipHostMalloc / gs_pinned_alloc
+ *                   give it), n elements each, 16-byte aligned, updated in place
  *   d_w_bf16        device bf16, n elements, written
  *   d_grads         host array of k device pointers (bf16, n elements each)
  *   d_sqnorm        as for gs_accum_adamw (device double or NULL)
  *   producer_stream stream on which the gradients and *d_sqnorm were produced; work already
- *                   enqueued there is waited for before the first kernel (NULL = null stream)
- * The call enqueues everything and returns; host buffers must stay untouched until
+ *                   enqueued there is waited for before the kernel (NULL = null stream)
+ * The call enqueues the work and returns; host buffers must stay untouched until
  * gs_stream_ctx_sync.  Several layers may be enqueued back to back on one context.  Must be
  * called with the device current on which the context was created (else GS_ERR_INVALID_ARG).
  */
@@ -277,7 +279,7 @@ gs_status gs_stream_layer_step(gs_stream_ctx *ctx, float *h_p, float *h_m, float
                                const gs_adamw_hparams *hp, const double *d_sqnorm,
                                void *producer_stream);
 
-/* Blocks until everything enqueued on the context has finished (including the downloads). */
+/* Blocks until everything enqueued on the context has finished (the host arrays hold the new states). */
 gs_status gs_stream_ctx_sync(gs_stream_ctx *ctx);
 
 /* ------------------------------------------------------------------------------------------
@@ -292,7 +294,8 @@ gs_status gs_stream_ctx_sync(gs_stream_ctx *ctx);
 typedef struct gs_tier_ctx gs_tier_ctx;
 
 typedef struct {
-    float *h_p, *h_m, *h_v;            /* pinned host fp32, elements [0,n_host); may be NULL if n_host == 0 */
+    float *h_p, *h_m, *h_v;            /* pinned host fp32, 16-byte aligned, elements [0,n_host); may be NULL
+                                          if n_host == 0 */
     int64_t n_host;                    /* 0 <= n_host <= n */
     int fd_p, fd_m, fd_v;              /* open descriptors (read+write); ignored if n_host == n */
     int64_t off_p, off_m, off_v;       /* byte offset of element n_host in each file; element i >= n_host
@@ -300,26 +303,27 @@ typedef struct {
 } gs_tier_layer;
 
 /*
- * Creates a context: a gs_stream_ctx (three streams, `slots` device staging slots of
- * 3 x chunk_elems fp32), `slots` bounce slots of the same size in pinned host memory (each array
- * starts on a 4 KB boundary), and one writer thread.  Same argument limits as
- * gs_stream_ctx_create; GS_ERR_NOMEM if device or pinned memory cannot be had.
+ * Creates a context: a gs_stream_ctx (num_cus as for gs_stream_ctx_create), `slots` (2..64) bounce
+ * slots of 3 x chunk_elems fp32 in pinned host memory (each array starts on a 4 KB boundary), and
+ * one writer thread.  chunk_elems in [1, 2^34].  GS_ERR_NOMEM if the pinned memory cannot be had.
  */
-gs_status gs_tier_ctx_create(gs_tier_ctx **out, int64_t chunk_elems, int slots);
+gs_status gs_tier_ctx_create(gs_tier_ctx **out, int64_t chunk_elems, int slots, int num_cus);
 
 /*
  * Applies the same update as gs_accum_adamw to all n elements of the layer described by *L.
- * The host share is enqueued like gs_stream_layer_step.  The file share is walked in chunks of
- * chunk_elems: the CALLING thread reads p/m/v of a chunk into a bounce slot (waiting, if need
- * be, until the writer has released that slot), enqueues upload -> kernel -> download, and the
- * writer thread writes the slot back to the same file offsets once the download has finished.
+ * The host share is stepped in place like gs_stream_layer_step, in launches of chunk_elems.  The
+ * file share is walked in chunks of chunk_elems, interleaved with those launches: the CALLING
+ * thread reads p/m/v of a chunk into a bounce slot (waiting, if need be, until the writer has
+ * released that slot) and enqueues the kernel in place on the slot; the writer thread writes the
+ * slot back to the same file offsets once the kernel has finished.
  * The call returns when the last chunk has been read and enqueued -- not when it has been
  * written; host arrays, files and device tensors must stay untouched until gs_tier_ctx_sync.
  * Results are bit-identical to gs_accum_adamw on a device copy of the same states, for every
  * n_host and chunk size.  Other arguments as for gs_stream_layer_step.  The files must hold the
  * whole range (a short file is GS_ERR_IO).  Descriptors opened with O_DIRECT are the caller's
  * business: offsets, n_host*4, chunk_elems*4 and (n-n_host)*4 then have to be multiples of the
- * device's block size.  The descriptors are not closed.
+ * device's block size (a chunk starting at element b sits (b mod 4) elements into its 4 KB-aligned
+ * bounce array).  The descriptors are not closed.
  * One thread at a time per context.  After any failure of the file tier the context stays
  * failed: this call and gs_tier_ctx_sync return that status, gs_tier_ctx_error its text.
  */
@@ -327,7 +331,7 @@ gs_status gs_tier_layer_step(gs_tier_ctx *ctx, const gs_tier_layer *L, uint16_t 
                              const uint16_t *const *d_grads, int k, int64_t n,
                              const gs_adamw_hparams *hp, const double *d_sqnorm, void *producer_stream);
 
-/* Blocks until every enqueued chunk has been computed, downloaded and written to its file
+/* Blocks until every enqueued chunk has been computed and written back to its host array or file
  * (the page cache counts as written; fsync is the caller's call). */
 gs_status gs_tier_ctx_sync(gs_tier_ctx *ctx);
 gs_status gs_tier_ctx_destroy(gs_tier_ctx *ctx); /* syncs, stops the writer, frees everything */

@@ -1,14 +1,14 @@
-// gs_tier.hip -- three-tier step: file (SSD) <-> pinned host <-> HBM.
+// gs_tier.hip -- three-tier step: file (SSD) <-> pinned host <-> GPU.
 //
 // The paper keeps optimizer states on SSD and, per layer, runs: states SSD->CPU, step, states
 // CPU->SSD, each stage overlapped with its neighbours (Sec. 4.3); a storage ratio decides which
 // share of the states stays in CPU memory instead (Sec. 4.5).  Here a layer's fp32 p/m/v are
 // split the same way: elements [0,n_host) in pinned host memory, elements [n_host,n) in files.
-// The host share goes through the host<->HBM pipeline directly.  The file share is walked in
-// chunks, interleaved with the host share's; for file chunk c the calling thread reads p/m/v
-// into a pinned bounce slot and enqueues upload -> step kernel -> download on the pipeline's
-// three streams, and a writer thread, woken by a host function that follows the download on its
-// stream, writes the slot back to the files.  Reading chunk c+1 overlaps the GPU work of chunk c and the write-back of chunk c-1.
+// The host share is stepped in place by the kernel, over the link.  The file share is walked in
+// chunks, interleaved with launches over the host share: for file chunk c the calling thread
+// reads p/m/v into a pinned bounce slot and enqueues the step kernel in place on that slot, and
+// a writer thread, woken by a host function that follows the kernel, writes the slot back to
+// the files.  Reading chunk c+1 overlaps the kernel of chunk c and the write-back of chunk c-1.
 //
 // Every element goes through the same kernel with the same absolute-index grouping as the
 // resident step, so the result is bit-identical for any n_host and chunk size.
@@ -36,6 +36,7 @@ namespace {
 struct WriteJob {
     int slot;
     int64_t len;            // elements
+    int pad;                // the chunk starts this many elements into the slot's arrays
     int fd[3];
     int64_t off[3];         // byte offsets
 };
@@ -125,12 +126,14 @@ struct gs_tier_ctx {
     int64_t chunk = 0;
     int64_t bounce_elems = 0;               // per-array stride of a bounce slot (multiple of 1024 floats)
     float *bounce = nullptr;                // pinned host: slots * 3 * bounce_elems floats
-    struct Note {                           // argument of the host function that follows a download
+    std::vector<hipEvent_t> ev_done;        // per bounce slot: its chunk's kernel has finished
+    int64_t next_slot = 0;                  // running file-chunk counter across calls -> slot rotation
+    struct Note {                           // argument of the host function that follows a chunk's kernel
         gs_tier_ctx *ctx;
         int slot;
     };
     std::vector<Note> notes;                // one per bounce slot, addresses stable after create
-    std::vector<char> downloaded;           // the slot's chunk is back in the bounce slot (guarded by mu)
+    std::vector<char> finished;           // the slot's chunk is back in the bounce slot (guarded by mu)
 
     std::mutex mu;
     std::condition_variable cv;
@@ -161,14 +164,15 @@ struct gs_tier_ctx {
     }
 };
 
-// Runs on a runtime thread when the download stream reaches it: flag the slot and wake the writer.
-static void on_download_done(void *arg)
+// Runs on a runtime thread when the notification stream reaches it (the chunk's kernel has
+// finished, its results are in the bounce slot): flag the slot and wake the writer.
+static void on_chunk_done(void *arg)
 {
     gs_tier_ctx::Note *note = static_cast<gs_tier_ctx::Note *>(arg);
     gs_tier_ctx *t = note->ctx;
     {
         std::lock_guard<std::mutex> g(t->mu);
-        t->downloaded[note->slot] = 1;
+        t->finished[note->slot] = 1;
     }
     t->cv.notify_all();
 }
@@ -185,16 +189,17 @@ static void writer_main(gs_tier_ctx *t)
             t->jobs.pop_front();
             t->writer_active = true;
         }
-        // The download's completion is announced by a host function enqueued behind it on the
-        // download stream; this thread makes no HIP call, so it cannot get in the way of the
+        // The chunk's completion is announced by a host function enqueued behind its kernel;
+        // this thread makes no HIP call, so it cannot get in the way of the
         // caller's enqueues.
         {
             std::unique_lock<std::mutex> lk(t->mu);
-            t->cv.wait(lk, [&] { return t->downloaded[j.slot] != 0; });
-            t->downloaded[j.slot] = 0;
+            t->cv.wait(lk, [&] { return t->finished[j.slot] != 0; });
+            t->finished[j.slot] = 0;
         }
         {
-            float *const buf[3] = {t->slot_ptr(j.slot, 0), t->slot_ptr(j.slot, 1), t->slot_ptr(j.slot, 2)};
+            float *const buf[3] = {t->slot_ptr(j.slot, 0) + j.pad, t->slot_ptr(j.slot, 1) + j.pad,
+                                   t->slot_ptr(j.slot, 2) + j.pad};
             int werr = 0;
             const int bad = move3(true, j.fd, buf, (size_t)j.len * sizeof(float), j.off, &werr);
             static const char *const names[3] = {"pwrite(p)", "pwrite(m)", "pwrite(v)"};
@@ -221,22 +226,24 @@ static void tier_free(gs_tier_ctx *t)
         t->writer.join();
     }
     if (t->sc) (void)gs_stream_ctx_destroy(t->sc);
+    for (auto e : t->ev_done)
+        if (e) (void)hipEventDestroy(e);
     if (t->bounce) (void)hipHostFree(t->bounce);
     delete t;
 }
 
 extern "C" {
 
-gs_status gs_tier_ctx_create(gs_tier_ctx **out, int64_t chunk_elems, int slots)
+gs_status gs_tier_ctx_create(gs_tier_ctx **out, int64_t chunk_elems, int slots, int num_cus)
 {
     if (!out) return GS_ERR_INVALID_ARG;
     *out = nullptr;
     if (chunk_elems < 1 || slots < 2 || slots > 64) return GS_ERR_INVALID_ARG;
-    if (chunk_elems > ((int64_t)1 << 34)) return GS_ERR_INVALID_ARG;
+    if (chunk_elems > ((int64_t)1 << 34) || num_cus < 0) return GS_ERR_INVALID_ARG;
 
     gs_tier_ctx *t = new (std::nothrow) gs_tier_ctx();
     if (!t) return GS_ERR_NOMEM;
-    gs_status st = gs_stream_ctx_create(&t->sc, chunk_elems, slots);
+    gs_status st = gs_stream_ctx_create(&t->sc, num_cus);
     if (st != GS_OK) {
         t->sc = nullptr;
         tier_free(t);
@@ -245,7 +252,7 @@ gs_status gs_tier_ctx_create(gs_tier_ctx **out, int64_t chunk_elems, int slots)
     t->device = t->sc->device;
     t->slots = slots;
     t->chunk = chunk_elems;
-    t->bounce_elems = ((chunk_elems + 1023) / 1024) * 1024;   // every array starts on a 4 KB boundary
+    t->bounce_elems = ((chunk_elems + 3 + 1023) / 1024) * 1024;   // every array starts on a 4 KB boundary
     t->busy.assign(slots, 0);
     const size_t bytes = (size_t)slots * 3u * (size_t)t->bounce_elems * sizeof(float);
     t->bounce = static_cast<float *>(gs_pinned_alloc(bytes));
@@ -253,7 +260,16 @@ gs_status gs_tier_ctx_create(gs_tier_ctx **out, int64_t chunk_elems, int slots)
         tier_free(t);
         return GS_ERR_NOMEM;
     }
-    t->downloaded.assign(slots, 0);
+    t->ev_done.assign(slots, nullptr);
+    for (int i = 0; i < slots; ++i) {
+        hipError_t e = hipEventCreateWithFlags(&t->ev_done[i], hipEventDisableTiming);
+        if (e != hipSuccess) {
+            t->ev_done[i] = nullptr;
+            tier_free(t);
+            return hip_fail(e, "hipEventCreateWithFlags");
+        }
+    }
+    t->finished.assign(slots, 0);
     t->notes.resize(slots);
     for (int i = 0; i < slots; ++i) t->notes[i] = gs_tier_ctx::Note{t, i};
     try {
@@ -305,7 +321,7 @@ gs_status gs_tier_layer_step(gs_tier_ctx *t, const gs_tier_layer *L, uint16_t *d
     if (L->n_host > 0) {
         if (!L->h_p || !L->h_m || !L->h_v) return GS_ERR_INVALID_ARG;
         if ((reinterpret_cast<uintptr_t>(L->h_p) | reinterpret_cast<uintptr_t>(L->h_m) |
-             reinterpret_cast<uintptr_t>(L->h_v)) & 3u)
+             reinterpret_cast<uintptr_t>(L->h_v)) & 15u)
             return GS_ERR_INVALID_ARG;
     }
     if (L->n_host < n) {
@@ -330,26 +346,27 @@ gs_status gs_tier_layer_step(gs_tier_ctx *t, const gs_tier_layer *L, uint16_t *d
     // is element-wise: the order of chunks does not change any result.)
     const int fd[3] = {L->fd_p, L->fd_m, L->fd_v};
     const int64_t base[3] = {L->off_p, L->off_m, L->off_v};
-    const int64_t host_chunks = (L->n_host + c->chunk - 1) / c->chunk;
-    const int64_t file_chunks = (n - L->n_host + c->chunk - 1) / c->chunk;
+    const int64_t host_chunks = (L->n_host + t->chunk - 1) / t->chunk;
+    const int64_t file_chunks = (n - L->n_host + t->chunk - 1) / t->chunk;
     int64_t hi = 0, fi = 0;
     while (hi < host_chunks || fi < file_chunks) {
         // next: the share that is further behind (fi/file_chunks < hi/host_chunks); ties go to the file share,
         // whose read takes host time
         const bool take_file = fi < file_chunks && (hi >= host_chunks || fi * host_chunks <= hi * file_chunks);
         if (!take_file) {
-            const int64_t b = hi * c->chunk;
-            const int64_t e = (b + c->chunk < L->n_host) ? b + c->chunk : L->n_host;
+            const int64_t b = hi * t->chunk;
+            const int64_t e = (b + t->chunk < L->n_host) ? b + t->chunk : L->n_host;
             ++hi;
-            st = stream_chunk(c, A, L->h_p + b, L->h_m + b, L->h_v + b, b, e, nullptr);
+            st = stream_range(c, A, L->h_p + b, L->h_m + b, L->h_v + b, b, e);
             if (st != GS_OK) return st;
             continue;
         }
-        const int64_t b = L->n_host + fi * c->chunk;
-        const int64_t e = (b + c->chunk < n) ? b + c->chunk : n;
+        const int64_t b = L->n_host + fi * t->chunk;
+        const int64_t e = (b + t->chunk < n) ? b + t->chunk : n;
         ++fi;
         const int64_t len = e - b;
-        const int slot = (int)(c->next_chunk % c->slots);    // the slot stream_chunk is about to take
+        const int slot = (int)(t->next_slot % t->slots);
+        t->next_slot++;
         {
             std::unique_lock<std::mutex> lk(t->mu);
             t->cv.wait(lk, [&] { return !t->busy[slot]; });
@@ -357,7 +374,10 @@ gs_status gs_tier_layer_step(gs_tier_ctx *t, const gs_tier_layer *L, uint16_t *d
         }
         int64_t off[3];
         for (int a = 0; a < 3; ++a) off[a] = base[a] + (b - L->n_host) * (int64_t)sizeof(float);
-        float *const buf[3] = {t->slot_ptr(slot, 0), t->slot_ptr(slot, 1), t->slot_ptr(slot, 2)};
+        // the chunk sits (b mod 4) elements into its bounce arrays, so that the kernel's 16-byte
+        // accesses to absolute-index groups stay aligned
+        const int64_t pad = b & 3;
+        float *const buf[3] = {t->slot_ptr(slot, 0) + pad, t->slot_ptr(slot, 1) + pad, t->slot_ptr(slot, 2) + pad};
         int rerr = 0;
         const int bad = move3(false, fd, buf, (size_t)len * sizeof(float), off, &rerr);
         if (bad >= 0) {
@@ -365,26 +385,30 @@ gs_status gs_tier_layer_step(gs_tier_ctx *t, const gs_tier_layer *L, uint16_t *d
             t->fail(GS_ERR_IO, names[bad], rerr);
             return GS_ERR_IO;
         }
-        int got = -1;
-        st = stream_chunk(c, A, buf[0], buf[1], buf[2], b, e, &got);
+        st = stream_range(c, A, buf[0], buf[1], buf[2], b, e);
         if (st == GS_OK) {
-            hipError_t he = hipLaunchHostFunc(c->s_d2h, on_download_done, &t->notes[got]);
-            if (he != hipSuccess) st = hip_fail(he, "hipLaunchHostFunc(download done)");
+            // the notification rides on its own stream so that the compute stream never waits
+            // for a host thread
+            hipError_t he = hipEventRecord(t->ev_done[slot], c->s_comp);
+            if (he == hipSuccess) he = hipStreamWaitEvent(c->s_note, t->ev_done[slot], 0);
+            if (he == hipSuccess) he = hipLaunchHostFunc(c->s_note, on_chunk_done, &t->notes[slot]);
+            if (he != hipSuccess) st = hip_fail(he, "hipLaunchHostFunc(chunk done)");
         }
         if (st != GS_OK) {
             t->fail(st, "enqueue of a file chunk failed", 0);
             return st;
         }
         WriteJob j;
-        j.slot = got;
+        j.slot = slot;
         j.len = len;
+        j.pad = (int)pad;
         for (int a = 0; a < 3; ++a) {
             j.fd[a] = fd[a];
             j.off[a] = off[a];
         }
         {
             std::lock_guard<std::mutex> g(t->mu);
-            t->busy[got] = 1;
+            t->busy[slot] = 1;
             t->jobs.push_back(j);
         }
         t->cv.notify_all();

@@ -89,7 +89,7 @@ _lib.gs_cu_stream_create.argtypes = [ctypes.POINTER(_vp), ctypes.c_int]
 _lib.gs_cu_stream_create.restype = ctypes.c_int
 _lib.gs_cu_stream_destroy.argtypes = [_vp]
 _lib.gs_cu_stream_destroy.restype = ctypes.c_int
-_lib.gs_stream_ctx_create.argtypes = [ctypes.POINTER(_vp), _i64, ctypes.c_int]
+_lib.gs_stream_ctx_create.argtypes = [ctypes.POINTER(_vp), ctypes.c_int]
 _lib.gs_stream_ctx_create.restype = ctypes.c_int
 _lib.gs_stream_ctx_destroy.argtypes = [_vp]
 _lib.gs_stream_ctx_destroy.restype = ctypes.c_int
@@ -287,9 +287,9 @@ def gs_cu_stream_destroy(stream, check: bool = True) -> int:
     return _check(_lib.gs_cu_stream_destroy(stream), "gs_cu_stream_destroy", check)
 
 
-def gs_stream_ctx_create(chunk_elems: int, slots: int = 3, check: bool = True):
+def gs_stream_ctx_create(num_cus: int = 0, check: bool = True):
     out = ctypes.c_void_p()
-    st = _lib.gs_stream_ctx_create(ctypes.byref(out), chunk_elems, slots)
+    st = _lib.gs_stream_ctx_create(ctypes.byref(out), num_cus)
     if check:
         _check(st, "gs_stream_ctx_create", True)
         return out.value
@@ -323,7 +323,7 @@ class gs_tier_layer(ctypes.Structure):
                 ("off_p", ctypes.c_int64), ("off_m", ctypes.c_int64), ("off_v", ctypes.c_int64)]
 
 
-_lib.gs_tier_ctx_create.argtypes = [ctypes.POINTER(ctypes.c_void_p), _i64, ctypes.c_int]
+_lib.gs_tier_ctx_create.argtypes = [ctypes.POINTER(ctypes.c_void_p), _i64, ctypes.c_int, ctypes.c_int]
 _lib.gs_tier_ctx_create.restype = ctypes.c_int
 _lib.gs_tier_ctx_destroy.argtypes = [_vp]
 _lib.gs_tier_ctx_destroy.restype = ctypes.c_int
@@ -335,9 +335,9 @@ _lib.gs_tier_layer_step.argtypes = [_vp, ctypes.POINTER(gs_tier_layer), _vp, _pp
 _lib.gs_tier_layer_step.restype = ctypes.c_int
 
 
-def gs_tier_ctx_create(chunk_elems: int, slots: int = 3, check: bool = True):
+def gs_tier_ctx_create(chunk_elems: int, slots: int = 3, num_cus: int = 0, check: bool = True):
     out = ctypes.c_void_p()
-    st = _lib.gs_tier_ctx_create(ctypes.byref(out), chunk_elems, slots)
+    st = _lib.gs_tier_ctx_create(ctypes.byref(out), chunk_elems, slots, num_cus)
     if check:
         _check(st, "gs_tier_ctx_create", True)
         return out.value

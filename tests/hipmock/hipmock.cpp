@@ -119,7 +119,14 @@ hipError_t hipStreamSynchronize(hipStream_t s)
 }
 
 hipError_t hipEventCreateWithFlags(hipEvent_t *e, unsigned) { *e = new hipmock_event(); return hipSuccess; }
-hipError_t hipEventDestroy(hipEvent_t e) { delete e; return hipSuccess; }
+hipError_t hipEventDestroy(hipEvent_t e)
+{
+    {
+        std::lock_guard<std::mutex> g(e->mu);   // let a completing record leave the lock first
+    }
+    delete e;
+    return hipSuccess;
+}
 
 hipError_t hipEventRecord(hipEvent_t e, hipStream_t s)
 {
@@ -129,10 +136,10 @@ hipError_t hipEventRecord(hipEvent_t e, hipStream_t s)
         seq = ++e->recorded;
     }
     hipmock_enqueue(s, [e, seq] {
-        {
-            std::lock_guard<std::mutex> g(e->mu);
-            if (e->completed < seq) e->completed = seq;
-        }
+        // notified under the lock: once a waiter has seen the completion, this task no longer
+        // touches the event, so the event may be destroyed (as HIP allows after completion)
+        std::lock_guard<std::mutex> g(e->mu);
+        if (e->completed < seq) e->completed = seq;
         e->cv.notify_all();
     });
     return hipSuccess;

@@ -6,11 +6,14 @@
 // surface as GS_ERR_IO instead of a hang.  Built with -fsanitize=thread by the test that runs it.
 #include <hip/hip_runtime_api.h>
 
+#include <algorithm>
+#include <chrono>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <fcntl.h>
 #include <string>
+#include <thread>
 #include <unistd.h>
 #include <vector>
 
@@ -90,11 +93,11 @@ struct Layer {
     }
 };
 
-static void test_stream(int64_t n, int64_t chunk, int slots)
+static void test_stream(int64_t n, int num_cus)
 {
     Layer A(n, 1), B(n / 2 + 3, 2);
     gs_stream_ctx *ctx = nullptr;
-    CHECK(gs_stream_ctx_create(&ctx, chunk, slots) == GS_OK, "create");
+    CHECK(gs_stream_ctx_create(&ctx, num_cus) == GS_OK, "create");
     float *hp_[2][3];
     Layer *Ls[2] = {&A, &B};
     for (int l = 0; l < 2; ++l) {
@@ -104,19 +107,34 @@ static void test_stream(int64_t n, int64_t chunk, int slots)
             memcpy(hp_[l][a], src[a]->data(), (size_t)Ls[l]->n * 4);
         }
     }
+    // the gradients are "produced" late on a stream of the caller's: the step has to wait for them
+    hipStream_t producer = nullptr;
+    CHECK(hipStreamCreateWithFlags(&producer, hipStreamNonBlocking) == hipSuccess, "producer stream");
     for (int step = 1; step <= 2; ++step) {
         for (int l = 0; l < 2; ++l) {
-            const uint16_t *gt[1] = {Ls[l]->g.data()};
+            std::vector<uint16_t> *g = &Ls[l]->g;
+            std::vector<uint16_t> real = *g;
+            std::fill(g->begin(), g->end(), (uint16_t)0x7777);
+            hipmock_enqueue(producer, [g, real] {
+                std::this_thread::sleep_for(std::chrono::milliseconds(20));
+                *g = real;
+            });
+            const uint16_t *gt[1] = {g->data()};
             CHECK(gs_stream_layer_step(ctx, hp_[l][0], hp_[l][1], hp_[l][2], Ls[l]->w.data(), gt, 1, Ls[l]->n, &HP, nullptr,
-                                       nullptr) == GS_OK, "layer step");
+                                       producer) == GS_OK, "layer step");
         }
         CHECK(gs_stream_ctx_sync(ctx) == GS_OK, "sync");
         for (int l = 0; l < 2; ++l) {
-            Ls[l]->check(hp_[l][0], hp_[l][1], hp_[l][2], 0, Ls[l]->n, 0, step, "streamed");
-            Ls[l]->check_w(1, "streamed");
+            Ls[l]->check(hp_[l][0], hp_[l][1], hp_[l][2], 0, Ls[l]->n, 0, step, "host-resident");
+            Ls[l]->check_w(1, "host-resident");
         }
     }
+    // a misaligned host array is refused
+    const uint16_t *gt[1] = {A.g.data()};
+    CHECK(gs_stream_layer_step(ctx, hp_[0][0] + 1, hp_[0][1], hp_[0][2], A.w.data(), gt, 1, 16, &HP, nullptr, nullptr) ==
+              GS_ERR_INVALID_ARG, "misaligned host array accepted");
     CHECK(gs_stream_ctx_destroy(ctx) == GS_OK, "destroy");
+    CHECK(hipStreamDestroy(producer) == hipSuccess, "producer stream destroy");
     for (int l = 0; l < 2; ++l)
         for (int a = 0; a < 3; ++a) gs_pinned_free(hp_[l][a]);
 }
@@ -170,7 +188,7 @@ static void test_tier(const std::string &dir, int64_t n, int64_t n_host, int64_t
     Layer *Ls[2] = {&A, &B};
     int64_t nh[2] = {n_host, n_host > B.n ? B.n : n_host / 2};
     gs_tier_ctx *ctx = nullptr;
-    CHECK(gs_tier_ctx_create(&ctx, chunk, slots) == GS_OK, "tier create");
+    CHECK(gs_tier_ctx_create(&ctx, chunk, slots, 0) == GS_OK, "tier create");
     float *host[2][3] = {{nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr}};
     Files *files[2];
     gs_tier_layer desc[2];
@@ -219,7 +237,7 @@ static void test_tier_failures(const std::string &dir)
         Layer shortL(3000, 21);
         Files f(dir, "short", shortL, 0, 0);
         gs_tier_ctx *ctx = nullptr;
-        CHECK(gs_tier_ctx_create(&ctx, 1024, 2) == GS_OK, "create");
+        CHECK(gs_tier_ctx_create(&ctx, 1024, 2, 0) == GS_OK, "create");
         gs_tier_layer d{nullptr, nullptr, nullptr, 0, f.fd[0], f.fd[1], f.fd[2], 0, 0, 0};
         CHECK(gs_tier_layer_step(ctx, &d, A.w.data(), gt, 1, A.n, &HP, nullptr, nullptr) == GS_ERR_IO, "short file accepted");
         CHECK(strstr(gs_tier_ctx_error(ctx), "pread") != nullptr, "error text: '%s'", gs_tier_ctx_error(ctx));
@@ -231,7 +249,7 @@ static void test_tier_failures(const std::string &dir)
     {
         Files f(dir, "ro", A, 0, 0, O_RDONLY);
         gs_tier_ctx *ctx = nullptr;
-        CHECK(gs_tier_ctx_create(&ctx, 1024, 2) == GS_OK, "create");
+        CHECK(gs_tier_ctx_create(&ctx, 1024, 2, 0) == GS_OK, "create");
         gs_tier_layer d{nullptr, nullptr, nullptr, 0, f.fd[0], f.fd[1], f.fd[2], 0, 0, 0};
         gs_status st = gs_tier_layer_step(ctx, &d, A.w.data(), gt, 1, A.n, &HP, nullptr, nullptr);
         CHECK(st == GS_OK || st == GS_ERR_IO, "unexpected status %d", (int)st);
@@ -243,7 +261,7 @@ static void test_tier_failures(const std::string &dir)
     {
         Files f(dir, "args", A, 0, 0);
         gs_tier_ctx *ctx = nullptr;
-        CHECK(gs_tier_ctx_create(&ctx, 1024, 2) == GS_OK, "create");
+        CHECK(gs_tier_ctx_create(&ctx, 1024, 2, 0) == GS_OK, "create");
         gs_tier_layer d{nullptr, nullptr, nullptr, 0, f.fd[0], f.fd[1], f.fd[2], 0, 0, 0};
         gs_tier_layer bad = d;
         bad.n_host = A.n + 1;
@@ -271,10 +289,9 @@ int main(int argc, char **argv)
         return 2;
     }
     const std::string dir = argv[1];
-    hipmock_set_copy_delay_us(50);   // let the three streams really overlap
-    test_stream(20000, 4096, 2);
-    test_stream(20000, 3001, 3);
-    test_stream(777, 100000, 2);
+    hipmock_set_copy_delay_us(50);
+    test_stream(20000, 0);
+    test_stream(777, 16);
     test_tier(dir, 30000, 0, 4096, 2);
     test_tier(dir, 30000, 9999, 3001, 3);
     test_tier(dir, 30000, 30000, 4096, 2);

@@ -114,9 +114,7 @@ def test_grad_sqnorm_empty_accumulate_is_noop():
 
 
 def test_stream_api_rejects_without_gpu():
-    st, ctx = gs.gs_stream_ctx_create(0, 2, check=False)
-    assert st == gs.GS_ERR_INVALID_ARG and not ctx
-    st, ctx = gs.gs_stream_ctx_create(1024, 1, check=False)
+    st, ctx = gs.gs_stream_ctx_create(-1, check=False)
     assert st == gs.GS_ERR_INVALID_ARG and not ctx
     assert gs.gs_stream_ctx_sync(None, check=False) == gs.GS_ERR_INVALID_ARG
     assert gs.gs_stream_ctx_destroy(None, check=False) == gs.GS_ERR_INVALID_ARG
@@ -126,8 +124,8 @@ def test_stream_api_rejects_without_gpu():
 
 
 def test_tier_api_rejects_without_gpu():
-    for chunk, slots in ((0, 2), (1024, 1), (1024, 65), (-5, 3), ((1 << 34) + 1, 2)):
-        st, ctx = gs.gs_tier_ctx_create(chunk, slots, check=False)
+    for chunk, slots, cus in ((0, 2, 0), (1024, 1, 0), (1024, 65, 0), (-5, 3, 0), ((1 << 34) + 1, 2, 0), (1024, 2, -1)):
+        st, ctx = gs.gs_tier_ctx_create(chunk, slots, cus, check=False)
         assert st == gs.GS_ERR_INVALID_ARG and not ctx
     assert gs.gs_tier_ctx_sync(None, check=False) == gs.GS_ERR_INVALID_ARG
     assert gs.gs_tier_ctx_destroy(None, check=False) == gs.GS_ERR_INVALID_ARG

@@ -287,9 +287,10 @@ def test_step_reload_step_equals_two_steps():
 
 
 # ----------------------------------------------------------------------------- a8 streamed == resident
-@pytest.mark.parametrize("chunk,slots", [(1, 2), (7, 3), (4096, 2), (100_000, 3), (1 << 22, 2)])
-def test_streamed_equals_resident(chunk, slots):
-    n = 300 if chunk == 1 else (5000 if chunk == 7 else 2048 * 600 + 13)
+@pytest.mark.parametrize("n,cus", [(1, 0), (300, 0), (5000, 16), (2048 * 600 + 13, 0), (2048 * 600 + 13, 32)])
+def test_streamed_equals_resident(n, cus):
+    """States in pinned host memory, stepped in place over the link: bit for bit the resident
+    result, on an ordinary stream and on a CU-limited one."""
     case = DeviceCase(n, 4, seed=80)
     case.gpu_sqnorm()
     full = run_gpu_step(case, HP)
@@ -299,7 +300,7 @@ def test_streamed_equals_resident(chunk, slots):
     try:
         hp_.copy_(case.p.cpu()); hm_.copy_(case.m.cpu()); hv_.copy_(case.v.cpu())
         w = torch.zeros_like(case.w)
-        ctx = gs.gs_stream_ctx_create(chunk, slots)
+        ctx = gs.gs_stream_ctx_create(cus)
         gs.gs_stream_layer_step(ctx, pp, pm, pv, w, case.grads, n, HP, case.sq)
         gs.gs_stream_ctx_sync(ctx)
         gs.gs_stream_ctx_destroy(ctx)
@@ -312,23 +313,45 @@ def test_streamed_equals_resident(chunk, slots):
         gs.gs_pinned_free(pp); gs.gs_pinned_free(pm); gs.gs_pinned_free(pv)
 
 
-def test_streamed_two_layers_back_to_back_with_poisoned_slots():
-    """Two 'layers' enqueued on one context without a sync in between; results must match the
-    resident path, i.e. slot reuse is correctly ordered."""
-    n, chunk = 2048 * 200 + 5, 50_000
+def test_streamed_rejects_misaligned_host_arrays_and_bad_cu_counts():
+    n = 4096
+    case = DeviceCase(n, 1, seed=81)
+    t, ptr = gs.pinned_f32(n + 4)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    st, ctx = gs.gs_stream_ctx_create(cus + 1, check=False)
+    assert st == gs.GS_ERR_INVALID_ARG and not ctx
+    ctx = gs.gs_stream_ctx_create(0)
+    try:
+        for bad in (4, 8, 12):
+            assert gs.gs_stream_layer_step(ctx, ptr + bad, ptr, ptr, case.w, case.grads, n, HP, None,
+                                           check=False) == gs.GS_ERR_INVALID_ARG
+    finally:
+        gs.gs_stream_ctx_destroy(ctx)
+        del t
+        gs.gs_pinned_free(ptr)
+
+
+def test_streamed_two_layers_back_to_back_after_a_producer_stream():
+    """Two 'layers' enqueued on one context without a sync in between, their norm produced on
+    another stream right before: results must match the resident path."""
+    n = 2048 * 200 + 5
     cases = [DeviceCase(n, 2, seed=90), DeviceCase(n, 2, seed=91)]
-    ctx = gs.gs_stream_ctx_create(chunk, 2)
+    ctx = gs.gs_stream_ctx_create(16)
+    prod = torch.cuda.Stream()
     held = []
     try:
         outs = []
         for case in cases:
-            case.gpu_sqnorm()
             bufs = [gs.pinned_f32(n) for _ in range(3)]
             held.append(bufs)
             for (t, _), src in zip(bufs, (case.p, case.m, case.v)):
                 t.copy_(src.cpu())
             w = torch.zeros_like(case.w)
-            gs.gs_stream_layer_step(ctx, bufs[0][1], bufs[1][1], bufs[2][1], w, case.grads, n, HP, case.sq)
+            torch.cuda.synchronize()
+            with torch.cuda.stream(prod):
+                gs.gs_grad_sqnorm(case.grads, 0, n, case.sq, case.ws, stream=prod)
+            gs.gs_stream_layer_step(ctx, bufs[0][1], bufs[1][1], bufs[2][1], w, case.grads, n, HP, case.sq,
+                                    producer_stream=prod)
             outs.append(w)
         gs.gs_stream_ctx_sync(ctx)
         for case, bufs, w in zip(cases, held, outs):
@@ -367,17 +390,18 @@ def _read_states(paths, count, header):
     return out
 
 
-@pytest.mark.parametrize("x,chunk,slots", [(0.0, 100_003, 2), (0.37, 65_536, 3), (1.0, 100_003, 2), (0.5, 10**7, 2)])
-def test_tiered_equals_resident_and_oracle(tmp_path, x, chunk, slots):
+@pytest.mark.parametrize("x,chunk,slots,cus", [(0.0, 100_003, 2, 0), (0.37, 65_536, 3, 16), (1.0, 100_003, 2, 0),
+                                               (0.5, 10**7, 2, 0), (0.25, 1, 2, 0)])
+def test_tiered_equals_resident_and_oracle(tmp_path, x, chunk, slots, cus):
     """States split between pinned host memory (share x, the storage ratio) and files: two steps
     in a row give bit for bit what the resident step gives, and the first matches the oracle."""
-    n, k, header = 512 * 900 + 77, 4, 24
+    n, k, header = (512 * 900 + 77, 4, 24) if chunk > 1 else (203, 4, 24)
     case = DeviceCase(n, k, seed=95)
     n_host = int(round(x * n))
     init = [np_f32(t) for t in (case.p, case.m, case.v)]
     fds, paths = _write_states(tmp_path, "L", init, n_host, header)
     bufs = [gs.pinned_f32(max(n_host, 1)) for _ in range(3)]
-    ctx = gs.gs_tier_ctx_create(chunk, slots)
+    ctx = gs.gs_tier_ctx_create(chunk, slots, cus)
     try:
         for (tn, _), a in zip(bufs, init):
             tn[:n_host].copy_(torch.from_numpy(a[:n_host]))
