@@ -257,14 +257,28 @@ typedef struct gs_stream_ctx gs_stream_ctx;
  * GS_ERR_INVALID_ARG.
  */
 gs_status gs_stream_ctx_create(gs_stream_ctx **out, int num_cus);
+
+/*
+ * The same, as a copy-engine pipeline: the context owns an upload stream, a compute stream, a
+ * download stream and `slots` (2..64) staging slots of 3 x chunk_elems fp32 in device memory
+ * (chunk_elems in [1, 2^34]); gs_stream_layer_step then walks the layer in chunks -- chunk c+1
+ * is uploaded with hipMemcpyAsync while the kernel updates chunk c in its slot and chunk c-1 is
+ * copied back.  Costs no CU time beyond the short kernel per chunk, and was the faster way at
+ * its best (48 against 44-45 GB/s each way), but how fast a copy runs is the runtime's choice
+ * of copy path.  Same results bit for bit.  GS_ERR_NOMEM if the slots cannot be allocated.
+ */
+gs_status gs_stream_ctx_create_staged(gs_stream_ctx **out, int64_t chunk_elems, int slots);
 gs_status gs_stream_ctx_destroy(gs_stream_ctx *ctx); /* waits for pending work, frees everything */
 
 /*
  * Applies the same update as gs_accum_adamw to all n elements of a layer whose p, m, v are in
- * PINNED host memory, in place, on the context's stream.  Results are bit-identical to
- * gs_accum_adamw on a device copy of the same states.
+ * PINNED host memory, updating them in place: by the kernel itself on the context's stream, or
+ * chunk by chunk through the staging slots of a context from gs_stream_ctx_create_staged.
+ * Results are bit-identical to gs_accum_adamw on a device copy of the same states, in both
+ * modes and for every chunk size.
  *   h_p, h_m, h_v   pinned host fp32 (device-accessible, as hipHostMalloc / gs_pinned_alloc
- *                   give it), n elements each, 16-byte aligned, updated in place
+ *                   give it), n elements each, 16-byte aligned (a staged context accepts
+ *                   4-byte alignment), updated in place
  *   d_w_bf16        device bf16, n elements, written
  *   d_grads         host array of k device pointers (bf16, n elements each)
  *   d_sqnorm        as for gs_accum_adamw (device double or NULL)

@@ -2,25 +2,31 @@
 //
 // The paper's optimizer step walks parameter chunks: load a chunk's master parameters and
 // optimizer states, step, write them back (Sec. 2.2), pipelined against the surrounding work
-// (Sec. 4.3).  There the slow link is SSD<->host; here it is host<->HBM over PCIe, and the
-// pipeline is the GPU's own: the step kernel runs IN PLACE on the pinned host arrays, so every
+// (Sec. 4.3).  There the slow link is SSD<->host; here it is host<->HBM over PCIe.  Two ways:
+//
+// In place (the default).  The step kernel runs on the pinned host arrays themselves, so every
 // wave loads its tile of p/m/v over the link, updates it and stores it back, thousands of waves
 // at different stages at any time.  Nothing is staged in HBM and no copy engine is involved.
+// Measured on MI355X (GPT-65B-shaped layers, k = 8): 44-45 GB/s each way at once, the same on a
+// stream confined to 16 of the 256 CUs, and the same whatever copy traffic the process ran
+// before.
 //
-// Measured on MI355X (one GPT-65B-shaped layer and more, k = 8): 44-45 GB/s each way at once,
-// the same on a stream confined to 16 of the 256 CUs, and the same whatever copy traffic the
-// process ran before.  The staged alternative (copy-engine upload into HBM slots, kernel in
-// HBM, copy back) reached 48 GB/s each way at best but depends on which engine the runtime
-// picks per copy: the same code was seen at 28 GB/s after unrelated copies on other streams, and
-// its device-to-host copies at a quarter of the link rate under the file tier's load.
+// Staged.  Chunk c+1 is uploaded by hipMemcpyAsync into one of `slots` staging slots in HBM while
+// the kernel updates chunk c there and chunk c-1 is copied back: three streams, events per slot.
+// It costs no CU time beyond the 0.5 ms kernel per chunk and reached 48 GB/s each way at its
+// best, but its rate is in the runtime's hands: which copy path a copy takes (under the file
+// tier's load its device-to-host copies were seen on the DMA engine at 12.8 GB/s) and which
+// hardware queue a stream lands on (upload and download on one queue: 28 GB/s each way).
 //
-// The kernel is the resident one, handed base pointers such that base[i] is element i of the
-// layer, so its 4-element groups fall on the same absolute indices and the result is
-// bit-identical to the device-resident step.
+// Either way the kernel is the resident one, handed base pointers such that base[i] is element i
+// of the layer (staged: chunk [b,e) sits at offset (b mod 8) of its slot), so its 4-element
+// groups fall on the same absolute indices and the result is bit-identical to the
+// device-resident step.
 #include <hip/hip_runtime.h>
 
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "gs_internal.h"
 #include "gs_stream_internal.h"
@@ -30,7 +36,13 @@ using namespace gs;
 static void destroy_partial(gs_stream_ctx *c)
 {
     if (!c) return;
+    for (auto e : c->ev_h2d) if (e) (void)hipEventDestroy(e);
+    for (auto e : c->ev_comp) if (e) (void)hipEventDestroy(e);
+    for (auto e : c->ev_d2h) if (e) (void)hipEventDestroy(e);
     if (c->ev_producer) (void)hipEventDestroy(c->ev_producer);
+    if (c->pool) (void)hipFree(c->pool);
+    if (c->s_h2d) (void)hipStreamDestroy(c->s_h2d);
+    if (c->s_d2h) (void)hipStreamDestroy(c->s_d2h);
     if (c->s_comp) (void)hipStreamDestroy(c->s_comp);
     if (c->s_note) (void)hipStreamDestroy(c->s_note);
     delete c;
@@ -99,7 +111,73 @@ gs_status stream_range(gs_stream_ctx *c, StepArgs &A, float *host_p, float *host
     return GS_OK;
 }
 
+// Staged mode: one chunk through upload -> kernel in its HBM slot -> download.
+static gs_status staged_chunk(gs_stream_ctx *c, StepArgs &A, float *host_p, float *host_m, float *host_v, int64_t b,
+                              int64_t e)
+{
+    const int64_t len = e - b;
+    const int slot = (int)(c->next_chunk % c->slots);
+    c->next_chunk++;
+    const int64_t pad = b & 7;
+    float *sp = c->pool + (size_t)slot * 3u * (size_t)c->slot_elems;
+    float *sm = sp + c->slot_elems;
+    float *sv = sm + c->slot_elems;
+    const size_t bytes = (size_t)len * sizeof(float);
+
+    // upload: wait until the slot's previous download has drained
+    if (c->used[slot]) GS_TRY(hipStreamWaitEvent(c->s_h2d, c->ev_d2h[slot], 0), "hipStreamWaitEvent(slot free)");
+    GS_TRY(hipMemcpyAsync(sp + pad, host_p, bytes, hipMemcpyHostToDevice, c->s_h2d), "hipMemcpyAsync(H2D p)");
+    GS_TRY(hipMemcpyAsync(sm + pad, host_m, bytes, hipMemcpyHostToDevice, c->s_h2d), "hipMemcpyAsync(H2D m)");
+    GS_TRY(hipMemcpyAsync(sv + pad, host_v, bytes, hipMemcpyHostToDevice, c->s_h2d), "hipMemcpyAsync(H2D v)");
+    GS_TRY(hipEventRecord(c->ev_h2d[slot], c->s_h2d), "hipEventRecord(h2d)");
+
+    // compute: base pointers chosen so that base[i] is element i of the layer
+    GS_TRY(hipStreamWaitEvent(c->s_comp, c->ev_h2d[slot], 0), "hipStreamWaitEvent(h2d)");
+    const intptr_t shift = (intptr_t)(pad - b) * (intptr_t)sizeof(float);
+    A.po = reinterpret_cast<float *>(reinterpret_cast<intptr_t>(sp) + shift);
+    A.mo = reinterpret_cast<float *>(reinterpret_cast<intptr_t>(sm) + shift);
+    A.vo = reinterpret_cast<float *>(reinterpret_cast<intptr_t>(sv) + shift);
+    A.p = A.po;
+    A.m = A.mo;
+    A.v = A.vo;
+    A.begin = b;
+    A.end = e;
+    hipError_t le = launch_accum_adamw(A, c->s_comp);
+    if (le != hipSuccess) return hip_fail(le, "staged step launch");
+    GS_TRY(hipEventRecord(c->ev_comp[slot], c->s_comp), "hipEventRecord(compute)");
+
+    // download
+    GS_TRY(hipStreamWaitEvent(c->s_d2h, c->ev_comp[slot], 0), "hipStreamWaitEvent(compute)");
+    GS_TRY(hipMemcpyAsync(host_p, sp + pad, bytes, hipMemcpyDeviceToHost, c->s_d2h), "hipMemcpyAsync(D2H p)");
+    GS_TRY(hipMemcpyAsync(host_m, sm + pad, bytes, hipMemcpyDeviceToHost, c->s_d2h), "hipMemcpyAsync(D2H m)");
+    GS_TRY(hipMemcpyAsync(host_v, sv + pad, bytes, hipMemcpyDeviceToHost, c->s_d2h), "hipMemcpyAsync(D2H v)");
+    GS_TRY(hipEventRecord(c->ev_d2h[slot], c->s_d2h), "hipEventRecord(d2h)");
+    c->used[slot] = 1;
+    return GS_OK;
+}
+
 }  // namespace gs
+
+// the compute stream and the producer event, common to both modes
+static gs_status create_common(gs_stream_ctx *c, int num_cus)
+{
+    hipError_t e;
+    // default priority on every stream
+    if (num_cus > 0) {
+        void *s = nullptr;
+        gs_status st = gs_cu_stream_create(&s, num_cus);
+        if (st != GS_OK) return st;
+        c->s_comp = static_cast<hipStream_t>(s);
+    } else if ((e = hipStreamCreateWithFlags(&c->s_comp, hipStreamNonBlocking)) != hipSuccess) {
+        c->s_comp = nullptr;
+        return hip_fail(e, "hipStreamCreateWithFlags");
+    }
+    if ((e = hipEventCreateWithFlags(&c->ev_producer, hipEventDisableTiming)) != hipSuccess) {
+        c->ev_producer = nullptr;
+        return hip_fail(e, "hipEventCreateWithFlags");
+    }
+    return GS_OK;
+}
 
 extern "C" {
 
@@ -113,28 +191,80 @@ gs_status gs_stream_ctx_create(gs_stream_ctx **out, int num_cus)
     if (!c) return GS_ERR_NOMEM;
     c->num_cus = num_cus;
     hipError_t e = hipGetDevice(&c->device);
-    if (e != hipSuccess) { destroy_partial(c); return hip_fail(e, "hipGetDevice"); }
-
-    // default priority on every stream
-    if (num_cus > 0) {
-        void *s = nullptr;
-        gs_status st = gs_cu_stream_create(&s, num_cus);
-        if (st != GS_OK) { destroy_partial(c); return st; }
-        c->s_comp = static_cast<hipStream_t>(s);
-    } else if ((e = hipStreamCreateWithFlags(&c->s_comp, hipStreamNonBlocking)) != hipSuccess) {
-        c->s_comp = nullptr;
+    if (e != hipSuccess) {
         destroy_partial(c);
-        return hip_fail(e, "hipStreamCreateWithFlags");
+        return hip_fail(e, "hipGetDevice");
+    }
+    gs_status st = create_common(c, num_cus);
+    if (st != GS_OK) {
+        destroy_partial(c);
+        return st;
     }
     if ((e = hipStreamCreateWithFlags(&c->s_note, hipStreamNonBlocking)) != hipSuccess) {
         c->s_note = nullptr;
         destroy_partial(c);
         return hip_fail(e, "hipStreamCreateWithFlags");
     }
-    if ((e = hipEventCreateWithFlags(&c->ev_producer, hipEventDisableTiming)) != hipSuccess) {
-        c->ev_producer = nullptr;
+    *out = c;
+    return GS_OK;
+}
+
+gs_status gs_stream_ctx_create_staged(gs_stream_ctx **out, int64_t chunk_elems, int slots)
+{
+    if (!out) return GS_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (chunk_elems < 1 || slots < 2 || slots > 64) return GS_ERR_INVALID_ARG;
+    if (chunk_elems > ((int64_t)1 << 34)) return GS_ERR_INVALID_ARG;
+
+    gs_stream_ctx *c = new (std::nothrow) gs_stream_ctx();
+    if (!c) return GS_ERR_NOMEM;
+    c->staged = true;
+    c->chunk = chunk_elems;
+    c->slots = slots;
+    c->slot_elems = ((chunk_elems + 8 + 63) / 64) * 64;   // keep every slot array 256-byte aligned
+    hipError_t e = hipGetDevice(&c->device);
+    if (e != hipSuccess) {
         destroy_partial(c);
-        return hip_fail(e, "hipEventCreateWithFlags");
+        return hip_fail(e, "hipGetDevice");
+    }
+    // Exactly three streams, created back to back: HIP multiplexes a process's streams onto a few
+    // hardware queues (4 here), and two of these three landing on one queue serialises the two
+    // copy directions (28 instead of 48 GB/s each way was measured when that happened).
+    if ((e = hipStreamCreateWithFlags(&c->s_h2d, hipStreamNonBlocking)) != hipSuccess) {
+        c->s_h2d = nullptr;
+        destroy_partial(c);
+        return hip_fail(e, "hipStreamCreateWithFlags");
+    }
+    gs_status st = create_common(c, 0);
+    if (st != GS_OK) {
+        destroy_partial(c);
+        return st;
+    }
+    if ((e = hipStreamCreateWithFlags(&c->s_d2h, hipStreamNonBlocking)) != hipSuccess) {
+        c->s_d2h = nullptr;
+        destroy_partial(c);
+        return hip_fail(e, "hipStreamCreateWithFlags");
+    }
+    const size_t bytes = (size_t)slots * 3u * (size_t)c->slot_elems * sizeof(float);
+    e = hipMalloc(reinterpret_cast<void **>(&c->pool), bytes);
+    if (e != hipSuccess) {
+        hip_fail(e, "hipMalloc(staging slots)");
+        (void)hipGetLastError();
+        c->pool = nullptr;
+        destroy_partial(c);
+        return GS_ERR_NOMEM;
+    }
+    c->ev_h2d.assign(slots, nullptr);
+    c->ev_comp.assign(slots, nullptr);
+    c->ev_d2h.assign(slots, nullptr);
+    c->used.assign(slots, 0);
+    for (int i = 0; i < slots; ++i) {
+        if ((e = hipEventCreateWithFlags(&c->ev_h2d[i], hipEventDisableTiming)) != hipSuccess ||
+            (e = hipEventCreateWithFlags(&c->ev_comp[i], hipEventDisableTiming)) != hipSuccess ||
+            (e = hipEventCreateWithFlags(&c->ev_d2h[i], hipEventDisableTiming)) != hipSuccess) {
+            destroy_partial(c);
+            return hip_fail(e, "hipEventCreateWithFlags");
+        }
     }
     *out = c;
     return GS_OK;
@@ -143,8 +273,10 @@ gs_status gs_stream_ctx_create(gs_stream_ctx **out, int num_cus)
 gs_status gs_stream_ctx_sync(gs_stream_ctx *c)
 {
     if (!c) return GS_ERR_INVALID_ARG;
+    if (c->s_h2d) GS_TRY(hipStreamSynchronize(c->s_h2d), "hipStreamSynchronize(h2d)");
     GS_TRY(hipStreamSynchronize(c->s_comp), "hipStreamSynchronize(compute)");
-    GS_TRY(hipStreamSynchronize(c->s_note), "hipStreamSynchronize(notify)");
+    if (c->s_d2h) GS_TRY(hipStreamSynchronize(c->s_d2h), "hipStreamSynchronize(d2h)");
+    if (c->s_note) GS_TRY(hipStreamSynchronize(c->s_note), "hipStreamSynchronize(notify)");
     return GS_OK;
 }
 
@@ -162,7 +294,9 @@ gs_status gs_stream_layer_step(gs_stream_ctx *c, float *h_p, float *h_m, float *
                                void *producer_stream)
 {
     if (!c || !h_p || !h_m || !h_v) return GS_ERR_INVALID_ARG;
-    if ((reinterpret_cast<uintptr_t>(h_p) | reinterpret_cast<uintptr_t>(h_m) | reinterpret_cast<uintptr_t>(h_v)) & 15u)
+    // in place the kernel's 16-byte accesses hit the host arrays; staged, only copies do
+    const uintptr_t align_mask = c->staged ? 3u : 15u;
+    if ((reinterpret_cast<uintptr_t>(h_p) | reinterpret_cast<uintptr_t>(h_m) | reinterpret_cast<uintptr_t>(h_v)) & align_mask)
         return GS_ERR_INVALID_ARG;
     gs_status st = stream_validate(c, d_w_bf16, d_grads, k, n, hp, d_sqnorm);
     if (st != GS_OK) return st;
@@ -171,7 +305,13 @@ gs_status gs_stream_layer_step(gs_stream_ctx *c, float *h_p, float *h_m, float *
     StepArgs A;
     st = stream_begin_layer(c, A, d_w_bf16, d_grads, k, hp, d_sqnorm, producer_stream);
     if (st != GS_OK) return st;
-    return stream_range(c, A, h_p, h_m, h_v, 0, n);
+    if (!c->staged) return stream_range(c, A, h_p, h_m, h_v, 0, n);
+    for (int64_t b = 0; b < n; b += c->chunk) {
+        const int64_t e = (b + c->chunk < n) ? b + c->chunk : n;
+        st = staged_chunk(c, A, h_p + b, h_m + b, h_v + b, b, e);
+        if (st != GS_OK) return st;
+    }
+    return GS_OK;
 }
 
 }  // extern "C"

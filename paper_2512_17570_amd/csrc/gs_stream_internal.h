@@ -5,14 +5,27 @@
 
 #include <hip/hip_runtime_api.h>
 
+#include <vector>
+
 #include "gs_internal.h"
 
 struct gs_stream_ctx {
     int device = 0;
-    int num_cus = 0;                        // 0: the compute stream may use every CU
+    bool staged = false;                    // false: kernel in place on host memory; true: copy-engine pipeline
+    int num_cus = 0;                        // in-place mode; 0: the compute stream may use every CU
     hipStream_t s_comp = nullptr;           // the step kernels
     hipStream_t s_note = nullptr;           // carries only host-function notifications (file tier)
     hipEvent_t ev_producer = nullptr;
+
+    // staged mode only
+    int64_t chunk = 0;
+    int slots = 0;
+    int64_t slot_elems = 0;                 // chunk + 8 (room for the (b mod 8) offset), rounded up
+    hipStream_t s_h2d = nullptr, s_d2h = nullptr;
+    float *pool = nullptr;                  // slots * 3 * slot_elems floats of device memory
+    std::vector<hipEvent_t> ev_h2d, ev_comp, ev_d2h;
+    std::vector<char> used;                 // ev_d2h[slot] has been recorded at least once
+    int64_t next_chunk = 0;                 // running chunk counter across calls -> slot rotation
 };
 
 namespace gs {

@@ -90,6 +90,8 @@ _lib.gs_cu_stream_create.restype = ctypes.c_int
 _lib.gs_cu_stream_destroy.argtypes = [_vp]
 _lib.gs_cu_stream_destroy.restype = ctypes.c_int
 _lib.gs_stream_ctx_create.argtypes = [ctypes.POINTER(_vp), ctypes.c_int]
+_lib.gs_stream_ctx_create_staged.argtypes = [ctypes.POINTER(_vp), _i64, ctypes.c_int]
+_lib.gs_stream_ctx_create_staged.restype = ctypes.c_int
 _lib.gs_stream_ctx_create.restype = ctypes.c_int
 _lib.gs_stream_ctx_destroy.argtypes = [_vp]
 _lib.gs_stream_ctx_destroy.restype = ctypes.c_int
@@ -292,6 +294,15 @@ def gs_stream_ctx_create(num_cus: int = 0, check: bool = True):
     st = _lib.gs_stream_ctx_create(ctypes.byref(out), num_cus)
     if check:
         _check(st, "gs_stream_ctx_create", True)
+        return out.value
+    return st, out.value
+
+
+def gs_stream_ctx_create_staged(chunk_elems: int, slots: int = 3, check: bool = True):
+    out = ctypes.c_void_p()
+    st = _lib.gs_stream_ctx_create_staged(ctypes.byref(out), chunk_elems, slots)
+    if check:
+        _check(st, "gs_stream_ctx_create_staged", True)
         return out.value
     return st, out.value
 

@@ -93,11 +93,13 @@ struct Layer {
     }
 };
 
-static void test_stream(int64_t n, int num_cus)
+// chunk > 0: the staged copy-engine pipeline with that chunk size; else the in-place step
+static void test_stream(int64_t n, int num_cus, int64_t chunk = 0, int slots = 0)
 {
     Layer A(n, 1), B(n / 2 + 3, 2);
     gs_stream_ctx *ctx = nullptr;
-    CHECK(gs_stream_ctx_create(&ctx, num_cus) == GS_OK, "create");
+    if (chunk > 0) CHECK(gs_stream_ctx_create_staged(&ctx, chunk, slots) == GS_OK, "create staged");
+    else CHECK(gs_stream_ctx_create(&ctx, num_cus) == GS_OK, "create");
     float *hp_[2][3];
     Layer *Ls[2] = {&A, &B};
     for (int l = 0; l < 2; ++l) {
@@ -129,10 +131,11 @@ static void test_stream(int64_t n, int num_cus)
             Ls[l]->check_w(1, "host-resident");
         }
     }
-    // a misaligned host array is refused
+    // a host array that is not 16-byte aligned is refused in place (staged: only copies touch it)
     const uint16_t *gt[1] = {A.g.data()};
-    CHECK(gs_stream_layer_step(ctx, hp_[0][0] + 1, hp_[0][1], hp_[0][2], A.w.data(), gt, 1, 16, &HP, nullptr, nullptr) ==
-              GS_ERR_INVALID_ARG, "misaligned host array accepted");
+    if (chunk == 0)
+        CHECK(gs_stream_layer_step(ctx, hp_[0][0] + 1, hp_[0][1], hp_[0][2], A.w.data(), gt, 1, 16, &HP, nullptr, nullptr) ==
+                  GS_ERR_INVALID_ARG, "misaligned host array accepted");
     CHECK(gs_stream_ctx_destroy(ctx) == GS_OK, "destroy");
     CHECK(hipStreamDestroy(producer) == hipSuccess, "producer stream destroy");
     for (int l = 0; l < 2; ++l)
@@ -292,6 +295,9 @@ int main(int argc, char **argv)
     hipmock_set_copy_delay_us(50);
     test_stream(20000, 0);
     test_stream(777, 16);
+    test_stream(20000, 0, 4096, 2);
+    test_stream(20000, 0, 3001, 3);
+    test_stream(777, 0, 100000, 2);
     test_tier(dir, 30000, 0, 4096, 2);
     test_tier(dir, 30000, 9999, 3001, 3);
     test_tier(dir, 30000, 30000, 4096, 2);

@@ -313,6 +313,62 @@ def test_streamed_equals_resident(n, cus):
         gs.gs_pinned_free(pp); gs.gs_pinned_free(pm); gs.gs_pinned_free(pv)
 
 
+@pytest.mark.parametrize("chunk,slots", [(1, 2), (7, 3), (4096, 2), (100_000, 3), (1 << 22, 2)])
+def test_staged_pipeline_equals_resident(chunk, slots):
+    """The copy-engine pipeline: upload | kernel in an HBM slot | download, for chunk sizes from one
+    element to more than the layer, host arrays only 4-byte aligned."""
+    n = 300 if chunk == 1 else (5000 if chunk == 7 else 2048 * 600 + 13)
+    case = DeviceCase(n, 4, seed=80)
+    case.gpu_sqnorm()
+    full = run_gpu_step(case, HP)
+    bufs = [gs.pinned_f32(n + 1) for _ in range(3)]
+    try:
+        for (t, _), src in zip(bufs, (case.p, case.m, case.v)):
+            t[1:].copy_(src.cpu())                       # element 0 of each array sits at offset 4 bytes
+        w = torch.zeros_like(case.w)
+        ctx = gs.gs_stream_ctx_create_staged(chunk, slots)
+        gs.gs_stream_layer_step(ctx, *(ptr + 4 for _, ptr in bufs), w, case.grads, n, HP, case.sq)
+        gs.gs_stream_ctx_sync(ctx)
+        gs.gs_stream_ctx_destroy(ctx)
+        for (t, _), ref in zip(bufs, full[:3]):
+            assert np.array_equal(t[1:].numpy(), np_f32(ref))
+        assert torch.equal(w, full[3])
+    finally:
+        for t, ptr in bufs:
+            gs.gs_pinned_free(ptr)
+
+
+def test_staged_pipeline_two_layers_back_to_back_reuse_slots():
+    """Two 'layers' enqueued on one staged context without a sync in between; results must match
+    the resident path, i.e. slot reuse is correctly ordered."""
+    n, chunk = 2048 * 200 + 5, 50_000
+    cases = [DeviceCase(n, 2, seed=90), DeviceCase(n, 2, seed=91)]
+    ctx = gs.gs_stream_ctx_create_staged(chunk, 2)
+    held = []
+    try:
+        outs = []
+        for case in cases:
+            case.gpu_sqnorm()
+            bufs = [gs.pinned_f32(n) for _ in range(3)]
+            held.append(bufs)
+            for (t, _), src in zip(bufs, (case.p, case.m, case.v)):
+                t.copy_(src.cpu())
+            w = torch.zeros_like(case.w)
+            gs.gs_stream_layer_step(ctx, bufs[0][1], bufs[1][1], bufs[2][1], w, case.grads, n, HP, case.sq)
+            outs.append(w)
+        gs.gs_stream_ctx_sync(ctx)
+        for case, bufs, w in zip(cases, held, outs):
+            full = run_gpu_step(case, HP)
+            for (t, _), ref in zip(bufs, full[:3]):
+                assert np.array_equal(t.numpy(), np_f32(ref))
+            assert torch.equal(w, full[3])
+    finally:
+        gs.gs_stream_ctx_destroy(ctx)
+        for bufs in held:
+            for t, ptr in bufs:
+                gs.gs_pinned_free(ptr)
+
+
 def test_streamed_rejects_misaligned_host_arrays_and_bad_cu_counts():
     n = 4096
     case = DeviceCase(n, 1, seed=81)

@@ -60,6 +60,14 @@ def test_pipelines_move_every_element_once_and_are_race_free(tmp_path, tsan_ok):
 MUTANTS = [
     ("kernel_ignores_producer", "gs_stream.hip",
      '    GS_TRY(hipStreamWaitEvent(c->s_comp, c->ev_producer, 0), "hipStreamWaitEvent(producer)");\n', ""),
+    ("staged_upload_ignores_pending_download", "gs_stream.hip",
+     '    if (c->used[slot]) GS_TRY(hipStreamWaitEvent(c->s_h2d, c->ev_d2h[slot], 0), "hipStreamWaitEvent(slot free)");\n', ""),
+    ("staged_kernel_ignores_upload", "gs_stream.hip",
+     '    GS_TRY(hipStreamWaitEvent(c->s_comp, c->ev_h2d[slot], 0), "hipStreamWaitEvent(h2d)");\n', ""),
+    ("staged_download_ignores_kernel", "gs_stream.hip",
+     '    GS_TRY(hipStreamWaitEvent(c->s_d2h, c->ev_comp[slot], 0), "hipStreamWaitEvent(compute)");\n', ""),
+    ("staged_chunk_lands_at_wrong_slot_offset", "gs_stream.hip",
+     "    const intptr_t shift = (intptr_t)(pad - b) * (intptr_t)sizeof(float);", "    const intptr_t shift = (intptr_t)(-b) * (intptr_t)sizeof(float);"),
     ("notification_ignores_kernel", "gs_tier.hip",
      "            if (he == hipSuccess) he = hipStreamWaitEvent(c->s_note, t->ev_done[slot], 0);\n", ""),
     ("read_into_slot_still_being_written", "gs_tier.hip",
@@ -82,7 +90,8 @@ def test_mutation_sites_exist_once():
 
 @pytest.mark.parametrize("name,fn,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
 def test_harness_notices_planted_pipeline_mistake(tmp_path, tsan_ok, name, fn, old, new):
-    if not tsan_ok and name in ("kernel_ignores_producer", "read_into_slot_still_being_written"):
+    if not tsan_ok and name in ("kernel_ignores_producer", "read_into_slot_still_being_written",
+                                "staged_upload_ignores_pending_download"):
         pytest.skip("without ThreadSanitizer this ordering mistake only shows by chance")
     src = tmp_path / "src"
     src.mkdir()
