@@ -287,3 +287,65 @@ def test_streamed_8_layers_h8192_equals_resident():
         del hp_t, hm_t, hv_t
         for t, ptr in bufs:
             gs.gs_pinned_free(ptr)
+
+
+@pytest.mark.timeout(900)
+def test_tiered_one_layer_h8192_equals_resident(tmp_path):
+    """One GPT-65B-shaped layer with half of its states in pinned host memory and half in files
+    (the tiered workload's split and chunk size): bit for bit the resident result, and the oracle
+    on windows at the head, across the host/file boundary, across a file-chunk boundary and at the
+    ragged tail."""
+    import os
+    wl = I.WORKLOADS["gpt65b_2layers_tiered_k8"]
+    nl, k, chunk, x = I.layer_numel(wl.h), wl.k, wl.extra["chunk_elems"], wl.extra["host_share"]
+    n_host = int(round(x * nl))
+    hp = hp_of(wl)
+    pd, md, vd = I.make_states(nl, wl.seed, DEV)
+    grads = I.make_grads(nl, k, wl.grad_sigma, wl.seed, DEV)
+    sq = torch.zeros(1, dtype=torch.float64, device=DEV)
+    ws = torch.empty(gs.gs_sqnorm_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    gs.gs_grad_sqnorm(grads, 0, nl, sq, ws)
+    bufs = gs.pinned_f32_set(n_host, 3)
+    assert bufs is not None, "could not pin the host share"
+    fds, paths = [], []
+    try:
+        for name, (t, _), src in zip("pmv", bufs, (pd, md, vd)):
+            t.copy_(src[:n_host])
+            path = str(tmp_path / f"{name}.bin")
+            src[n_host:].cpu().numpy().tofile(path)
+            paths.append(path)
+            fds.append(os.open(path, os.O_RDWR))
+        print(f"[tiered] n={nl} n_host={n_host} file bytes={12 * (nl - n_host) / 1e9:.1f} GB chunk={chunk}", flush=True)
+        wins = [(0, 4000), (n_host - 3000, n_host + 3001), (n_host + chunk - 3000, n_host + chunk + 3001), (nl - 4000, nl)]
+        before = {lo: grab((pd, md, vd), lo, hi) for lo, hi in wins}
+        w = torch.zeros(nl, dtype=torch.bfloat16, device=DEV)
+        ctx = gs.gs_tier_ctx_create(chunk, 3, 16)
+        gs.gs_tier_layer_step(ctx, bufs[0][1], bufs[1][1], bufs[2][1], n_host, fds, (0, 0, 0), w, grads, nl, hp, sq)
+        gs.gs_tier_ctx_sync(ctx)
+        assert gs.gs_tier_ctx_error(ctx) == ""
+        gs.gs_tier_ctx_destroy(ctx)
+        print("[tiered] tiered pass done", flush=True)
+        wd = torch.zeros(nl, dtype=torch.bfloat16, device=DEV)
+        gs.gs_accum_adamw(pd, md, vd, wd, grads, 0, nl, hp, sq)
+        torch.cuda.synchronize()
+        assert torch.equal(w, wd)
+        for (t, _), path, ref, nm in zip(bufs, paths, (pd, md, vd), "pmv"):
+            assert torch.equal(t.to(DEV), ref[:n_host]), f"{nm}: host share != resident"
+            tail = np.memmap(path, dtype=np.float32, mode="r")
+            assert tail.shape[0] == nl - n_host
+            for lo in range(0, nl - n_host, 1 << 26):
+                hi = min(nl - n_host, lo + (1 << 26))
+                up = torch.from_numpy(np.array(tail[lo:hi])).to(DEV)
+                assert torch.equal(up, ref[n_host + lo:n_host + hi]), f"{nm}: file share [{lo}:{hi}) != resident"
+            del tail
+        c = O.clip_coef(float(sq.item()), hp.max_grad_norm)
+        after = {lo: grab((pd, md, vd), lo, hi) + [np_bf16(wd[lo:hi])] for lo, hi in wins}
+        check_windows(wins, before, after, grads, hp, c, "tiered")
+    finally:
+        for fd in fds:
+            os.close(fd)
+        for p_ in paths:
+            if os.path.exists(p_):
+                os.unlink(p_)
+        for _, ptr in bufs:
+            gs.gs_pinned_free(ptr)
