@@ -199,6 +199,81 @@ def bench_split(args, wl):
         budget[str(ncu)]["gemm_slowdown"] = budget[str(ncu)]["gemm_concurrent_ms"] / t_gemm
         del sc
         gs.gs_cu_stream_destroy(raw)
+    # A sequence of layers (Sec. 4.4: a layer's deferred update only has to be finished before that
+    # layer's forward of the next iteration): the forward of layer i (its four bf16 GEMMs for
+    # `tokens` tokens) waits for the event of layer i's deferred step; the deferred steps run in
+    # layer order on their own stream, so step i+1 overlaps forward i.  Every "layer" reuses the
+    # same state and weight tensors: this times the schedule, not the arithmetic.
+    seq_layers = 6
+    wq = torch.randn(wl.h, 3 * wl.h, dtype=torch.bfloat16, device=dev)
+    wo = gb
+    w1 = torch.randn(wl.h, 4 * wl.h, dtype=torch.bfloat16, device=dev)
+    w2 = torch.randn(4 * wl.h, wl.h, dtype=torch.bfloat16, device=dev)
+    o_q = torch.empty(tokens, 3 * wl.h, dtype=torch.bfloat16, device=dev)
+    o_1 = torch.empty(tokens, 4 * wl.h, dtype=torch.bfloat16, device=dev)
+
+    def forward_layer():
+        torch.matmul(ga, wq, out=o_q)
+        torch.matmul(ga, wo, out=gc)
+        torch.matmul(ga, w1, out=o_1)
+        torch.matmul(o_1, w2, out=gc)
+
+    def sequence(step_stream, overlap, reps):
+        def once():
+            evs = []
+            with torch.cuda.stream(step_stream):
+                for _ in range(seq_layers):
+                    deferred(step_stream)
+                    ev = torch.cuda.Event()
+                    ev.record(step_stream)
+                    evs.append(ev)
+            with torch.cuda.stream(sa):
+                if not overlap:
+                    sa.wait_event(evs[-1])
+                for i in range(seq_layers):
+                    if overlap:
+                        sa.wait_event(evs[i])
+                    forward_layer()
+            # the next iteration's steps follow this iteration's forward
+            done = torch.cuda.Event()
+            done.record(sa)
+            step_stream.wait_event(done)
+        once()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            once()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps * 1e3
+
+    with torch.cuda.stream(sa):
+        for _ in range(2):
+            forward_layer()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(sa):
+        e0.record(sa)
+        for _ in range(seq_layers):
+            forward_layer()
+        e1.record(sa)
+    torch.cuda.synchronize()
+    t_fwd_layer = e0.elapsed_time(e1) / seq_layers
+    seq_reps = max(2, args.steps // 4)
+    seq = {"layers": seq_layers, "forward_ms_per_layer_alone": t_fwd_layer,
+           "forward_TFLOPs_alone": 2.0 * tokens * wl.h * 12 * wl.h / (t_fwd_layer * 1e-3) / 1e12,
+           "deferred_ms_per_layer_alone": t_def,
+           "serial_ms": sequence(sb, False, seq_reps),
+           "overlapped_all_cus_ms": sequence(sb, True, seq_reps)}
+    for ncu in (cus // 4, cus // 2):
+        raw = gs.gs_cu_stream_create(ncu)
+        sc = torch.cuda.ExternalStream(raw)
+        seq[f"overlapped_{ncu}_cus_ms"] = sequence(sc, True, seq_reps)
+        del sc
+        gs.gs_cu_stream_destroy(raw)
+    seq["bound_ms"] = t_def + seq_layers * t_fwd_layer      # first step exposed, everything else hidden
+    seq["note"] = ("forward of layer i waits for layer i's deferred step; steps run in layer order on their own stream. "
+                   "bound = one exposed deferred step + the forwards at their solo speed")
+
     bpp = 2 * k + 26
     rec = _base_record(wl, props, n / ((t_imm + t_def) * 1e-3), args.steps, args.warmup, t_imm + t_def,
                        {"split_point": s_pt, "immediate_frac": wl.extra["immediate_frac"],
@@ -215,6 +290,7 @@ def bench_split(args, wl):
         "deferred_slowdown": t_def_c / t_def, "gemm_slowdown": t_gemm_c / t_gemm,
         "concurrent_wall_ms_per_iter": wall, "serial_ms_per_iter": t_def + reps_gemm * t_gemm,
         "deferred_on_cu_budget_stream": budget,
+        "layer_sequence": seq,
     }
     rec["cpu_baseline"] = None
     print(json.dumps(rec))
