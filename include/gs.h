@@ -242,43 +242,46 @@ gs_status gs_cu_stream_destroy(void *stream);
  * Step for states that live in pinned host memory (Sec. 2.2: for each parameter chunk, load
  * gradients + master parameters + optimizer states, step, write back; Sec. 4.3 the optimizer
  * stages of the backward pipeline -- here the slow link is host<->device PCIe instead of
- * SSD<->host).  The kernel runs in place on the host arrays: each wave loads its tile of p, m, v
- * over the link, updates it and stores it back; nothing is staged in device memory and no copy
- * engine is used, so the rate does not depend on the runtime's choice of copy path.
+ * SSD<->host).  A context fixes how the states cross the link: staged through device memory by
+ * the copy path (gs_stream_ctx_create), or touched in place by the kernel
+ * (gs_stream_ctx_create_inplace).  gs_stream_layer_step is the same call for both and gives
+ * the same bits.
  * ------------------------------------------------------------------------------------------ */
 
 typedef struct gs_stream_ctx gs_stream_ctx;
 
 /*
- * Creates a context that owns the stream the host-resident steps run on.  num_cus = 0: an
- * ordinary stream; num_cus >= 1: a stream confined to that many compute units, as from
- * gs_cu_stream_create (the link, not the CU count, bounds this step: 16 CUs sustain the full rate
- * and leave the rest of the GPU to other work).  num_cus < 0 or above the device's count is
- * GS_ERR_INVALID_ARG.
+ * Staged: the context owns an upload stream, a compute stream, a download stream, `slots`
+ * (2..64) staging slots of 3 x chunk_elems fp32 in device memory (chunk_elems in [1, 2^34]) and
+ * the events that order them; gs_stream_layer_step walks the layer in chunks -- chunk c+1 is
+ * uploaded with hipMemcpyAsync while the kernel updates chunk c in its slot and chunk c-1 is
+ * copied back.  Costs no CU time beyond the short kernel per chunk and measured 48 GB/s each way
+ * at its best, but how fast a copy runs is up to the runtime (copy path per copy, hardware queue
+ * per stream).  GS_ERR_NOMEM if the slots cannot be allocated.
  */
-gs_status gs_stream_ctx_create(gs_stream_ctx **out, int num_cus);
+gs_status gs_stream_ctx_create(gs_stream_ctx **out, int64_t chunk_elems, int slots);
 
 /*
- * The same, as a copy-engine pipeline: the context owns an upload stream, a compute stream, a
- * download stream and `slots` (2..64) staging slots of 3 x chunk_elems fp32 in device memory
- * (chunk_elems in [1, 2^34]); gs_stream_layer_step then walks the layer in chunks -- chunk c+1
- * is uploaded with hipMemcpyAsync while the kernel updates chunk c in its slot and chunk c-1 is
- * copied back.  Costs no CU time beyond the short kernel per chunk, and was the faster way at
- * its best (48 against 44-45 GB/s each way), but how fast a copy runs is the runtime's choice
- * of copy path.  Same results bit for bit.  GS_ERR_NOMEM if the slots cannot be allocated.
+ * In place: the context owns one stream, and the step kernel runs on the pinned host arrays
+ * themselves -- each wave loads its tile of p, m, v over the link, updates it and stores it
+ * back.  Nothing is staged in device memory and no copy engine is used: 44-45 GB/s each way,
+ * whatever else the process does with copies and streams.  num_cus = 0: an ordinary stream;
+ * num_cus >= 1: a stream confined to that many compute units, as from gs_cu_stream_create (the
+ * link, not the CU count, bounds this step: 16 CUs sustain the full rate and leave the rest of
+ * the GPU to other work).  num_cus < 0 or above the device's count is GS_ERR_INVALID_ARG.
  */
-gs_status gs_stream_ctx_create_staged(gs_stream_ctx **out, int64_t chunk_elems, int slots);
+gs_status gs_stream_ctx_create_inplace(gs_stream_ctx **out, int num_cus);
 gs_status gs_stream_ctx_destroy(gs_stream_ctx *ctx); /* waits for pending work, frees everything */
 
 /*
  * Applies the same update as gs_accum_adamw to all n elements of a layer whose p, m, v are in
- * PINNED host memory, updating them in place: by the kernel itself on the context's stream, or
- * chunk by chunk through the staging slots of a context from gs_stream_ctx_create_staged.
+ * PINNED host memory, updating them in place: chunk by chunk through the context's staging
+ * slots, or by the kernel itself if the context is from gs_stream_ctx_create_inplace.
  * Results are bit-identical to gs_accum_adamw on a device copy of the same states, in both
  * modes and for every chunk size.
  *   h_p, h_m, h_v   pinned host fp32 (device-accessible, as hipHostMalloc / gs_pinned_alloc
- *                   give it), n elements each, 16-byte aligned (a staged context accepts
- *                   4-byte alignment), updated in place
+ *                   give it), n elements each, updated in place; 4-byte aligned for a
+ *                   staged context, 16-byte aligned for an in-place one
  *   d_w_bf16        device bf16, n elements, written
  *   d_grads         host array of k device pointers (bf16, n elements each)
  *   d_sqnorm        as for gs_accum_adamw (device double or NULL)
@@ -317,7 +320,7 @@ typedef struct {
 } gs_tier_layer;
 
 /*
- * Creates a context: a gs_stream_ctx (num_cus as for gs_stream_ctx_create), `slots` (2..64) bounce
+ * Creates a context: a gs_stream_ctx (num_cus as for gs_stream_ctx_create_inplace), `slots` (2..64) bounce
  * slots of 3 x chunk_elems fp32 in pinned host memory (each array starts on a 4 KB boundary), and
  * one writer thread.  chunk_elems in [1, 2^34].  GS_ERR_NOMEM if the pinned memory cannot be had.
  */

@@ -181,7 +181,7 @@ static gs_status create_common(gs_stream_ctx *c, int num_cus)
 
 extern "C" {
 
-gs_status gs_stream_ctx_create(gs_stream_ctx **out, int num_cus)
+gs_status gs_stream_ctx_create_inplace(gs_stream_ctx **out, int num_cus)
 {
     if (!out) return GS_ERR_INVALID_ARG;
     *out = nullptr;
@@ -209,7 +209,7 @@ gs_status gs_stream_ctx_create(gs_stream_ctx **out, int num_cus)
     return GS_OK;
 }
 
-gs_status gs_stream_ctx_create_staged(gs_stream_ctx **out, int64_t chunk_elems, int slots)
+gs_status gs_stream_ctx_create(gs_stream_ctx **out, int64_t chunk_elems, int slots)
 {
     if (!out) return GS_ERR_INVALID_ARG;
     *out = nullptr;

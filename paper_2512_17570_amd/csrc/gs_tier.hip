@@ -243,7 +243,7 @@ gs_status gs_tier_ctx_create(gs_tier_ctx **out, int64_t chunk_elems, int slots, 
 
     gs_tier_ctx *t = new (std::nothrow) gs_tier_ctx();
     if (!t) return GS_ERR_NOMEM;
-    gs_status st = gs_stream_ctx_create(&t->sc, num_cus);
+    gs_status st = gs_stream_ctx_create_inplace(&t->sc, num_cus);
     if (st != GS_OK) {
         t->sc = nullptr;
         tier_free(t);

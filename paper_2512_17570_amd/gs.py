@@ -89,10 +89,10 @@ _lib.gs_cu_stream_create.argtypes = [ctypes.POINTER(_vp), ctypes.c_int]
 _lib.gs_cu_stream_create.restype = ctypes.c_int
 _lib.gs_cu_stream_destroy.argtypes = [_vp]
 _lib.gs_cu_stream_destroy.restype = ctypes.c_int
-_lib.gs_stream_ctx_create.argtypes = [ctypes.POINTER(_vp), ctypes.c_int]
-_lib.gs_stream_ctx_create_staged.argtypes = [ctypes.POINTER(_vp), _i64, ctypes.c_int]
-_lib.gs_stream_ctx_create_staged.restype = ctypes.c_int
+_lib.gs_stream_ctx_create_inplace.argtypes = [ctypes.POINTER(_vp), ctypes.c_int]
+_lib.gs_stream_ctx_create.argtypes = [ctypes.POINTER(_vp), _i64, ctypes.c_int]
 _lib.gs_stream_ctx_create.restype = ctypes.c_int
+_lib.gs_stream_ctx_create_inplace.restype = ctypes.c_int
 _lib.gs_stream_ctx_destroy.argtypes = [_vp]
 _lib.gs_stream_ctx_destroy.restype = ctypes.c_int
 _lib.gs_stream_ctx_sync.argtypes = [_vp]
@@ -289,20 +289,20 @@ def gs_cu_stream_destroy(stream, check: bool = True) -> int:
     return _check(_lib.gs_cu_stream_destroy(stream), "gs_cu_stream_destroy", check)
 
 
-def gs_stream_ctx_create(num_cus: int = 0, check: bool = True):
+def gs_stream_ctx_create_inplace(num_cus: int = 0, check: bool = True):
     out = ctypes.c_void_p()
-    st = _lib.gs_stream_ctx_create(ctypes.byref(out), num_cus)
+    st = _lib.gs_stream_ctx_create_inplace(ctypes.byref(out), num_cus)
     if check:
-        _check(st, "gs_stream_ctx_create", True)
+        _check(st, "gs_stream_ctx_create_inplace", True)
         return out.value
     return st, out.value
 
 
-def gs_stream_ctx_create_staged(chunk_elems: int, slots: int = 3, check: bool = True):
+def gs_stream_ctx_create(chunk_elems: int, slots: int = 3, check: bool = True):
     out = ctypes.c_void_p()
-    st = _lib.gs_stream_ctx_create_staged(ctypes.byref(out), chunk_elems, slots)
+    st = _lib.gs_stream_ctx_create(ctypes.byref(out), chunk_elems, slots)
     if check:
-        _check(st, "gs_stream_ctx_create_staged", True)
+        _check(st, "gs_stream_ctx_create", True)
         return out.value
     return st, out.value
 

@@ -98,8 +98,8 @@ static void test_stream(int64_t n, int num_cus, int64_t chunk = 0, int slots = 0
 {
     Layer A(n, 1), B(n / 2 + 3, 2);
     gs_stream_ctx *ctx = nullptr;
-    if (chunk > 0) CHECK(gs_stream_ctx_create_staged(&ctx, chunk, slots) == GS_OK, "create staged");
-    else CHECK(gs_stream_ctx_create(&ctx, num_cus) == GS_OK, "create");
+    if (chunk > 0) CHECK(gs_stream_ctx_create(&ctx, chunk, slots) == GS_OK, "create staged");
+    else CHECK(gs_stream_ctx_create_inplace(&ctx, num_cus) == GS_OK, "create");
     float *hp_[2][3];
     Layer *Ls[2] = {&A, &B};
     for (int l = 0; l < 2; ++l) {

@@ -25,7 +25,7 @@ def declared_functions():
 def test_header_symbols_all_exported():
     names = declared_functions()
     assert {"gs_grad_sqnorm", "gs_accum_adamw", "gs_stream_layer_step", "gs_sqnorm_workspace_bytes",
-            "gs_stream_ctx_create", "gs_stream_ctx_create_staged", "gs_stream_ctx_destroy", "gs_stream_ctx_sync", "gs_pinned_alloc",
+            "gs_stream_ctx_create_inplace", "gs_stream_ctx_create", "gs_stream_ctx_destroy", "gs_stream_ctx_sync", "gs_pinned_alloc",
             "gs_pinned_free", "gs_strerror", "gs_last_hip_error", "gs_grad_accum_sqnorm", "gs_adamw_from_acc",
             "gs_cu_stream_create", "gs_cu_stream_destroy", "gs_accum_adamw_oop", "gs_accum_adamw_spec",
             "gs_clip_coefficient", "gs_sqnorm_workspace_bytes_for", "gs_accum_add",
@@ -114,10 +114,10 @@ def test_grad_sqnorm_empty_accumulate_is_noop():
 
 
 def test_stream_api_rejects_without_gpu():
-    st, ctx = gs.gs_stream_ctx_create(-1, check=False)
+    st, ctx = gs.gs_stream_ctx_create_inplace(-1, check=False)
     assert st == gs.GS_ERR_INVALID_ARG and not ctx
     for chunk, slots in ((0, 2), (1024, 1), (1024, 65), ((1 << 34) + 1, 2)):
-        st, ctx = gs.gs_stream_ctx_create_staged(chunk, slots, check=False)
+        st, ctx = gs.gs_stream_ctx_create(chunk, slots, check=False)
         assert st == gs.GS_ERR_INVALID_ARG and not ctx
     assert gs.gs_stream_ctx_sync(None, check=False) == gs.GS_ERR_INVALID_ARG
     assert gs.gs_stream_ctx_destroy(None, check=False) == gs.GS_ERR_INVALID_ARG

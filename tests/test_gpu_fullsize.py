@@ -257,7 +257,7 @@ def test_streamed_8_layers_h8192_equals_resident():
         # a window that straddles a chunk boundary inside layer 0 and the ragged tail chunk of the last layer
         wins = [(chunk - 3000, chunk + 3001), (nl - 4000, nl)]
         before0 = {lo: [hp_t[lo:hi].numpy().copy(), hm_t[lo:hi].numpy().copy(), hv_t[lo:hi].numpy().copy()] for lo, hi in wins}
-        ctx = gs.gs_stream_ctx_create(16)      # 16 of the CUs carry the full link rate
+        ctx = gs.gs_stream_ctx_create_inplace(16)      # 16 of the CUs carry the full link rate
         for L in range(layers):
             o = L * nl * 4
             gs.gs_stream_layer_step(ctx, hp_p + o, hm_p + o, hv_p + o, w_l[L], grads_l[L], nl, hp, sq)

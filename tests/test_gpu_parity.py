@@ -300,7 +300,7 @@ def test_streamed_equals_resident(n, cus):
     try:
         hp_.copy_(case.p.cpu()); hm_.copy_(case.m.cpu()); hv_.copy_(case.v.cpu())
         w = torch.zeros_like(case.w)
-        ctx = gs.gs_stream_ctx_create(cus)
+        ctx = gs.gs_stream_ctx_create_inplace(cus)
         gs.gs_stream_layer_step(ctx, pp, pm, pv, w, case.grads, n, HP, case.sq)
         gs.gs_stream_ctx_sync(ctx)
         gs.gs_stream_ctx_destroy(ctx)
@@ -326,7 +326,7 @@ def test_staged_pipeline_equals_resident(chunk, slots):
         for (t, _), src in zip(bufs, (case.p, case.m, case.v)):
             t[1:].copy_(src.cpu())                       # element 0 of each array sits at offset 4 bytes
         w = torch.zeros_like(case.w)
-        ctx = gs.gs_stream_ctx_create_staged(chunk, slots)
+        ctx = gs.gs_stream_ctx_create(chunk, slots)
         gs.gs_stream_layer_step(ctx, *(ptr + 4 for _, ptr in bufs), w, case.grads, n, HP, case.sq)
         gs.gs_stream_ctx_sync(ctx)
         gs.gs_stream_ctx_destroy(ctx)
@@ -343,7 +343,7 @@ def test_staged_pipeline_two_layers_back_to_back_reuse_slots():
     the resident path, i.e. slot reuse is correctly ordered."""
     n, chunk = 2048 * 200 + 5, 50_000
     cases = [DeviceCase(n, 2, seed=90), DeviceCase(n, 2, seed=91)]
-    ctx = gs.gs_stream_ctx_create_staged(chunk, 2)
+    ctx = gs.gs_stream_ctx_create(chunk, 2)
     held = []
     try:
         outs = []
@@ -374,9 +374,9 @@ def test_streamed_rejects_misaligned_host_arrays_and_bad_cu_counts():
     case = DeviceCase(n, 1, seed=81)
     t, ptr = gs.pinned_f32(n + 4)
     cus = torch.cuda.get_device_properties(0).multi_processor_count
-    st, ctx = gs.gs_stream_ctx_create(cus + 1, check=False)
+    st, ctx = gs.gs_stream_ctx_create_inplace(cus + 1, check=False)
     assert st == gs.GS_ERR_INVALID_ARG and not ctx
-    ctx = gs.gs_stream_ctx_create(0)
+    ctx = gs.gs_stream_ctx_create_inplace(0)
     try:
         for bad in (4, 8, 12):
             assert gs.gs_stream_layer_step(ctx, ptr + bad, ptr, ptr, case.w, case.grads, n, HP, None,
@@ -392,7 +392,7 @@ def test_streamed_two_layers_back_to_back_after_a_producer_stream():
     another stream right before: results must match the resident path."""
     n = 2048 * 200 + 5
     cases = [DeviceCase(n, 2, seed=90), DeviceCase(n, 2, seed=91)]
-    ctx = gs.gs_stream_ctx_create(16)
+    ctx = gs.gs_stream_ctx_create_inplace(16)
     prod = torch.cuda.Stream()
     held = []
     try:
