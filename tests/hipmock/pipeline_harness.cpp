@@ -152,7 +152,7 @@ struct Files {
             path[a] = dir + "/" + tag + "_" + "pmv"[a] + ".bin";
             FILE *f = fopen(path[a].c_str(), "wb");
             std::vector<char> hdr((size_t)header_bytes, (char)0x5a);
-            fwrite(hdr.data(), 1, hdr.size(), f);
+            if (!hdr.empty()) fwrite(hdr.data(), 1, hdr.size(), f);
             fwrite(src[a]->data() + n_host, 4, (size_t)(L.n - n_host), f);
             fwrite("TAIL", 1, 4, f);
             fclose(f);
@@ -179,7 +179,7 @@ struct Files {
         for (int64_t i = 0; i < header_bytes && *frame_ok; ++i) *frame_ok = raw[(size_t)i] == (char)0x5a;
         if (*frame_ok) *frame_ok = memcmp(raw.data() + header_bytes + count * 4, "TAIL", 4) == 0;
         std::vector<float> out((size_t)count);
-        if (*frame_ok) memcpy(out.data(), raw.data() + header_bytes, (size_t)count * 4);
+        if (*frame_ok && count > 0) memcpy(out.data(), raw.data() + header_bytes, (size_t)count * 4);
         return out;
     }
 };

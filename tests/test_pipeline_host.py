@@ -20,10 +20,10 @@ MOCK = os.path.join(ROOT, "tests", "hipmock")
 HOST_SOURCES = ["gs_api.hip", "gs_stream.hip", "gs_tier.hip"]
 
 
-def _build(src_dir: str, out: str, tsan: bool) -> None:
+def _build(src_dir: str, out: str, tsan: bool, sanitize: str = "thread") -> None:
     cmd = ["g++", "-std=c++17", "-O1", "-g", "-Wall", "-I", MOCK, "-I", os.path.join(ROOT, "include"), "-I", src_dir]
     if tsan:
-        cmd.append("-fsanitize=thread")
+        cmd += [f"-fsanitize={sanitize}", "-fno-omit-frame-pointer"]
     for s in HOST_SOURCES:
         cmd += ["-x", "c++", os.path.join(src_dir, s)]
     cmd += [os.path.join(MOCK, "hipmock.cpp"), os.path.join(MOCK, "pipeline_harness.cpp"), "-o", out, "-lpthread"]
@@ -32,7 +32,8 @@ def _build(src_dir: str, out: str, tsan: bool) -> None:
 
 def _run(exe: str, scratch: str):
     os.makedirs(scratch, exist_ok=True)
-    env = dict(os.environ, TSAN_OPTIONS="halt_on_error=0 exitcode=66")
+    env = dict(os.environ, TSAN_OPTIONS="halt_on_error=0 exitcode=66", ASAN_OPTIONS="detect_leaks=1 exitcode=67",
+               UBSAN_OPTIONS="print_stacktrace=1 halt_on_error=1 exitcode=68")
     return subprocess.run([exe, scratch], capture_output=True, text=True, timeout=30, env=env)
 
 
@@ -55,6 +56,18 @@ def test_pipelines_move_every_element_once_and_are_race_free(tmp_path, tsan_ok):
     r = _run(exe, str(tmp_path / "scratch"))
     assert "PIPELINE OK" in r.stdout and r.returncode == 0, r.stdout[-3000:] + r.stderr[-3000:]
     assert "ThreadSanitizer" not in r.stderr, r.stderr[-3000:]
+
+
+def test_pipelines_under_address_and_undefined_behaviour_sanitizers(tmp_path, tsan_ok):
+    """The same harness under AddressSanitizer (with leak detection: every context that is created
+    is destroyed, failure paths included) and UndefinedBehaviorSanitizer."""
+    if not tsan_ok:
+        pytest.skip("sanitizer runtimes do not start in this environment")
+    exe = str(tmp_path / "harness_asan")
+    _build(CSRC, exe, True, "address,undefined")
+    r = _run(exe, str(tmp_path / "scratch"))
+    assert "PIPELINE OK" in r.stdout and r.returncode == 0, r.stdout[-3000:] + r.stderr[-3000:]
+    assert "ERROR: AddressSanitizer" not in r.stderr and "runtime error" not in r.stderr, r.stderr[-3000:]
 
 
 MUTANTS = [
