@@ -349,3 +349,75 @@ def test_tiered_one_layer_h8192_equals_resident(tmp_path):
                 os.unlink(p_)
         for _, ptr in bufs:
             gs.gs_pinned_free(ptr)
+
+
+@pytest.mark.timeout(600)
+def test_element_indices_beyond_2_to_31():
+    """Arrays longer than 2^31 elements: a window straddling index 2^31 is stepped as a range of
+    its own and as part of the whole [0,N) range (N/512 = 4.2 M workgroups; the norm folds more
+    tiles than its fixed workspace has partials), and checked against the oracle.  Everything
+    outside the window is zero, where the step leaves zeros and the norm adds nothing."""
+    N = (1 << 31) + 4096 + 5
+    lo, hi = (1 << 31) - 3001, N
+    k = 2
+    hp = gs.HParams(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, max_grad_norm=1.0, step=7)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(4242)
+    p = torch.zeros(N, dtype=torch.float32, device=DEV)
+    m = torch.zeros(N, dtype=torch.float32, device=DEV)
+    v = torch.zeros(N, dtype=torch.float32, device=DEV)
+    w = torch.zeros(N, dtype=torch.bfloat16, device=DEV)
+    grads = [torch.zeros(N, dtype=torch.bfloat16, device=DEV) for _ in range(k)]
+    wn = hi - lo
+    p[lo:hi] = torch.randn(wn, generator=gen, device=DEV) * 0.02
+    m[lo:hi] = torch.randn(wn, generator=gen, device=DEV) * 1e-3
+    v[lo:hi] = (torch.randn(wn, generator=gen, device=DEV) * 1e-3) ** 2
+    for g in grads:
+        g[lo:hi] = (torch.randn(wn, generator=gen, device=DEV) * 1e-2).to(torch.bfloat16)
+    h_p, h_m, h_v = (np_f32(t[lo:hi]) for t in (p, m, v))
+    h_g = [np_bf16(g[lo:hi]) for g in grads]
+    sq = torch.zeros(1, dtype=torch.float64, device=DEV)
+    ws = torch.empty(gs.gs_sqnorm_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    S_o = O.grad_sqnorm(h_g)
+    # the norm: window alone, whole range, and whole range staged (large and minimum workspace)
+    gs.gs_grad_sqnorm(grads, lo, hi, sq, ws)
+    torch.cuda.synchronize()
+    assert abs(float(sq.item()) - S_o) <= 1e-12 * S_o
+    gs.gs_grad_sqnorm(grads, 0, N, sq, ws)
+    torch.cuda.synchronize()
+    assert abs(float(sq.item()) - S_o) <= 1e-12 * S_o
+    acc = torch.full((N,), 3.0, dtype=torch.float32, device=DEV)
+    gs.gs_grad_accum_sqnorm(grads, 0, N, acc, sq, ws)
+    torch.cuda.synchronize()
+    assert abs(float(sq.item()) - S_o) <= 1e-12 * S_o
+    assert np.array_equal(np_f32(acc[lo:hi]), O.accumulate(h_g)) and float(acc[:lo].abs().max().item()) == 0.0
+    # accumulate as you go over the whole range
+    acc.fill_(5.0)
+    gs.gs_accum_add(acc, grads[0], True, 0, N)
+    gs.gs_accum_add(acc, grads[1], False, 0, N, sq, ws)
+    torch.cuda.synchronize()
+    assert abs(float(sq.item()) - S_o) <= 1e-12 * S_o
+    assert np.array_equal(np_f32(acc[lo:hi]), O.accumulate(h_g)) and float(acc[:lo].abs().max().item()) == 0.0
+    del acc
+    c = O.clip_coef(S_o, hp.max_grad_norm)
+    o_p, o_m, o_v, o_w = h_p.copy(), h_m.copy(), h_v.copy(), np.zeros(wn, np.uint16)
+    O.accum_adamw(o_p, o_m, o_v, o_w, h_g, ohp(hp), c)
+    # the step over the window as a range of its own (out of place, so the inputs survive)
+    po, mo, vo = (torch.zeros(N, dtype=torch.float32, device=DEV) for _ in range(3))
+    gs.gs_accum_adamw_oop(p, m, v, po, mo, vo, w, grads, lo, hi, hp, sq)
+    torch.cuda.synchronize()
+    for got, want, nm in ((po, o_p, "p"), (mo, o_m, "m"), (vo, o_v, "v")):
+        assert_f32_close(np_f32(got[lo:hi]), want, f"2^31 window {nm}")
+        assert float(got[:lo].abs().max().item()) == 0.0
+    assert_bf16_close(np_bf16(w[lo:hi]), o_w, "2^31 window w")
+    del po, mo, vo
+    # and as part of the whole range, in place
+    w.zero_()
+    gs.gs_accum_adamw(p, m, v, w, grads, 0, N, hp, sq)
+    torch.cuda.synchronize()
+    for got, want, nm in ((p, o_p, "p"), (m, o_m, "m"), (v, o_v, "v")):
+        assert_f32_close(np_f32(got[lo:hi]), want, f"whole range {nm}")
+        assert float(got[:lo].abs().max().item()) == 0.0, f"{nm}: zeros outside the window moved"
+    assert_bf16_close(np_bf16(w[lo:hi]), o_w, "whole range w")
+    assert int(torch.count_nonzero(w[:lo].view(torch.int16)).item()) == 0
+    print(f"[2^31] N={N} window=[{lo},{hi}) S={S_o:.6e} c={c:.5f}", flush=True)
