@@ -142,7 +142,8 @@ def test_resident_layer_sampled(name):
 def test_h8192_k16_staged_and_speculative_at_full_size():
     """The widened entry points at the headline size, in the shapes bench.py times (large
     workspace): staged two-pass == fused bit for bit; speculative pass == oracle with c = 1 on
-    sampled windows, inputs untouched, its norm equal to gs_grad_sqnorm's."""
+    sampled windows, inputs untouched, its norm equal to gs_grad_sqnorm's; k calls of gs_accum_add
+    leave the staged buffer bit for bit."""
     wl = I.WORKLOADS["gpt65b_layer_h8192_k16"]
     n, k = wl.n, wl.k
     print(f"[h8192 staged/spec] n={n} k={k}", flush=True)
@@ -184,7 +185,15 @@ def test_h8192_k16_staged_and_speculative_at_full_size():
         assert torch.equal(a, b), f"staged != fused in {nm}"
     lo, hi = wins[3]
     assert np.array_equal(np_f32(acc[lo:hi]), O.accumulate([np_bf16(g[lo:hi]) for g in grads]))
-    print(f"[h8192 staged/spec] S={S:.6e}; staged == fused bitwise; spec windows ok", flush=True)
+    # accumulate as you go, one call per micro-batch, the last with the norm: the same buffer bit for bit
+    acc2 = torch.full((n,), float("nan"), dtype=torch.float32, device=DEV)
+    for j in range(k):
+        last = j == k - 1
+        gs.gs_accum_add(acc2, grads[j], j == 0, 0, n, sq2 if last else None, big if last else None)
+    torch.cuda.synchronize()
+    assert torch.equal(acc, acc2), "k calls of gs_accum_add != k-way sum"
+    assert abs(float(sq2.item()) - S) <= 1e-12 * S
+    print(f"[h8192 staged/spec] S={S:.6e}; staged == fused bitwise; spec windows ok; as-you-go == staged", flush=True)
 
 
 @pytest.mark.timeout(600)
