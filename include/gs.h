@@ -281,7 +281,11 @@ gs_status gs_stream_ctx_destroy(gs_stream_ctx *ctx); /* waits for pending work, 
  * modes and for every chunk size.
  *   h_p, h_m, h_v   pinned host fp32 (device-accessible, as hipHostMalloc / gs_pinned_alloc
  *                   give it), n elements each, updated in place; 4-byte aligned for a
- *                   staged context, 16-byte aligned for an in-place one
+ *                   staged context, 16-byte aligned for an in-place one.  An in-place context
+ *                   asks the runtime about the first and last element of each array and
+ *                   returns GS_ERR_INVALID_ARG unless both are page-locked host memory mapped
+ *                   at the same address on the device (pageable memory under a kernel would
+ *                   fault the GPU)
  *   d_w_bf16        device bf16, n elements, written
  *   d_grads         host array of k device pointers (bf16, n elements each)
  *   d_sqnorm        as for gs_accum_adamw (device double or NULL)
@@ -311,8 +315,8 @@ gs_status gs_stream_ctx_sync(gs_stream_ctx *ctx);
 typedef struct gs_tier_ctx gs_tier_ctx;
 
 typedef struct {
-    float *h_p, *h_m, *h_v;            /* pinned host fp32, 16-byte aligned, elements [0,n_host); may be NULL
-                                          if n_host == 0 */
+    float *h_p, *h_m, *h_v;            /* pinned host fp32, 16-byte aligned, elements [0,n_host), checked like
+                                          gs_stream_layer_step's in-place arrays; may be NULL if n_host == 0 */
     int64_t n_host;                    /* 0 <= n_host <= n */
     int fd_p, fd_m, fd_v;              /* open descriptors (read+write); ignored if n_host == n */
     int64_t off_p, off_m, off_v;       /* byte offset of element n_host in each file; element i >= n_host

@@ -73,6 +73,25 @@ gs_status stream_validate(const gs_stream_ctx *c, const uint16_t *d_w_bf16, cons
     return GS_OK;
 }
 
+// In-place contexts hand host addresses to a kernel: anything but page-locked, device-mapped host
+// memory would fault the GPU, so the runtime is asked about the first and the last element of
+// every array (a range that runs past its allocation fails on the last).
+gs_status stream_check_mapped(const float *h, int64_t n)
+{
+    const float *probe[2] = {h, h + (n - 1)};
+    for (const float *q : probe) {
+        hipPointerAttribute_t a;
+        memset(&a, 0, sizeof a);
+        hipError_t e = hipPointerGetAttributes(&a, q);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            return GS_ERR_INVALID_ARG;
+        }
+        if (a.type != hipMemoryTypeHost || a.devicePointer != static_cast<const void *>(q)) return GS_ERR_INVALID_ARG;
+    }
+    return GS_OK;
+}
+
 gs_status stream_begin_layer(gs_stream_ctx *c, StepArgs &A, uint16_t *d_w_bf16, const uint16_t *const *d_grads, int k,
                              const gs_adamw_hparams *hp, const double *d_sqnorm, void *producer_stream)
 {
@@ -301,6 +320,11 @@ gs_status gs_stream_layer_step(gs_stream_ctx *c, float *h_p, float *h_m, float *
     gs_status st = stream_validate(c, d_w_bf16, d_grads, k, n, hp, d_sqnorm);
     if (st != GS_OK) return st;
     if (n == 0) return GS_OK;
+    if (!c->staged) {
+        if ((st = stream_check_mapped(h_p, n)) != GS_OK || (st = stream_check_mapped(h_m, n)) != GS_OK ||
+            (st = stream_check_mapped(h_v, n)) != GS_OK)
+            return st;
+    }
 
     StepArgs A;
     st = stream_begin_layer(c, A, d_w_bf16, d_grads, k, hp, d_sqnorm, producer_stream);

@@ -35,6 +35,10 @@ namespace gs {
 gs_status stream_validate(const gs_stream_ctx *c, const uint16_t *d_w_bf16, const uint16_t *const *d_grads, int k,
                           int64_t n, const gs_adamw_hparams *hp, const double *d_sqnorm);
 
+// GS_OK if h[0] and h[n-1] (n >= 1) are page-locked host memory that the device addresses at the same
+// pointer; GS_ERR_INVALID_ARG otherwise (pageable memory under a kernel would fault the GPU).
+gs_status stream_check_mapped(const float *h, int64_t n);
+
 // Makes the compute stream wait for what `producer_stream` holds now and fills the parts of A
 // that are the same for every launch of a layer.
 gs_status stream_begin_layer(gs_stream_ctx *c, StepArgs &A, uint16_t *d_w_bf16, const uint16_t *const *d_grads, int k,

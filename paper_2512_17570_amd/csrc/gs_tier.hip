@@ -335,6 +335,11 @@ gs_status gs_tier_layer_step(gs_tier_ctx *t, const gs_tier_layer *L, uint16_t *d
         if (t->err != GS_OK) return t->err;     // a failed context stays failed
     }
     if (n == 0) return GS_OK;
+    if (L->n_host > 0) {
+        if ((st = stream_check_mapped(L->h_p, L->n_host)) != GS_OK || (st = stream_check_mapped(L->h_m, L->n_host)) != GS_OK ||
+            (st = stream_check_mapped(L->h_v, L->n_host)) != GS_OK)
+            return st;
+    }
 
     gs_stream_ctx *c = t->sc;
     StepArgs A;

@@ -44,6 +44,17 @@ hipError_t hipEventCreateWithFlags(hipEvent_t *e, unsigned flags);
 hipError_t hipEventDestroy(hipEvent_t e);
 hipError_t hipEventRecord(hipEvent_t e, hipStream_t s);
 hipError_t hipEventSynchronize(hipEvent_t e);
+typedef enum { hipMemoryTypeUnregistered = 0, hipMemoryTypeHost = 1, hipMemoryTypeDevice = 2, hipMemoryTypeManaged = 3 } hipMemoryType;
+typedef struct {
+    hipMemoryType type;
+    int device;
+    void *devicePointer;
+    void *hostPointer;
+    int isManaged;
+    unsigned allocationFlags;
+} hipPointerAttribute_t;
+/* knows the blocks handed out by hipHostMalloc (host type) and hipMalloc (device type) */
+hipError_t hipPointerGetAttributes(hipPointerAttribute_t *attr, const void *ptr);
 typedef void (*hipHostFn_t)(void *userData);
 hipError_t hipLaunchHostFunc(hipStream_t s, hipHostFn_t fn, void *userData);
 hipError_t hipMemcpyAsync(void *dst, const void *src, size_t bytes, hipMemcpyKind kind, hipStream_t s);

@@ -7,6 +7,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <deque>
+#include <map>
 #include <mutex>
 #include <thread>
 
@@ -96,18 +97,54 @@ hipError_t hipGetDevice(int *dev) { *dev = 0; return hipSuccess; }
 hipError_t hipSetDevice(int) { return hipSuccess; }
 hipError_t hipDeviceGetAttribute(int *value, hipDeviceAttribute_t, int) { *value = 256; return hipSuccess; }
 
+// live allocations: base -> (bytes, type)
+static std::mutex g_alloc_mu;
+static std::map<uintptr_t, std::pair<size_t, hipMemoryType>> g_allocs;
+
+static void remember(void *p, size_t bytes, hipMemoryType t)
+{
+    std::lock_guard<std::mutex> g(g_alloc_mu);
+    g_allocs[reinterpret_cast<uintptr_t>(p)] = {bytes, t};
+}
+static void forget(void *p)
+{
+    std::lock_guard<std::mutex> g(g_alloc_mu);
+    g_allocs.erase(reinterpret_cast<uintptr_t>(p));
+}
+
 hipError_t hipMalloc(void **ptr, size_t bytes)
 {
     *ptr = aligned_alloc(256, (bytes + 255) / 256 * 256);
+    if (*ptr) remember(*ptr, bytes, hipMemoryTypeDevice);
     return *ptr ? hipSuccess : hipErrorOutOfMemory;
 }
-hipError_t hipFree(void *ptr) { free(ptr); return hipSuccess; }
+hipError_t hipFree(void *ptr) { forget(ptr); free(ptr); return hipSuccess; }
 hipError_t hipHostMalloc(void **ptr, size_t bytes, unsigned)
 {
     *ptr = aligned_alloc(4096, (bytes + 4095) / 4096 * 4096);
+    if (*ptr) remember(*ptr, bytes, hipMemoryTypeHost);
     return *ptr ? hipSuccess : hipErrorOutOfMemory;
 }
-hipError_t hipHostFree(void *ptr) { free(ptr); return hipSuccess; }
+hipError_t hipHostFree(void *ptr) { forget(ptr); free(ptr); return hipSuccess; }
+
+hipError_t hipPointerGetAttributes(hipPointerAttribute_t *attr, const void *ptr)
+{
+    std::lock_guard<std::mutex> g(g_alloc_mu);
+    const uintptr_t a = reinterpret_cast<uintptr_t>(ptr);
+    memset(attr, 0, sizeof *attr);
+    attr->device = -2;
+    auto it = g_allocs.upper_bound(a);
+    if (it != g_allocs.begin()) {
+        --it;
+        if (a < it->first + it->second.first) {
+            attr->type = it->second.second;
+            attr->device = 0;
+            attr->devicePointer = const_cast<void *>(ptr);
+            if (attr->type == hipMemoryTypeHost) attr->hostPointer = const_cast<void *>(ptr);
+        }
+    }
+    return hipSuccess;
+}
 
 hipError_t hipStreamCreateWithFlags(hipStream_t *s, unsigned) { *s = new hipmock_stream(); return hipSuccess; }
 hipError_t hipExtStreamCreateWithCUMask(hipStream_t *s, uint32_t, const uint32_t *) { *s = new hipmock_stream(); return hipSuccess; }

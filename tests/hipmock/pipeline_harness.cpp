@@ -133,9 +133,17 @@ static void test_stream(int64_t n, int num_cus, int64_t chunk = 0, int slots = 0
     }
     // a host array that is not 16-byte aligned is refused in place (staged: only copies touch it)
     const uint16_t *gt[1] = {A.g.data()};
-    if (chunk == 0)
+    if (chunk == 0) {
         CHECK(gs_stream_layer_step(ctx, hp_[0][0] + 1, hp_[0][1], hp_[0][2], A.w.data(), gt, 1, 16, &HP, nullptr, nullptr) ==
                   GS_ERR_INVALID_ARG, "misaligned host array accepted");
+        // ... and so is pageable memory, and a range that runs past the end of a pinned array
+        std::vector<float> pageable(64 + 4);
+        float *pg = reinterpret_cast<float *>((reinterpret_cast<uintptr_t>(pageable.data()) + 15) & ~(uintptr_t)15);
+        CHECK(gs_stream_layer_step(ctx, hp_[0][0], pg, hp_[0][2], A.w.data(), gt, 1, 16, &HP, nullptr, nullptr) ==
+                  GS_ERR_INVALID_ARG, "pageable host array accepted");
+        CHECK(gs_stream_layer_step(ctx, hp_[0][0], hp_[0][1], hp_[0][2], A.w.data(), gt, 1, A.n + 4096, &HP, nullptr,
+                                   nullptr) == GS_ERR_INVALID_ARG, "range past the end of the pinned arrays accepted");
+    }
     CHECK(gs_stream_ctx_destroy(ctx) == GS_OK, "destroy");
     CHECK(hipStreamDestroy(producer) == hipSuccess, "producer stream destroy");
     for (int l = 0; l < 2; ++l)

@@ -381,6 +381,17 @@ def test_streamed_rejects_misaligned_host_arrays_and_bad_cu_counts():
         for bad in (4, 8, 12):
             assert gs.gs_stream_layer_step(ctx, ptr + bad, ptr, ptr, case.w, case.grads, n, HP, None,
                                            check=False) == gs.GS_ERR_INVALID_ARG
+        # pageable memory and ranges past the end of a pinned array are refused before any launch
+        # (the runtime is asked what the first and the last element are)
+        pageable = np.zeros(n + 4, np.float32)
+        pg = (pageable.ctypes.data + 15) & ~15
+        assert gs.gs_stream_layer_step(ctx, ptr, pg, ptr, case.w, case.grads, n, HP, None,
+                                       check=False) == gs.GS_ERR_INVALID_ARG
+        assert gs.gs_stream_layer_step(ctx, ptr, ptr, ptr + 4096, case.w, case.grads, n, HP, None,
+                                       check=False) == gs.GS_ERR_INVALID_ARG
+        assert gs.gs_stream_layer_step(ctx, case.p.data_ptr(), ptr, ptr, case.w, case.grads, n, HP, None,
+                                       check=False) == gs.GS_ERR_INVALID_ARG      # device memory is not host memory
+        assert gs.gs_stream_ctx_sync(ctx) == gs.GS_OK
     finally:
         gs.gs_stream_ctx_destroy(ctx)
         del t
