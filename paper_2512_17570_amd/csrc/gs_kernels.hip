@@ -8,9 +8,11 @@
 //     4 consecutive elements, i.e. one 8-byte load per bf16 stream (512 B per wave) and one
 //     16-byte load/store per fp32 stream (1 KB per wave); lanes that own 8 elements would split
 //     each fp32 line across two instructions and fetch it twice;
-//   * workgroups are NOT persistent: one 1024-element tile per workgroup, dispatched in order,
-//     keeps the set of addresses in flight compact, which HBM rewards (a grid-stride loop costs
-//     30-40 % on stores on this part);
+//   * workgroups are NOT persistent: one 512-element tile per 128-lane workgroup, dispatched in
+//     order, keeps the set of addresses in flight compact, which HBM rewards (a grid-stride loop
+//     costs 30-40 % on stores on this part);
+//   * a wave keeps its memory queues shallow in the step kernels: the three state loads up
+//     front, then one gradient load in flight at a time, then the four stores one by one;
 //   * every stream is touched once, so loads and stores carry the non-temporal hint.
 // The norm pass is read-only and does best with short contiguous spans of tiles per workgroup.
 //

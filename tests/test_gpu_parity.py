@@ -1,6 +1,6 @@
 """GPU parity: the HIP path (through the C-ABI binding) against the CPU oracle, element by
-element, on the same seeded inputs.  Sizes span many launch tiles (a workgroup handles 1024
-elements; a norm workgroup a run of 8 such tiles) and ragged tails; full workload sizes are in
+element, on the same seeded inputs.  Sizes span many launch tiles (a step workgroup handles 512
+elements; a norm workgroup a run of 8 tiles of 1024) and ragged tails; full workload sizes are in
 test_gpu_fullsize.py."""
 import os
 
