@@ -50,6 +50,8 @@ def parse():
     ap.add_argument("--stream-cus", type=int, default=32,
                     help="compute units the host-resident step may use in the streamed and tiered workloads (0 = all)")
     ap.add_argument("--tier-dir", default=None, help="directory for the file tier's state files (default: the system temp dir)")
+    ap.add_argument("--tier-direct", action="store_true",
+                    help="open the file tier's state files with O_DIRECT (no page cache: the storage device's own rate)")
     return ap.parse_args()
 
 
@@ -460,7 +462,7 @@ def bench_tiered(args, wl):
                 t[:n_host].copy_(src[:n_host])
                 path = os.path.join(root, f"L{L}_{name}.bin")
                 src[n_host:].cpu().numpy().tofile(path)
-                lf.append(os.open(path, os.O_RDWR))
+                lf.append(os.open(path, os.O_RDWR | (os.O_DIRECT if args.tier_direct else 0)))
             fds.append(lf)
             del pd, md, vd
             grads_l.append(I.make_grads(nl, k, wl.grad_sigma, wl.seed + L, dev))
@@ -472,11 +474,12 @@ def bench_tiered(args, wl):
         torch.cuda.synchronize()
 
         # raw file ceilings: p/m/v of every layer read (then written) chunk by chunk by three threads
-        scratch = [np.empty(chunk, np.float32) for _ in range(3)]
+        import mmap
+        scratch = [mmap.mmap(-1, chunk * 4) for _ in range(3)]      # page-aligned, as O_DIRECT needs
 
         def sweep(write):
             def worker(a):
-                buf = memoryview(scratch[a]).cast("B")
+                buf = memoryview(scratch[a])
                 for L in range(layers):
                     for off in range(0, n_file * 4, chunk * 4):
                         ln = min(chunk * 4, n_file * 4 - off)
@@ -493,14 +496,15 @@ def bench_tiered(args, wl):
             return layers * n_file * 12 / (time.perf_counter() - t0) / 1e9
 
         print(f"[tiered] {layers} layers staged under {root}, {layers * n_file * 12 / 1e9:.1f} GB in files", file=sys.stderr, flush=True)
-        sweep(False)
+        if not args.tier_direct:
+            sweep(False)                          # warm the page cache
         read_gbs = sweep(False)
         print(f"[tiered] raw pread {read_gbs:.2f} GB/s", file=sys.stderr, flush=True)
         write_gbs = None
         if n_file:
             # write back what was just read, so the files keep their contents
             def rw_worker(a, out):
-                buf = memoryview(scratch[a]).cast("B")
+                buf = memoryview(scratch[a])
                 t_w = 0.0
                 for L in range(layers):
                     for off in range(0, n_file * 4, chunk * 4):
@@ -540,18 +544,46 @@ def bench_tiered(args, wl):
         gs.gs_tier_ctx_destroy(ctx)
         per = elapsed / args.steps
         n = layers * nl
+
+        # both directions at once on the same device (after the timed run: this overwrites the last
+        # layer's files): three threads read the first layer's files while three write the last layer's
+        duplex_gbs = None
+        if n_file:
+            wbuf = [mmap.mmap(-1, chunk * 4) for _ in range(3)]
+
+            def dworker(a, write):
+                buf = memoryview(wbuf[a] if write else scratch[a])
+                L = layers - 1 if write else 0
+                for off in range(0, n_file * 4, chunk * 4):
+                    ln = min(chunk * 4, n_file * 4 - off)
+                    if write:
+                        os.pwrite(fds[L][a], buf[:ln], off)
+                    else:
+                        os.preadv(fds[L][a], [buf[:ln]], off)
+            ths = [threading.Thread(target=dworker, args=(a, wr)) for a in range(3) for wr in (False, True)]
+            t0 = time.perf_counter()
+            for t in ths:
+                t.start()
+            for t in ths:
+                t.join()
+            duplex_gbs = n_file * 12 / (time.perf_counter() - t0) / 1e9
         rec = _base_record(wl, props, n / per, args.steps, args.warmup, per * 1e3,
                            {"layers": layers, "n_params": n, "chunk_elems": chunk, "slots": args.slots,
                             "host_share_x": x, "file_bytes": layers * n_file * 12, "host_pinned_bytes": layers * n_host * 12,
+                            "tier_dir": os.path.dirname(root), "o_direct": bool(args.tier_direct), "stream_cus": args.stream_cus,
                             "tier_dir_fs_free_bytes": free})
         file_dir = layers * n_file * 12 / per / 1e9
-        peak = min(read_gbs, write_gbs) if write_gbs else read_gbs
+        # the pipeline reads and writes at once, so the both-at-once probe is the ceiling it is held against
+        peak = duplex_gbs if duplex_gbs else (min(read_gbs, write_gbs) if write_gbs else read_gbs)
         rec["roofline"] = {"bound": "file", "kernel": "gs_tier_layer_step (file share: 12 B read + 12 B written per parameter)",
                            "achieved": file_dir, "peak": peak, "unit": "GB/s per direction", "frac": file_dir / peak,
                            "traffic": None,
-                           "peak_source": "measured here on the same files: chunked pread / pwrite by three threads "
-                                          "(page cache included, as in the timed run; no fsync)",
+                           "peak_source": "measured here on the same files: three threads reading one layer's files while three "
+                                          "write another's, chunk-sized requests "
+                                          + ("with O_DIRECT, as in the timed run" if args.tier_direct else
+                                             "(page cache included, as in the timed run; no fsync)"),
                            "pread_GBps": read_gbs, "pwrite_GBps": write_gbs,
+                           "duplex_probe_GBps_per_direction": duplex_gbs,
                            "pcie_GBps_per_direction": 12 * n / per / 1e9}
         rec["cpu_baseline"] = None
         print(json.dumps(rec))

@@ -341,10 +341,11 @@ gs_status gs_tier_ctx_create(gs_tier_ctx **out, int64_t chunk_elems, int slots, 
  * written; host arrays, files and device tensors must stay untouched until gs_tier_ctx_sync.
  * Results are bit-identical to gs_accum_adamw on a device copy of the same states, for every
  * n_host and chunk size.  Other arguments as for gs_stream_layer_step.  The files must hold the
- * whole range (a short file is GS_ERR_IO).  Descriptors opened with O_DIRECT are the caller's
- * business: offsets, n_host*4, chunk_elems*4 and (n-n_host)*4 then have to be multiples of the
- * device's block size (a chunk starting at element b sits (b mod 4) elements into its 4 KB-aligned
- * bounce array).  The descriptors are not closed.
+ * whole range (a short file is GS_ERR_IO).  Descriptors opened with O_DIRECT are recognised
+ * (fcntl): their transfers go through ordinary page-aligned memory of the bounce slots' size
+ * (allocated on first use) and one extra host copy, because the kernel cannot do direct I/O on
+ * page-locked memory that the GPU driver maps; offsets, n_host*4, chunk_elems*4 and (n-n_host)*4
+ * then have to be multiples of the device's block size.  The descriptors are not closed.
  * One thread at a time per context.  After any failure of the file tier the context stays
  * failed: this call and gs_tier_ctx_sync return that status, gs_tier_ctx_error its text.
  */

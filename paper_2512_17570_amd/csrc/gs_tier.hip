@@ -12,13 +12,18 @@
 //
 // Every element goes through the same kernel with the same absolute-index grouping as the
 // resident step, so the result is bit-identical for any n_host and chunk size.
+#ifndef _GNU_SOURCE
+#define _GNU_SOURCE   // O_DIRECT
+#endif
 #include <hip/hip_runtime.h>
 
 #include <cerrno>
 #include <condition_variable>
 #include <cstdio>
 #include <cstring>
+#include <cstdlib>
 #include <deque>
+#include <fcntl.h>
 #include <mutex>
 #include <new>
 #include <string>
@@ -37,6 +42,7 @@ struct WriteJob {
     int slot;
     int64_t len;            // elements
     int pad;                // the chunk starts this many elements into the slot's arrays
+    bool direct;            // the descriptors are O_DIRECT: go through the slot's ordinary-memory twin
     int fd[3];
     int64_t off[3];         // byte offsets
 };
@@ -85,14 +91,23 @@ bool write_all(int fd, const void *buf, size_t bytes, int64_t off, int *err)
 }
 
 // p, m and v of one chunk move concurrently (two helper threads + the caller); if a thread cannot
-// be started its transfer runs on the caller instead.  Returns the index of the first array that
-// failed (errno in *err), or -1.
-int move3(bool write, const int fd[3], float *const buf[3], size_t bytes, const int64_t off[3], int *err)
+// be started its transfer runs on the caller instead.  via != nullptr: the file side of each
+// transfer uses via[a] (ordinary page-aligned memory) and the data is copied between via[a] and
+// buf[a] -- descriptors opened with O_DIRECT cannot transfer to or from page-locked memory that
+// the GPU driver maps (EFAULT).  Returns the index of the first array that failed (errno in *err),
+// or -1.
+int move3(bool write, const int fd[3], float *const buf[3], float *const *via, size_t bytes, const int64_t off[3], int *err)
 {
     int e[3] = {0, 0, 0};
     bool ok[3] = {true, true, true};
     auto one = [&](int a) {
-        ok[a] = write ? write_all(fd[a], buf[a], bytes, off[a], &e[a]) : read_all(fd[a], buf[a], bytes, off[a], &e[a]);
+        if (write) {
+            if (via) memcpy(via[a], buf[a], bytes);
+            ok[a] = write_all(fd[a], via ? via[a] : buf[a], bytes, off[a], &e[a]);
+        } else {
+            ok[a] = read_all(fd[a], via ? via[a] : buf[a], bytes, off[a], &e[a]);
+            if (via && ok[a]) memcpy(buf[a], via[a], bytes);
+        }
     };
     std::thread th[2];
     bool started[2] = {false, false};
@@ -126,6 +141,8 @@ struct gs_tier_ctx {
     int64_t chunk = 0;
     int64_t bounce_elems = 0;               // per-array stride of a bounce slot (multiple of 1024 floats)
     float *bounce = nullptr;                // pinned host: slots * 3 * bounce_elems floats
+    float *plain = nullptr;                 // ordinary 4 KB-aligned memory of the same shape, made on first use
+                                            // by a layer whose descriptors are O_DIRECT
     std::vector<hipEvent_t> ev_done;        // per bounce slot: its chunk's kernel has finished
     int64_t next_slot = 0;                  // running file-chunk counter across calls -> slot rotation
     struct Note {                           // argument of the host function that follows a chunk's kernel
@@ -149,6 +166,10 @@ struct gs_tier_ctx {
     float *slot_ptr(int slot, int which) const
     {
         return bounce + ((size_t)slot * 3u + (size_t)which) * (size_t)bounce_elems;
+    }
+    float *plain_ptr(int slot, int which) const
+    {
+        return plain + ((size_t)slot * 3u + (size_t)which) * (size_t)bounce_elems;
     }
     void fail(gs_status st, const char *what, int err_no)
     {
@@ -200,8 +221,10 @@ static void writer_main(gs_tier_ctx *t)
         {
             float *const buf[3] = {t->slot_ptr(j.slot, 0) + j.pad, t->slot_ptr(j.slot, 1) + j.pad,
                                    t->slot_ptr(j.slot, 2) + j.pad};
+            float *const via[3] = {j.direct ? t->plain_ptr(j.slot, 0) : nullptr, j.direct ? t->plain_ptr(j.slot, 1) : nullptr,
+                                   j.direct ? t->plain_ptr(j.slot, 2) : nullptr};
             int werr = 0;
-            const int bad = move3(true, j.fd, buf, (size_t)j.len * sizeof(float), j.off, &werr);
+            const int bad = move3(true, j.fd, buf, j.direct ? via : nullptr, (size_t)j.len * sizeof(float), j.off, &werr);
             static const char *const names[3] = {"pwrite(p)", "pwrite(m)", "pwrite(v)"};
             if (bad >= 0) t->fail(GS_ERR_IO, names[bad], werr);
         }
@@ -229,6 +252,7 @@ static void tier_free(gs_tier_ctx *t)
     for (auto e : t->ev_done)
         if (e) (void)hipEventDestroy(e);
     if (t->bounce) (void)hipHostFree(t->bounce);
+    free(t->plain);
     delete t;
 }
 
@@ -341,6 +365,22 @@ gs_status gs_tier_layer_step(gs_tier_ctx *t, const gs_tier_layer *L, uint16_t *d
             return st;
     }
 
+    bool direct = false;
+    if (L->n_host < n) {
+        const int fds[3] = {L->fd_p, L->fd_m, L->fd_v};
+        for (int a = 0; a < 3; ++a) {
+            const int fl = fcntl(fds[a], F_GETFL);
+            if (fl < 0) return GS_ERR_INVALID_ARG;          // not an open descriptor
+            if (fl & O_DIRECT) direct = true;
+        }
+        if (direct && !t->plain) {
+            void *mem = nullptr;
+            const size_t bytes = (size_t)t->slots * 3u * (size_t)t->bounce_elems * sizeof(float);
+            if (posix_memalign(&mem, 4096, bytes) != 0) return GS_ERR_NOMEM;
+            t->plain = static_cast<float *>(mem);
+        }
+    }
+
     gs_stream_ctx *c = t->sc;
     StepArgs A;
     st = stream_begin_layer(c, A, d_w_bf16, d_grads, k, hp, d_sqnorm, producer_stream);
@@ -383,8 +423,10 @@ gs_status gs_tier_layer_step(gs_tier_ctx *t, const gs_tier_layer *L, uint16_t *d
         // accesses to absolute-index groups stay aligned
         const int64_t pad = b & 3;
         float *const buf[3] = {t->slot_ptr(slot, 0) + pad, t->slot_ptr(slot, 1) + pad, t->slot_ptr(slot, 2) + pad};
+        float *const via[3] = {direct ? t->plain_ptr(slot, 0) : nullptr, direct ? t->plain_ptr(slot, 1) : nullptr,
+                               direct ? t->plain_ptr(slot, 2) : nullptr};
         int rerr = 0;
-        const int bad = move3(false, fd, buf, (size_t)len * sizeof(float), off, &rerr);
+        const int bad = move3(false, fd, buf, direct ? via : nullptr, (size_t)len * sizeof(float), off, &rerr);
         if (bad >= 0) {
             static const char *const names[3] = {"pread(p)", "pread(m)", "pread(v)"};
             t->fail(GS_ERR_IO, names[bad], rerr);
@@ -407,6 +449,7 @@ gs_status gs_tier_layer_step(gs_tier_ctx *t, const gs_tier_layer *L, uint16_t *d
         j.slot = slot;
         j.len = len;
         j.pad = (int)pad;
+        j.direct = direct;
         for (int a = 0; a < 3; ++a) {
             j.fd[a] = fd[a];
             j.off[a] = off[a];

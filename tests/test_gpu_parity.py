@@ -500,6 +500,53 @@ def test_tiered_equals_resident_and_oracle(tmp_path, x, chunk, slots, cus):
             gs.gs_pinned_free(ptr)
 
 
+def test_tiered_with_direct_io_descriptors(tmp_path):
+    """O_DIRECT descriptors, the way an SSD tier is read: with n_host, the chunk and the file share
+    multiples of 1024 elements and block-aligned file offsets every transfer the tier makes is
+    aligned.  Skipped where the file system refuses O_DIRECT."""
+    n, n_host, chunk, header, k = 96 * 1024, 32 * 1024, 16 * 1024, 4096, 2
+    case = DeviceCase(n, k, seed=97)
+    init = [np_f32(t) for t in (case.p, case.m, case.v)]
+    paths, fds = [], []
+    for name, a in zip("pmv", init):
+        path = str(tmp_path / f"D_{name}.bin")
+        with open(path, "wb") as f:
+            f.write(b"\x5a" * header)
+            f.write(a[n_host:].tobytes())
+        paths.append(path)
+        try:
+            fds.append(os.open(path, os.O_RDWR | os.O_DIRECT))
+        except OSError:
+            for fd in fds:
+                os.close(fd)
+            pytest.skip("O_DIRECT not available on the test directory's file system")
+    bufs = [gs.pinned_f32(n_host) for _ in range(3)]
+    ctx = gs.gs_tier_ctx_create(chunk, 3, 16)
+    try:
+        for (tn, _), a in zip(bufs, init):
+            tn.copy_(torch.from_numpy(a[:n_host]))
+        case.gpu_sqnorm()
+        w = torch.zeros_like(case.w)
+        st = gs.gs_tier_layer_step(ctx, bufs[0][1], bufs[1][1], bufs[2][1], n_host, fds, (header,) * 3, w, case.grads, n,
+                                   HP, case.sq, check=False)
+        st2 = gs.gs_tier_ctx_sync(ctx, check=False)
+        assert st == gs.GS_OK and st2 == gs.GS_OK, f"status {st}/{st2}: {gs.gs_tier_ctx_error(ctx)}"
+        full = run_gpu_step(case, HP)
+        for (tn, _), path, r in zip(bufs, paths, full[:3]):
+            want = np_f32(r)
+            assert np.array_equal(tn.numpy(), want[:n_host])
+            raw = open(path, "rb").read()
+            assert len(raw) == header + 4 * (n - n_host) and raw[:header] == b"\x5a" * header
+            assert np.array_equal(np.frombuffer(raw, np.float32, offset=header), want[n_host:])
+        assert torch.equal(w, full[3])
+    finally:
+        gs.gs_tier_ctx_destroy(ctx, check=False)
+        for fd in fds:
+            os.close(fd)
+        for _, ptr in bufs:
+            gs.gs_pinned_free(ptr)
+
+
 def test_tiered_short_file_is_an_error_not_a_hang(tmp_path):
     n = 50_000
     case = DeviceCase(n, 1, seed=96)
