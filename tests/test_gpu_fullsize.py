@@ -233,7 +233,8 @@ def test_h12288_k8_split_equals_full_and_sampled():
 
 
 @pytest.mark.timeout(900)
-def test_streamed_8_layers_h8192_equals_resident():
+@pytest.mark.parametrize("mode", ["staged", "inplace"])
+def test_streamed_8_layers_h8192_equals_resident(mode):
     wl = I.WORKLOADS["gpt65b_8layers_streamed_k8"]
     nl, k, chunk = I.layer_numel(wl.h), wl.k, wl.extra["chunk_elems"]
     layers = wl.layers
@@ -245,7 +246,7 @@ def test_streamed_8_layers_h8192_equals_resident():
         layers -= 1
     assert layers >= 1, "could not pin host memory for one layer"
     n = layers * nl
-    print(f"[streamed] layers={layers} n={n} k={k} chunk={chunk} pinned={12 * n / 1e9:.1f} GB", flush=True)
+    print(f"[streamed {mode}] layers={layers} n={n} k={k} chunk={chunk} pinned={12 * n / 1e9:.1f} GB", flush=True)
     (hp_t, hp_p), (hm_t, hm_p), (hv_t, hv_p) = bufs
     try:
         hp = hp_of(wl)
@@ -266,7 +267,10 @@ def test_streamed_8_layers_h8192_equals_resident():
         # a window that straddles a chunk boundary inside layer 0 and the ragged tail chunk of the last layer
         wins = [(chunk - 3000, chunk + 3001), (nl - 4000, nl)]
         before0 = {lo: [hp_t[lo:hi].numpy().copy(), hm_t[lo:hi].numpy().copy(), hv_t[lo:hi].numpy().copy()] for lo, hi in wins}
-        ctx = gs.gs_stream_ctx_create_inplace(16)      # 16 of the CUs carry the full link rate
+        if mode == "staged":
+            ctx = gs.gs_stream_ctx_create(chunk, 3)        # 2^26-element chunks through three HBM slots, as bench.py times
+        else:
+            ctx = gs.gs_stream_ctx_create_inplace(16)      # 16 of the CUs carry the full link rate
         for L in range(layers):
             o = L * nl * 4
             gs.gs_stream_layer_step(ctx, hp_p + o, hm_p + o, hv_p + o, w_l[L], grads_l[L], nl, hp, sq)
