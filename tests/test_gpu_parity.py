@@ -808,6 +808,40 @@ def test_norm_and_step_replay_from_a_hip_graph():
     compare_states(st, ora, "graph reference")
 
 
+def test_accumulate_as_you_go_chain_replays_from_a_hip_graph():
+    """k calls of gs_accum_add (the last with the norm) and the step from the buffer, captured as one
+    graph: every replay, with eager work between replays, equals the eager fused result."""
+    n, k = 512 * 500 + 131, 4
+    case = DeviceCase(n, k, seed=171)
+    acc = torch.empty(n, dtype=torch.float32, device=DEV)
+    sq = torch.zeros(1, dtype=torch.float64, device=DEV)
+    p, m, v, w = case.clone_states()
+
+    def chain(states):
+        for j in range(k):
+            last = j == k - 1
+            gs.gs_accum_add(acc, case.grads[j], j == 0, 0, n, sq if last else None, case.ws if last else None)
+        gs.gs_adamw_from_acc(*states, acc, 0, n, HP, sq)
+
+    chain(case.clone_states())                                      # warm up outside capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        chain((p, m, v, w))
+    torch.cuda.synchronize()
+    eager = case.clone_states()
+    for it in range(3):
+        g.replay()
+        torch.cuda.synchronize()
+        acc.fill_(float("nan"))                                     # eager work between replays
+        case.gpu_sqnorm()
+        gs.gs_accum_adamw(*eager, case.grads, 0, n, HP, case.sq)
+        torch.cuda.synchronize()
+        assert abs(float(sq.item()) - float(case.sq.item())) <= 1e-12 * float(case.sq.item())
+        for a, b in zip((p, m, v, w), eager):
+            assert torch.equal(a, b), f"replay {it}"
+
+
 # ----------------------------------------------------------------------------- large-workspace shapes
 @pytest.mark.parametrize("k", [1, 2, 5, 16])
 def test_staged_and_speculative_fast_shapes_with_large_workspace(k):
