@@ -42,5 +42,25 @@ def build(verbose: bool = True, extra_flags=(), out: str | None = None) -> str:
     return out
 
 
+C_DEMO = os.path.join(PKG, "gs_c_demo")
+
+
+def build_c_demo(verbose: bool = True) -> str:
+    """The plain-C program that drives the library through its C ABI (tests/c_abi/step_demo.c, C99,
+    gcc): HIP runtime C API for memory, libgs.so for the step, the C oracle for the expected values.
+    A test program; the GPU tests run it."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-Wextra", "-Wno-unused-parameter", "-ffp-contract=off",
+           "-I", os.path.join(rocm, "include"), "-I", os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "c_abi", "step_demo.c"), os.path.join(ROOT, "oracle", "gs_oracle.c"),
+           "-L", PKG, "-lgs", "-L", os.path.join(rocm, "lib"), "-lamdhip64", "-lm",
+           "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", C_DEMO]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return C_DEMO
+
+
 if __name__ == "__main__":
     build()
+    build_c_demo()

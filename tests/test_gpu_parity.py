@@ -882,3 +882,15 @@ def test_staged_and_speculative_fast_shapes_with_large_workspace(k):
     assert abs(float(sq.item()) - So) <= 1e-12 * So
     for a, b in zip((po, mo, vo, w), (po2, mo2, vo2, w2)):
         assert torch.equal(a, b)
+
+
+# ----------------------------------------------------------------------------- the ABI from plain C
+def test_c_program_drives_the_abi_without_python_or_torch():
+    """tests/c_abi/step_demo.c (C99, built by the package's build step) allocates with the HIP
+    runtime's C API, calls the library and compares with the C oracle linked into it: norm over two
+    ranges and the resident step over a split range, bit for bit."""
+    import subprocess
+    from paper_2512_17570_amd import build as B
+    assert os.path.exists(B.C_DEMO), f"{B.C_DEMO} not built: run __graft_entry__.build() first"
+    r = subprocess.run([B.C_DEMO], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and "C ABI OK" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
