@@ -231,8 +231,10 @@ float gs_clip_coefficient(double sqnorm_total, float max_grad_norm);
 
 /*
  * Creates a HIP stream (default priority) whose kernels run on at most `num_cus` compute units
- * (the lowest-numbered ones; 1 <= num_cus <= CUs of the current device).  *stream receives a
- * hipStream_t to pass as the `stream` argument of the calls above.  Destroy with
+ * (the lowest-numbered ones; CUs/16 <= num_cus <= CUs of the current device, i.e. 16..256 on
+ * MI355X: the mask is spread over the chip's eight dies, and masks that leave a die with fewer
+ * than two CUs have not been validated, so they are refused with GS_ERR_INVALID_ARG).  *stream
+ * receives a hipStream_t to pass as the `stream` argument of the calls above.  Destroy with
  * gs_cu_stream_destroy after the work on it has finished.
  */
 gs_status gs_cu_stream_create(void **stream, int num_cus);
@@ -266,7 +268,7 @@ gs_status gs_stream_ctx_create(gs_stream_ctx **out, int64_t chunk_elems, int slo
  * themselves -- each wave loads its tile of p, m, v over the link, updates it and stores it
  * back.  Nothing is staged in device memory and no copy engine is used: 44-45 GB/s each way,
  * whatever else the process does with copies and streams.  num_cus = 0: an ordinary stream;
- * num_cus >= 1: a stream confined to that many compute units, as from gs_cu_stream_create (the
+ * num_cus > 0: a stream confined to that many compute units, as from gs_cu_stream_create (the
  * link, not the CU count, bounds this step: 16 CUs sustain the full rate and leave the rest of
  * the GPU to other work).  num_cus < 0 or above the device's count is GS_ERR_INVALID_ARG.
  */

@@ -271,6 +271,8 @@ gs_status gs_cu_stream_create(void **stream, int num_cus)
     e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return hip_fail(e, "hipDeviceGetAttribute");
     if (num_cus > cus) return GS_ERR_INVALID_ARG;
+    // the driver spreads the mask over the dies; fewer than two CUs per die is not a validated shape
+    if (num_cus < (cus + 15) / 16) return GS_ERR_INVALID_ARG;
     // one bit per CU, lowest-numbered CUs enabled (the driver rejects scattered masks)
     const uint32_t words = (uint32_t)((cus + 31) / 32);
     uint32_t mask[64] = {0};

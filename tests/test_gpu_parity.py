@@ -702,6 +702,8 @@ def test_cu_budget_stream_gives_same_result():
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     st_, raw = gs.gs_cu_stream_create(cus + 1, check=False)
     assert st_ == gs.GS_ERR_INVALID_ARG and not raw
+    st_, raw = gs.gs_cu_stream_create(max(1, cus // 16 - 1), check=False)      # fewer than two CUs per die: refused
+    assert st_ == gs.GS_ERR_INVALID_ARG and not raw
     raw = gs.gs_cu_stream_create(max(1, cus // 2))
     try:
         st = case.clone_states()
