@@ -96,6 +96,17 @@ double gs_oracle_accum_add(float *acc, const uint16_t *grad, int first, int64_t 
     return S;
 }
 
+/* a2 on a finished accumulation buffer: sum of acc[i]^2 over [begin,end), squares and sum in double. */
+double gs_oracle_acc_sqnorm(const float *acc, int64_t begin, int64_t end)
+{
+    double S = 0.0;
+    for (int64_t i = begin; i < end; ++i) {
+        double x = (double)acc[i];
+        S += x * x;
+    }
+    return S;
+}
+
 /* ---- a2: squared L2 norm of the accumulated gradient over [begin,end) ------------------ */
 /* (Sec. 2.1: clipping needs the global L2 norm.)  Each square is exact in double. */
 double gs_oracle_grad_sqnorm(const uint16_t *const *grads, int k, int64_t begin, int64_t end)

@@ -70,6 +70,8 @@ def lib():
         L.gs_oracle_accumulate.restype = None
         L.gs_oracle_accum_add.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64]
         L.gs_oracle_accum_add.restype = ctypes.c_double
+        L.gs_oracle_acc_sqnorm.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64]
+        L.gs_oracle_acc_sqnorm.restype = ctypes.c_double
         L.gs_oracle_clip_coef.argtypes = [ctypes.c_double, ctypes.c_float]
         L.gs_oracle_clip_coef.restype = ctypes.c_float
         L.gs_oracle_accum_adamw.argtypes = [ctypes.c_void_p] * 4 + [
@@ -131,6 +133,14 @@ def accum_add(acc: np.ndarray, grad: np.ndarray, first: bool, begin: int = 0, en
     end = len(grad) if end is None else end
     assert 0 <= begin <= end <= len(grad) and len(acc) >= end
     return float(lib().gs_oracle_accum_add(acc.ctypes.data, grad.ctypes.data, int(bool(first)), begin, end))
+
+
+def acc_sqnorm(acc: np.ndarray, begin: int = 0, end: int | None = None) -> float:
+    """Squared L2 norm of a finished fp32 accumulation buffer over [begin,end)."""
+    _check(acc, np.float32, "acc")
+    end = len(acc) if end is None else end
+    assert 0 <= begin <= end <= len(acc)
+    return float(lib().gs_oracle_acc_sqnorm(acc.ctypes.data, begin, end))
 
 
 def clip_coef(sqnorm_total: float, max_norm: float) -> float:

@@ -36,6 +36,9 @@ MUTANTS = [
     ("add_forgets_buffer", "float base = first ? 0.0f : acc[i];", "float base = 0.0f;"),
     ("add_first_keeps_old", "float base = first ? 0.0f : acc[i];", "float base = acc[i];"),
     ("add_norm_before_update", "double ad = (double)a;", "double ad = (double)base;"),
+    ("acc_norm_sums_plain_values", "S += x * x;", "S += x;"),
+    ("acc_norm_range_start_ignored", "for (int64_t i = begin; i < end; ++i) {\n        double x = (double)acc[i];",
+     "for (int64_t i = 0; i < end; ++i) {\n        double x = (double)acc[i];"),
     ("bf16_decode_shift", "uint32_t u = (uint32_t)h << 16;", "uint32_t u = (uint32_t)h << 15;"),
 ]
 

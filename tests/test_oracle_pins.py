@@ -379,6 +379,21 @@ def test_accum_add_one_micro_batch_at_a_time():
     assert O.accum_add(z, np.zeros(4, np.uint16), first=True, begin=2, end=2) == 0.0
 
 
+def test_acc_sqnorm_of_a_finished_buffer():
+    """Norm of an fp32 buffer: numpy's fp64 dot (library routine), the closed form of a constant
+    buffer, additivity over ranges, and agreement with the norm computed from the k bf16 buffers."""
+    n, k = 20_000, 3
+    _, _, _, g = rand_case(n, k, seed=72, sigma=1e-2)
+    acc = O.accumulate(g)
+    a64 = acc.astype(np.float64)
+    assert math.isclose(O.acc_sqnorm(acc), float(np.dot(a64, a64)), rel_tol=1e-13)
+    assert math.isclose(O.acc_sqnorm(acc), O.grad_sqnorm(g), rel_tol=1e-13)
+    assert math.isclose(O.acc_sqnorm(acc, 0, 777) + O.acc_sqnorm(acc, 777, n), O.acc_sqnorm(acc), rel_tol=1e-13)
+    assert O.acc_sqnorm(acc, 5, 5) == 0.0
+    assert O.acc_sqnorm(np.full(4096, np.float32(-0.25))) == 4096 * 0.0625
+    assert math.isclose(O.acc_sqnorm(acc, 123, 124), float(a64[123] ** 2), rel_tol=1e-15)
+
+
 def test_sum_not_mean():
     n = 256
     one = np.full(n, 0x3C00, dtype=np.uint16)       # 2^-7
