@@ -23,9 +23,11 @@ _LIB = os.path.join(_HERE, "libgs_oracle.so")
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (no FMA contraction, no fast-math)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = f"{_LIB}.{os.getpid()}.tmp"       # written aside, then renamed: parallel test workers may build at once
         cmd = ["gcc", "-O2", "-ffp-contract=off", "-fno-fast-math", "-std=c11", "-Wall", "-Wextra",
-               "-shared", "-fPIC", _SRC, "-o", _LIB, "-lm"]
+               "-shared", "-fPIC", _SRC, "-o", tmp, "-lm"]
         subprocess.run(cmd, check=True)
+        os.replace(tmp, _LIB)
     return _LIB
 
 
