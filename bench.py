@@ -712,6 +712,7 @@ def main():
     add_first_ms = timed(lambda: gs.gs_accum_add(acc, grads[0], True, 0, n), args.steps)
     add_ms = timed(lambda: gs.gs_accum_add(acc, grads[1 % k], False, 0, n), args.steps)
     add_norm_ms = timed(lambda: gs.gs_accum_add(acc, grads[k - 1], False, 0, n, sq, ws_big), args.steps)
+    acc_norm_ms = timed(lambda: gs.gs_acc_sqnorm(acc, 0, n, sq, ws), args.steps)
     del acc
 
     # speculative single pass (c = 1 step + norm in one read of the gradients), out of place with
@@ -776,6 +777,7 @@ def main():
             "gs_accum_add": {"avg_ms": add_ms, "bytes_per_param": 10, "GBps": n * 10 / (add_ms * 1e-3) / 1e9},
             "gs_accum_add_with_norm": {"avg_ms": add_norm_ms, "bytes_per_param": 10,
                                        "GBps": n * 10 / (add_norm_ms * 1e-3) / 1e9},
+            "gs_acc_sqnorm": {"avg_ms": acc_norm_ms, "bytes_per_param": 4, "GBps": n * 4 / (acc_norm_ms * 1e-3) / 1e9},
             "note": "one call per micro-batch into the resident fp32 buffer; the step then runs gs_adamw_from_acc"},
         "speculative_single_pass": {"avg_ms": spec_ms, "bytes_per_param": 2 * k + 26,
                                     "GBps": step_bytes / (spec_ms * 1e-3) / 1e9, "params_per_s": n / (spec_ms * 1e-3),

@@ -176,6 +176,16 @@ gs_status gs_accum_add(float *acc_f32, const uint16_t *grad_bf16, int first, int
                        void *d_workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Squared L2 norm of a finished accumulation buffer: S = sum over i in [begin,end) of acc_f32[i]^2,
+ * squares and reduction in fp64 -- for a buffer whose norm was not taken by the call that
+ * finished it (e.g. a shard that came back from a reduction across devices).  Arguments as for
+ * gs_grad_sqnorm with the fp32 buffer (device, >= end elements, 16-byte aligned, read only) in
+ * place of the k gradient buffers.
+ */
+gs_status gs_acc_sqnorm(const float *acc_f32, int64_t begin, int64_t end, double *d_sqnorm, int accumulate,
+                        void *d_workspace, size_t workspace_bytes, void *stream);
+
+/*
  * gs_accum_adamw with the gradient sum taken from acc_f32 (as written by gs_grad_accum_sqnorm)
  * instead of k bf16 buffers.  p, m, v, w come out bit-identical to gs_accum_adamw on the
  * same gradients, and the same partition independence holds.

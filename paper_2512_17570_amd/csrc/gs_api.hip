@@ -144,6 +144,21 @@ gs_status gs_accum_add(float *acc_f32, const uint16_t *grad_bf16, int first, int
     return GS_OK;
 }
 
+gs_status gs_acc_sqnorm(const float *acc_f32, int64_t begin, int64_t end, double *d_sqnorm, int accumulate,
+                        void *d_workspace, size_t workspace_bytes, void *stream)
+{
+    if (!acc_f32 || !aligned16(acc_f32)) return GS_ERR_INVALID_ARG;
+    if (begin < 0 || end < begin) return GS_ERR_INVALID_ARG;
+    if (!d_sqnorm || (reinterpret_cast<uintptr_t>(d_sqnorm) & 7u)) return GS_ERR_INVALID_ARG;
+    if (!d_workspace || workspace_bytes < gs_sqnorm_workspace_bytes()) return GS_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(d_workspace) & 7u) return GS_ERR_WORKSPACE;
+    if (begin == end && accumulate) return GS_OK;
+    hipError_t e = launch_acc_sqnorm(acc_f32, begin, end, static_cast<double *>(d_workspace), workspace_bytes, d_sqnorm,
+                                     accumulate, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "gs_acc_sqnorm launch");
+    return GS_OK;
+}
+
 // host mirror of the kernels' clip coefficient
 static float clip_coefficient_host(double sqnorm_total, float max_norm)
 {

@@ -66,6 +66,10 @@ hipError_t launch_grad_sqnorm(const SqnormArgs &A, size_t workspace_bytes, doubl
 hipError_t launch_accum_add(const AccumAddArgs &A, int first, size_t workspace_bytes, double *d_out, int accumulate,
                             hipStream_t stream);
 
+// squared norm of a finished fp32 buffer over [begin,end)
+hipError_t launch_acc_sqnorm(const float *acc, int64_t begin, int64_t end, double *partials, size_t workspace_bytes,
+                             double *d_out, int accumulate, hipStream_t stream);
+
 // host side (gs_api.hip)
 gs_status validate_hparams(const gs_adamw_hparams *hp);
 gs_status validate_grads(const uint16_t *const *grads, int k);

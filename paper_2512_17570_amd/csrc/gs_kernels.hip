@@ -393,6 +393,36 @@ __global__ __launch_bounds__(BLOCK) void k_accum_add(AccumAddArgs A, int span)
     }
 }
 
+// Norm of a finished fp32 accumulation buffer (the buffer gs_accum_add builds, or one that came
+// back from a reduction across devices): 4 bytes read per element, the read-only shape of the
+// gradient norm -- a short contiguous run of tiles per workgroup.
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void k_acc_sqnorm(const float *acc, int64_t begin, int64_t end, double *partials, int span)
+{
+    constexpr int TILE = BLOCK * 4;
+    __shared__ double lds[BLOCK / 64];
+    const int64_t first = (begin / TILE + (int64_t)blockIdx.x * span) * TILE + (int64_t)threadIdx.x * 4;
+    double acc0 = 0.0, acc1 = 0.0;
+    for (int it = 0; it < span; ++it) {
+        const int64_t lo = first + (int64_t)it * TILE;
+        if (lo >= end) break;
+        if (lo + 4 <= begin) continue;
+        if (lo >= begin && lo + 4 <= end) {
+            const f32x4 a = ld_stream(reinterpret_cast<const f32x4 *>(acc + lo));
+            acc0 = fma((double)a.x, (double)a.x, acc0);
+            acc1 = fma((double)a.y, (double)a.y, acc1);
+            acc0 = fma((double)a.z, (double)a.z, acc0);
+            acc1 = fma((double)a.w, (double)a.w, acc1);
+        } else {
+            const int64_t i0 = lo > begin ? lo : begin;
+            const int64_t i1 = lo + 4 < end ? lo + 4 : end;
+            for (int64_t i = i0; i < i1; ++i) acc0 = fma((double)acc[i], (double)acc[i], acc0);
+        }
+    }
+    double t = block_sum<BLOCK>(acc0 + acc1, lds);
+    if (threadIdx.x == 0) partials[blockIdx.x] = t;
+}
+
 // Folding the workgroup partials, in a fixed order (deterministic).  Up to 262144 partials are too
 // many for one workgroup to read quickly, so large counts go through GS_FINAL_SLICES workgroups
 // that each fold a contiguous slice into the tail of the workspace, then one workgroup folds those.
@@ -539,6 +569,22 @@ hipError_t launch_grad_sqnorm(const SqnormArgs &A, size_t workspace_bytes, doubl
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_fold(A.partials, cap, grid, d_out, accumulate, stream);
+}
+
+hipError_t launch_acc_sqnorm(const float *acc, int64_t begin, int64_t end, double *partials, size_t workspace_bytes,
+                             double *d_out, int accumulate, hipStream_t stream)
+{
+    const int64_t cap = partial_capacity(workspace_bytes);
+    int64_t tiles = tiles_of(begin, end, GS_TILE);
+    if (tiles < 1) tiles = 1;
+    int64_t span = GS_NORM_SPAN;
+    if ((tiles + span - 1) / span > cap) span = (tiles + cap - 1) / cap;
+    if (span > 0x7fffffff) return hipErrorInvalidValue;
+    const int grid = (int)((tiles + span - 1) / span);
+    k_acc_sqnorm<GS_BLOCK><<<grid, GS_BLOCK, 0, stream>>>(acc, begin, end, partials, (int)span);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_fold(partials, cap, grid, d_out, accumulate, stream);
 }
 
 hipError_t launch_accum_add(const AccumAddArgs &A, int first, size_t workspace_bytes, double *d_out, int accumulate,

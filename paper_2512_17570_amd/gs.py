@@ -76,6 +76,8 @@ _lib.gs_grad_accum_sqnorm.argtypes = [_pp, ctypes.c_int, _i64, _i64, _vp, _vp, c
 _lib.gs_grad_accum_sqnorm.restype = ctypes.c_int
 _lib.gs_accum_add.argtypes = [_vp, _vp, ctypes.c_int, _i64, _i64, _vp, ctypes.c_int, _vp, ctypes.c_size_t, _vp]
 _lib.gs_accum_add.restype = ctypes.c_int
+_lib.gs_acc_sqnorm.argtypes = [_vp, _i64, _i64, _vp, ctypes.c_int, _vp, ctypes.c_size_t, _vp]
+_lib.gs_acc_sqnorm.restype = ctypes.c_int
 _lib.gs_adamw_from_acc.argtypes = [_vp, _vp, _vp, _vp, _vp, _i64, _i64, ctypes.POINTER(gs_adamw_hparams), _vp, _vp]
 _lib.gs_adamw_from_acc.restype = ctypes.c_int
 _lib.gs_accum_adamw_oop.argtypes = [_vp] * 7 + [_pp, ctypes.c_int, _i64, _i64, ctypes.POINTER(gs_adamw_hparams), _vp, _vp]
@@ -229,6 +231,16 @@ def gs_accum_add(acc_f32, grad_bf16, first: bool, begin: int, end: int, d_sqnorm
     st = _lib.gs_accum_add(_addr(acc_f32), _addr(grad_bf16), int(bool(first)), begin, end, _addr(d_sqnorm),
                            int(bool(accumulate)), _addr(d_workspace), workspace_bytes, _stream(stream))
     return _check(st, "gs_accum_add", check)
+
+
+def gs_acc_sqnorm(acc_f32, begin: int, end: int, d_sqnorm, d_workspace, workspace_bytes: int | None = None,
+                  accumulate: bool = False, stream=None, check: bool = True) -> int:
+    _need(acc_f32, end, 4, "acc_f32")
+    if workspace_bytes is None:
+        workspace_bytes = d_workspace.numel() * d_workspace.element_size() if hasattr(d_workspace, "numel") else 0
+    st = _lib.gs_acc_sqnorm(_addr(acc_f32), begin, end, _addr(d_sqnorm), int(bool(accumulate)), _addr(d_workspace),
+                            workspace_bytes, _stream(stream))
+    return _check(st, "gs_acc_sqnorm", check)
 
 
 def gs_adamw_from_acc(p, m, v, w_bf16, acc_f32, begin: int, end: int, hp, d_sqnorm=None, stream=None,

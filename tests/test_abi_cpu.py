@@ -28,7 +28,7 @@ def test_header_symbols_all_exported():
             "gs_stream_ctx_create_inplace", "gs_stream_ctx_create", "gs_stream_ctx_destroy", "gs_stream_ctx_sync", "gs_pinned_alloc",
             "gs_pinned_free", "gs_strerror", "gs_last_hip_error", "gs_grad_accum_sqnorm", "gs_adamw_from_acc",
             "gs_cu_stream_create", "gs_cu_stream_destroy", "gs_accum_adamw_oop", "gs_accum_adamw_spec",
-            "gs_clip_coefficient", "gs_sqnorm_workspace_bytes_for", "gs_accum_add",
+            "gs_clip_coefficient", "gs_sqnorm_workspace_bytes_for", "gs_accum_add", "gs_acc_sqnorm",
             "gs_tier_ctx_create", "gs_tier_ctx_destroy", "gs_tier_ctx_sync", "gs_tier_ctx_error", "gs_tier_layer_step"} <= set(names)
     lib = ctypes.CDLL(gs.LIB_PATH)
     for n in names:
@@ -151,6 +151,17 @@ def test_accum_add_rejects_without_gpu():
     # an empty range launches nothing: with no norm, or with a norm that is only added to
     assert gs.gs_accum_add(**{**ok, "begin": 5, "end": 5, "d_sqnorm": None, "d_workspace": None}) == gs.GS_OK
     assert gs.gs_accum_add(**{**ok, "begin": 5, "end": 5, "accumulate": True}) == gs.GS_OK
+
+
+def test_acc_sqnorm_rejects_without_gpu():
+    ws = gs.gs_sqnorm_workspace_bytes()
+    ok = dict(acc_f32=FAKE, begin=0, end=64, d_sqnorm=FAKE, d_workspace=FAKE, workspace_bytes=ws, stream=0, check=False)
+    for kw, want in ((dict(acc_f32=None), gs.GS_ERR_INVALID_ARG), (dict(acc_f32=FAKE + 4), gs.GS_ERR_INVALID_ARG),
+                     (dict(begin=9, end=3), gs.GS_ERR_INVALID_ARG), (dict(begin=-1), gs.GS_ERR_INVALID_ARG),
+                     (dict(d_sqnorm=None), gs.GS_ERR_INVALID_ARG), (dict(d_sqnorm=FAKE + 4), gs.GS_ERR_INVALID_ARG),
+                     (dict(workspace_bytes=8), gs.GS_ERR_WORKSPACE), (dict(d_workspace=None), gs.GS_ERR_WORKSPACE)):
+        assert gs.gs_acc_sqnorm(**{**ok, **kw}) == want
+    assert gs.gs_acc_sqnorm(**{**ok, "begin": 5, "end": 5, "accumulate": True}) == gs.GS_OK
 
 
 def test_staged_variant_rejects_without_gpu():

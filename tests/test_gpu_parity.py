@@ -671,6 +671,29 @@ def test_accum_add_ranges_norm_accumulate_and_large_workspace():
         assert float(sq.item()) == 0.0 and np.array_equal(np_f32(acc), h_acc)
 
 
+def test_acc_sqnorm_of_a_finished_buffer():
+    """Norm of an fp32 buffer over full and ragged ranges, accumulated over pieces, against the oracle
+    and against the norm taken from the k gradient buffers."""
+    n, k = 1024 * 77 + 19, 3
+    case = DeviceCase(n, k, seed=160)
+    acc = torch.empty(n, dtype=torch.float32, device=DEV)
+    sq = torch.zeros(1, dtype=torch.float64, device=DEV)
+    gs.gs_grad_accum_sqnorm(case.grads, 0, n, acc, sq, case.ws)
+    torch.cuda.synchronize()
+    S_k = float(sq.item())
+    h_acc = np_f32(acc)
+    for b, e in ((0, n), (5, n - 3), (1023, 1029), (4096, 4096)):
+        gs.gs_acc_sqnorm(acc, b, e, sq, case.ws)
+        torch.cuda.synchronize()
+        want = O.acc_sqnorm(h_acc, b, e)
+        assert abs(float(sq.item()) - want) <= 1e-12 * max(want, 1e-300), (b, e)
+    gs.gs_acc_sqnorm(acc, 0, 5000, sq, case.ws)
+    gs.gs_acc_sqnorm(acc, 5000, n, sq, case.ws, accumulate=True)
+    torch.cuda.synchronize()
+    assert abs(float(sq.item()) - S_k) <= 1e-12 * S_k
+    assert abs(float(sq.item()) - O.grad_sqnorm(case.h_g)) <= 1e-12 * S_k
+
+
 def test_accum_add_special_values():
     """Inf, NaN, -0 and cancelling gradients go through the add like through the oracle."""
     pats = np.array([0x7F80, 0xFF80, 0x7FC0, 0x8000, 0x0000, 0x3F80, 0xBF80, 0x0001, 0x7F7F, 0xFF7F], np.uint16)
