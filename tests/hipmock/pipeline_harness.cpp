@@ -41,6 +41,7 @@ hipError_t launch_accum_adamw(const StepArgs &A, hipStream_t stream)
 hipError_t launch_accum_adamw_spec(const StepArgs &, double *, size_t, double *, int, hipStream_t) { return hipErrorUnknown; }
 hipError_t launch_grad_sqnorm(const SqnormArgs &, size_t, double *, int, hipStream_t) { return hipErrorUnknown; }
 hipError_t launch_accum_add(const AccumAddArgs &, int, size_t, double *, int, hipStream_t) { return hipErrorUnknown; }
+hipError_t launch_acc_sqnorm(const float *, int64_t, int64_t, double *, size_t, double *, int, hipStream_t) { return hipErrorUnknown; }
 
 }  // namespace gs
 
