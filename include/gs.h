@@ -280,7 +280,8 @@ gs_status gs_stream_ctx_create(gs_stream_ctx **out, int64_t chunk_elems, int slo
  * whatever else the process does with copies and streams.  num_cus = 0: an ordinary stream;
  * num_cus > 0: a stream confined to that many compute units, as from gs_cu_stream_create (the
  * link, not the CU count, bounds this step: 16 CUs sustain the full rate and leave the rest of
- * the GPU to other work).  num_cus < 0 or above the device's count is GS_ERR_INVALID_ARG.
+ * the GPU to other work).  num_cus < 0, or outside gs_cu_stream_create's range when positive, is
+ * GS_ERR_INVALID_ARG.
  */
 gs_status gs_stream_ctx_create_inplace(gs_stream_ctx **out, int num_cus);
 gs_status gs_stream_ctx_destroy(gs_stream_ctx *ctx); /* waits for pending work, frees everything */
