@@ -313,6 +313,18 @@ gs_status gs_stream_layer_step(gs_stream_ctx *ctx, float *h_p, float *h_m, float
                                const gs_adamw_hparams *hp, const double *d_sqnorm,
                                void *producer_stream);
 
+/*
+ * The same over [begin,end) only (0 <= begin <= end; the arrays hold at least `end` elements and
+ * are indexed from the layer's element 0, as everywhere): the split step of Sec. 4.4 on
+ * host-resident states -- the immediate part now, the deferred part later, on the same or another
+ * context; [0,s) followed by [s,n) leaves bit for bit what gs_stream_layer_step leaves.
+ */
+gs_status gs_stream_layer_step_range(gs_stream_ctx *ctx, float *h_p, float *h_m, float *h_v,
+                                     uint16_t *d_w_bf16, const uint16_t *const *d_grads, int k,
+                                     int64_t begin, int64_t end,
+                                     const gs_adamw_hparams *hp, const double *d_sqnorm,
+                                     void *producer_stream);
+
 /* Blocks until everything enqueued on the context has finished (the host arrays hold the new states). */
 gs_status gs_stream_ctx_sync(gs_stream_ctx *ctx);
 
@@ -365,6 +377,13 @@ gs_status gs_tier_ctx_create(gs_tier_ctx **out, int64_t chunk_elems, int slots, 
 gs_status gs_tier_layer_step(gs_tier_ctx *ctx, const gs_tier_layer *L, uint16_t *d_w_bf16,
                              const uint16_t *const *d_grads, int k, int64_t n,
                              const gs_adamw_hparams *hp, const double *d_sqnorm, void *producer_stream);
+
+/* The same over [begin,end) of the layer only (0 <= begin <= end <= n): whatever part of the range
+ * lies in the host share is stepped in place, whatever part lies in the file share goes through
+ * the bounce slots.  Split at any point, the two calls leave bit for bit what the whole call leaves. */
+gs_status gs_tier_layer_step_range(gs_tier_ctx *ctx, const gs_tier_layer *L, uint16_t *d_w_bf16,
+                                   const uint16_t *const *d_grads, int k, int64_t n, int64_t begin, int64_t end,
+                                   const gs_adamw_hparams *hp, const double *d_sqnorm, void *producer_stream);
 
 /* Blocks until every enqueued chunk has been computed and written back to its host array or file
  * (the page cache counts as written; fsync is the caller's call). */

@@ -307,35 +307,47 @@ gs_status gs_stream_ctx_destroy(gs_stream_ctx *c)
     return st;
 }
 
-gs_status gs_stream_layer_step(gs_stream_ctx *c, float *h_p, float *h_m, float *h_v,
-                               uint16_t *d_w_bf16, const uint16_t *const *d_grads, int k, int64_t n,
-                               const gs_adamw_hparams *hp, const double *d_sqnorm,
-                               void *producer_stream)
+gs_status gs_stream_layer_step_range(gs_stream_ctx *c, float *h_p, float *h_m, float *h_v,
+                                     uint16_t *d_w_bf16, const uint16_t *const *d_grads, int k,
+                                     int64_t begin, int64_t end,
+                                     const gs_adamw_hparams *hp, const double *d_sqnorm,
+                                     void *producer_stream)
 {
     if (!c || !h_p || !h_m || !h_v) return GS_ERR_INVALID_ARG;
     // in place the kernel's 16-byte accesses hit the host arrays; staged, only copies do
     const uintptr_t align_mask = c->staged ? 3u : 15u;
     if ((reinterpret_cast<uintptr_t>(h_p) | reinterpret_cast<uintptr_t>(h_m) | reinterpret_cast<uintptr_t>(h_v)) & align_mask)
         return GS_ERR_INVALID_ARG;
-    gs_status st = stream_validate(c, d_w_bf16, d_grads, k, n, hp, d_sqnorm);
+    if (begin < 0 || end < begin) return GS_ERR_INVALID_ARG;
+    gs_status st = stream_validate(c, d_w_bf16, d_grads, k, end, hp, d_sqnorm);
     if (st != GS_OK) return st;
-    if (n == 0) return GS_OK;
+    if (begin == end) return GS_OK;
     if (!c->staged) {
-        if ((st = stream_check_mapped(h_p, n)) != GS_OK || (st = stream_check_mapped(h_m, n)) != GS_OK ||
-            (st = stream_check_mapped(h_v, n)) != GS_OK)
+        const int64_t len = end - begin;
+        if ((st = stream_check_mapped(h_p + begin, len)) != GS_OK || (st = stream_check_mapped(h_m + begin, len)) != GS_OK ||
+            (st = stream_check_mapped(h_v + begin, len)) != GS_OK)
             return st;
     }
 
     StepArgs A;
     st = stream_begin_layer(c, A, d_w_bf16, d_grads, k, hp, d_sqnorm, producer_stream);
     if (st != GS_OK) return st;
-    if (!c->staged) return stream_range(c, A, h_p, h_m, h_v, 0, n);
-    for (int64_t b = 0; b < n; b += c->chunk) {
-        const int64_t e = (b + c->chunk < n) ? b + c->chunk : n;
+    if (!c->staged) return stream_range(c, A, h_p + begin, h_m + begin, h_v + begin, begin, end);
+    for (int64_t b = begin; b < end; b += c->chunk) {
+        const int64_t e = (b + c->chunk < end) ? b + c->chunk : end;
         st = staged_chunk(c, A, h_p + b, h_m + b, h_v + b, b, e);
         if (st != GS_OK) return st;
     }
     return GS_OK;
+}
+
+gs_status gs_stream_layer_step(gs_stream_ctx *c, float *h_p, float *h_m, float *h_v,
+                               uint16_t *d_w_bf16, const uint16_t *const *d_grads, int k, int64_t n,
+                               const gs_adamw_hparams *hp, const double *d_sqnorm,
+                               void *producer_stream)
+{
+    if (n < 0) return GS_ERR_INVALID_ARG;
+    return gs_stream_layer_step_range(c, h_p, h_m, h_v, d_w_bf16, d_grads, k, 0, n, hp, d_sqnorm, producer_stream);
 }
 
 }  // extern "C"

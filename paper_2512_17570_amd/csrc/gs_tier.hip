@@ -340,8 +340,16 @@ gs_status gs_tier_layer_step(gs_tier_ctx *t, const gs_tier_layer *L, uint16_t *d
                              const uint16_t *const *d_grads, int k, int64_t n,
                              const gs_adamw_hparams *hp, const double *d_sqnorm, void *producer_stream)
 {
+    return gs_tier_layer_step_range(t, L, d_w_bf16, d_grads, k, n, 0, n, hp, d_sqnorm, producer_stream);
+}
+
+gs_status gs_tier_layer_step_range(gs_tier_ctx *t, const gs_tier_layer *L, uint16_t *d_w_bf16,
+                                   const uint16_t *const *d_grads, int k, int64_t n, int64_t begin, int64_t end,
+                                   const gs_adamw_hparams *hp, const double *d_sqnorm, void *producer_stream)
+{
     if (!t || !L) return GS_ERR_INVALID_ARG;
     if (n < 0 || L->n_host < 0 || L->n_host > n) return GS_ERR_INVALID_ARG;
+    if (begin < 0 || end < begin || end > n) return GS_ERR_INVALID_ARG;
     if (L->n_host > 0) {
         if (!L->h_p || !L->h_m || !L->h_v) return GS_ERR_INVALID_ARG;
         if ((reinterpret_cast<uintptr_t>(L->h_p) | reinterpret_cast<uintptr_t>(L->h_m) |
@@ -358,15 +366,19 @@ gs_status gs_tier_layer_step(gs_tier_ctx *t, const gs_tier_layer *L, uint16_t *d
         std::lock_guard<std::mutex> g(t->mu);
         if (t->err != GS_OK) return t->err;     // a failed context stays failed
     }
-    if (n == 0) return GS_OK;
-    if (L->n_host > 0) {
-        if ((st = stream_check_mapped(L->h_p, L->n_host)) != GS_OK || (st = stream_check_mapped(L->h_m, L->n_host)) != GS_OK ||
-            (st = stream_check_mapped(L->h_v, L->n_host)) != GS_OK)
+    if (begin == end) return GS_OK;
+    // the parts of the range that fall into the host share and into the file share
+    const int64_t h_lo = begin, h_hi = end < L->n_host ? end : L->n_host;          // empty if h_hi <= h_lo
+    const int64_t f_lo = begin > L->n_host ? begin : L->n_host, f_hi = end;        // empty if f_hi <= f_lo
+    if (h_hi > h_lo) {
+        const int64_t len = h_hi - h_lo;
+        if ((st = stream_check_mapped(L->h_p + h_lo, len)) != GS_OK || (st = stream_check_mapped(L->h_m + h_lo, len)) != GS_OK ||
+            (st = stream_check_mapped(L->h_v + h_lo, len)) != GS_OK)
             return st;
     }
 
     bool direct = false;
-    if (L->n_host < n) {
+    if (f_hi > f_lo) {
         const int fds[3] = {L->fd_p, L->fd_m, L->fd_v};
         for (int a = 0; a < 3; ++a) {
             const int fl = fcntl(fds[a], F_GETFL);
@@ -391,23 +403,23 @@ gs_status gs_tier_layer_step(gs_tier_ctx *t, const gs_tier_layer *L, uint16_t *d
     // is element-wise: the order of chunks does not change any result.)
     const int fd[3] = {L->fd_p, L->fd_m, L->fd_v};
     const int64_t base[3] = {L->off_p, L->off_m, L->off_v};
-    const int64_t host_chunks = (L->n_host + t->chunk - 1) / t->chunk;
-    const int64_t file_chunks = (n - L->n_host + t->chunk - 1) / t->chunk;
+    const int64_t host_chunks = h_hi > h_lo ? (h_hi - h_lo + t->chunk - 1) / t->chunk : 0;
+    const int64_t file_chunks = f_hi > f_lo ? (f_hi - f_lo + t->chunk - 1) / t->chunk : 0;
     int64_t hi = 0, fi = 0;
     while (hi < host_chunks || fi < file_chunks) {
         // next: the share that is further behind (fi/file_chunks < hi/host_chunks); ties go to the file share,
         // whose read takes host time
         const bool take_file = fi < file_chunks && (hi >= host_chunks || fi * host_chunks <= hi * file_chunks);
         if (!take_file) {
-            const int64_t b = hi * t->chunk;
-            const int64_t e = (b + t->chunk < L->n_host) ? b + t->chunk : L->n_host;
+            const int64_t b = h_lo + hi * t->chunk;
+            const int64_t e = (b + t->chunk < h_hi) ? b + t->chunk : h_hi;
             ++hi;
             st = stream_range(c, A, L->h_p + b, L->h_m + b, L->h_v + b, b, e);
             if (st != GS_OK) return st;
             continue;
         }
-        const int64_t b = L->n_host + fi * t->chunk;
-        const int64_t e = (b + t->chunk < n) ? b + t->chunk : n;
+        const int64_t b = f_lo + fi * t->chunk;
+        const int64_t e = (b + t->chunk < f_hi) ? b + t->chunk : f_hi;
         ++fi;
         const int64_t len = e - b;
         const int slot = (int)(t->next_slot % t->slots);

@@ -398,6 +398,42 @@ def gs_tier_layer_step(ctx, h_p, h_m, h_v, n_host: int, fds, offsets, d_w_bf16, 
     return _check(st, "gs_tier_layer_step", check)
 
 
+_lib.gs_stream_layer_step_range.argtypes = [_vp, _vp, _vp, _vp, _vp, _pp, ctypes.c_int, _i64, _i64, _vp, _vp, _vp]
+_lib.gs_stream_layer_step_range.restype = ctypes.c_int
+_lib.gs_tier_layer_step_range.argtypes = [_vp, ctypes.POINTER(gs_tier_layer), _vp, _pp, ctypes.c_int, _i64, _i64, _i64,
+                                          _vp, _vp, _vp]
+_lib.gs_tier_layer_step_range.restype = ctypes.c_int
+
+
+def gs_stream_layer_step_range(ctx, h_p, h_m, h_v, d_w_bf16, d_grads, begin: int, end: int, hp, d_sqnorm=None,
+                               producer_stream=None, check: bool = True, k: int | None = None) -> int:
+    tab, kk = _table(d_grads) if d_grads is not None else (None, 0)
+    for j, g in enumerate(d_grads or ()):
+        _need(g, end, 2, f"d_grads[{j}]")
+    for x, eb, nm in ((h_p, 4, "h_p"), (h_m, 4, "h_m"), (h_v, 4, "h_v"), (d_w_bf16, 2, "d_w_bf16")):
+        _need(x, end, eb, nm)
+    st = _lib.gs_stream_layer_step_range(ctx, _addr(h_p), _addr(h_m), _addr(h_v), _addr(d_w_bf16), tab,
+                                         kk if k is None else k, begin, end, _hp(hp), _addr(d_sqnorm),
+                                         _stream(producer_stream))
+    return _check(st, "gs_stream_layer_step_range", check)
+
+
+def gs_tier_layer_step_range(ctx, h_p, h_m, h_v, n_host: int, fds, offsets, d_w_bf16, d_grads, n: int, begin: int,
+                             end: int, hp, d_sqnorm=None, producer_stream=None, check: bool = True,
+                             k: int | None = None) -> int:
+    tab, kk = _table(d_grads) if d_grads is not None else (None, 0)
+    for j, g in enumerate(d_grads or ()):
+        _need(g, n, 2, f"d_grads[{j}]")
+    _need(d_w_bf16, n, 2, "d_w_bf16")
+    for x, nm in ((h_p, "h_p"), (h_m, "h_m"), (h_v, "h_v")):
+        _need(x, n_host, 4, nm)
+    layer = gs_tier_layer(_addr(h_p), _addr(h_m), _addr(h_v), n_host, fds[0], fds[1], fds[2],
+                          offsets[0], offsets[1], offsets[2])
+    st = _lib.gs_tier_layer_step_range(ctx, ctypes.byref(layer), _addr(d_w_bf16), tab, kk if k is None else k, n,
+                                       begin, end, _hp(hp), _addr(d_sqnorm), _stream(producer_stream))
+    return _check(st, "gs_tier_layer_step_range", check)
+
+
 def gs_pinned_alloc(nbytes: int) -> int | None:
     return _lib.gs_pinned_alloc(nbytes)
 

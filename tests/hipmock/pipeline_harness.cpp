@@ -126,8 +126,20 @@ static void test_stream(int64_t n, int num_cus, int64_t chunk = 0, int slots = 0
                 *g = real;
             });
             const uint16_t *gt[1] = {g->data()};
-            CHECK(gs_stream_layer_step(ctx, hp_[l][0], hp_[l][1], hp_[l][2], Ls[l]->w.data(), gt, 1, Ls[l]->n, &HP, nullptr,
-                                       producer) == GS_OK, "layer step");
+            if (step == 1) {
+                CHECK(gs_stream_layer_step(ctx, hp_[l][0], hp_[l][1], hp_[l][2], Ls[l]->w.data(), gt, 1, Ls[l]->n, &HP, nullptr,
+                                           producer) == GS_OK, "layer step");
+            } else {
+                // the second step in three unaligned pieces, the last one first
+                const int64_t cut[4] = {0, Ls[l]->n / 5 + 1, 3 * Ls[l]->n / 4 + 2, Ls[l]->n};
+                for (int piece = 2; piece >= 0; --piece)
+                    CHECK(gs_stream_layer_step_range(ctx, hp_[l][0], hp_[l][1], hp_[l][2], Ls[l]->w.data(), gt, 1, cut[piece],
+                                                     cut[piece + 1], &HP, nullptr, producer) == GS_OK, "layer step range");
+                CHECK(gs_stream_layer_step_range(ctx, hp_[l][0], hp_[l][1], hp_[l][2], Ls[l]->w.data(), gt, 1, 7, 7, &HP, nullptr,
+                                                 producer) == GS_OK, "empty range");
+                CHECK(gs_stream_layer_step_range(ctx, hp_[l][0], hp_[l][1], hp_[l][2], Ls[l]->w.data(), gt, 1, 9, 3, &HP, nullptr,
+                                                 producer) == GS_ERR_INVALID_ARG, "reversed range accepted");
+            }
         }
         CHECK(gs_stream_ctx_sync(ctx) == GS_OK, "sync");
         for (int l = 0; l < 2; ++l) {
@@ -220,8 +232,18 @@ static void test_tier(const std::string &dir, int64_t n, int64_t n_host, int64_t
     for (int step = 1; step <= 2; ++step) {
         for (int l = 0; l < 2; ++l) {
             const uint16_t *gt[2] = {Ls[l]->g.data(), Ls[l]->g.data()};
-            CHECK(gs_tier_layer_step(ctx, &desc[l], Ls[l]->w.data(), gt, 2, Ls[l]->n, &HP, nullptr, nullptr) == GS_OK,
-                  "tier layer step: %s", gs_tier_ctx_error(ctx));
+            if (step == 1) {
+                CHECK(gs_tier_layer_step(ctx, &desc[l], Ls[l]->w.data(), gt, 2, Ls[l]->n, &HP, nullptr, nullptr) == GS_OK,
+                      "tier layer step: %s", gs_tier_ctx_error(ctx));
+            } else {
+                // the second step in three unaligned pieces (the cuts fall into either share, depending on n_host)
+                const int64_t cut[4] = {0, Ls[l]->n / 5 + 1, 3 * Ls[l]->n / 4 + 2, Ls[l]->n};
+                for (int piece = 2; piece >= 0; --piece)
+                    CHECK(gs_tier_layer_step_range(ctx, &desc[l], Ls[l]->w.data(), gt, 2, Ls[l]->n, cut[piece], cut[piece + 1],
+                                                   &HP, nullptr, nullptr) == GS_OK, "tier range: %s", gs_tier_ctx_error(ctx));
+                CHECK(gs_tier_layer_step_range(ctx, &desc[l], Ls[l]->w.data(), gt, 2, Ls[l]->n, 5, Ls[l]->n + 1, &HP, nullptr,
+                                               nullptr) == GS_ERR_INVALID_ARG, "range past the layer accepted");
+            }
         }
         CHECK(gs_tier_ctx_sync(ctx) == GS_OK, "tier sync: %s", gs_tier_ctx_error(ctx));
         for (int l = 0; l < 2; ++l) {

@@ -29,7 +29,8 @@ def test_header_symbols_all_exported():
             "gs_pinned_free", "gs_strerror", "gs_last_hip_error", "gs_grad_accum_sqnorm", "gs_adamw_from_acc",
             "gs_cu_stream_create", "gs_cu_stream_destroy", "gs_accum_adamw_oop", "gs_accum_adamw_spec",
             "gs_clip_coefficient", "gs_sqnorm_workspace_bytes_for", "gs_accum_add", "gs_acc_sqnorm",
-            "gs_tier_ctx_create", "gs_tier_ctx_destroy", "gs_tier_ctx_sync", "gs_tier_ctx_error", "gs_tier_layer_step"} <= set(names)
+            "gs_tier_ctx_create", "gs_tier_ctx_destroy", "gs_tier_ctx_sync", "gs_tier_ctx_error", "gs_tier_layer_step",
+            "gs_stream_layer_step_range", "gs_tier_layer_step_range"} <= set(names)
     lib = ctypes.CDLL(gs.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in gs.h but not exported"
@@ -136,6 +137,10 @@ def test_tier_api_rejects_without_gpu():
     assert gs.gs_tier_layer_step(None, FAKE, FAKE, FAKE, 4, (3, 4, 5), (0, 0, 0), FAKE, [FAKE], 10, GOOD_HP,
                                  check=False) == gs.GS_ERR_INVALID_ARG
     assert gs.gs_strerror(gs.GS_ERR_IO) == "file read or write failed"
+    assert gs.gs_tier_layer_step_range(None, FAKE, FAKE, FAKE, 4, (3, 4, 5), (0, 0, 0), FAKE, [FAKE], 10, 0, 10, GOOD_HP,
+                                       check=False) == gs.GS_ERR_INVALID_ARG
+    assert gs.gs_stream_layer_step_range(None, FAKE, FAKE, FAKE, FAKE, [FAKE], 0, 10, GOOD_HP,
+                                         check=False) == gs.GS_ERR_INVALID_ARG
 
 
 def test_accum_add_rejects_without_gpu():

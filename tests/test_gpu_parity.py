@@ -369,6 +369,38 @@ def test_staged_pipeline_two_layers_back_to_back_reuse_slots():
                 gs.gs_pinned_free(ptr)
 
 
+@pytest.mark.parametrize("mode", ["inplace", "staged"])
+def test_streamed_split_ranges_equal_full(mode):
+    """The split step on host-resident states: the deferred part first, then the immediate part,
+    at an unaligned split point, leaves bit for bit what the resident full step leaves."""
+    n = 2048 * 300 + 77
+    s_pt = int(0.4 * n) + 1
+    case = DeviceCase(n, 3, seed=82)
+    case.gpu_sqnorm()
+    full = run_gpu_step(case, HP)
+    bufs = [gs.pinned_f32(n) for _ in range(3)]
+    ctx = gs.gs_stream_ctx_create_inplace(16) if mode == "inplace" else gs.gs_stream_ctx_create(70_001, 3)
+    try:
+        for (t, _), src in zip(bufs, (case.p, case.m, case.v)):
+            t.copy_(src.cpu())
+        w = torch.zeros_like(case.w)
+        ptrs = [ptr for _, ptr in bufs]
+        gs.gs_stream_layer_step_range(ctx, *ptrs, w, case.grads, s_pt, n, HP, case.sq)
+        gs.gs_stream_ctx_sync(ctx)
+        for (t, _), src in zip(bufs, (case.p, case.m, case.v)):      # the immediate part is still untouched
+            assert np.array_equal(t[:s_pt].numpy(), np_f32(src[:s_pt]))
+        gs.gs_stream_layer_step_range(ctx, *ptrs, w, case.grads, 0, s_pt, HP, case.sq)
+        gs.gs_stream_layer_step_range(ctx, *ptrs, w, case.grads, 11, 11, HP, case.sq)
+        gs.gs_stream_ctx_sync(ctx)
+        for (t, _), ref in zip(bufs, full[:3]):
+            assert np.array_equal(t.numpy(), np_f32(ref))
+        assert torch.equal(w, full[3])
+    finally:
+        gs.gs_stream_ctx_destroy(ctx)
+        for t, ptr in bufs:
+            gs.gs_pinned_free(ptr)
+
+
 def test_streamed_rejects_misaligned_host_arrays_and_bad_cu_counts():
     n = 4096
     case = DeviceCase(n, 1, seed=81)
@@ -492,6 +524,44 @@ def test_tiered_equals_resident_and_oracle(tmp_path, x, chunk, slots, cus):
             if step == 1:
                 compare_states(ref, case.oracle_step(HP, O.clip_coef(O.grad_sqnorm(case.h_g), HP.max_grad_norm)),
                                f"tiered x={x}")
+    finally:
+        gs.gs_tier_ctx_destroy(ctx)
+        for fd in fds:
+            os.close(fd)
+        for _, ptr in bufs:
+            gs.gs_pinned_free(ptr)
+
+
+@pytest.mark.parametrize("x", [0.0, 0.3, 0.7, 1.0])
+def test_tiered_split_ranges_equal_full(tmp_path, x):
+    """The split step on tiered states: [s,n) then [0,s) with the split point falling into the
+    host share or the file share, depending on x; bit for bit the resident full step."""
+    n, k, header = 512 * 700 + 19, 2, 8
+    s_pt = n // 2 + 3
+    case = DeviceCase(n, k, seed=98)
+    n_host = int(round(x * n))
+    init = [np_f32(t) for t in (case.p, case.m, case.v)]
+    fds, paths = _write_states(tmp_path, "R", init, n_host, header)
+    bufs = [gs.pinned_f32(max(n_host, 1)) for _ in range(3)]
+    ctx = gs.gs_tier_ctx_create(60_001, 3, 0)
+    try:
+        for (tn, _), a in zip(bufs, init):
+            tn[:n_host].copy_(torch.from_numpy(a[:n_host]))
+        case.gpu_sqnorm()
+        w = torch.zeros_like(case.w)
+        args = (bufs[0][1], bufs[1][1], bufs[2][1], n_host, fds, (header,) * 3, w, case.grads, n)
+        gs.gs_tier_layer_step_range(ctx, *args, s_pt, n, HP, case.sq)
+        gs.gs_tier_layer_step_range(ctx, *args, 0, s_pt, HP, case.sq)
+        gs.gs_tier_ctx_sync(ctx)
+        assert gs.gs_tier_ctx_error(ctx) == ""
+        full = run_gpu_step(case, HP)
+        tail = _read_states(paths, n - n_host, header)
+        for (tn, _), fl, r in zip(bufs, tail, full[:3]):
+            want = np_f32(r)
+            assert np.array_equal(tn[:n_host].numpy(), want[:n_host])
+            assert np.array_equal(fl, want[n_host:])
+        assert torch.equal(w, full[3])
+        assert gs.gs_tier_layer_step_range(ctx, *args, 5, n + 1, HP, case.sq, check=False) == gs.GS_ERR_INVALID_ARG
     finally:
         gs.gs_tier_ctx_destroy(ctx)
         for fd in fds:

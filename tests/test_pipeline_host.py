@@ -90,7 +90,9 @@ MUTANTS = [
     ("file_offset_from_layer_start", "gs_tier.hip",
      "off[a] = base[a] + (b - L->n_host) * (int64_t)sizeof(float);", "off[a] = base[a] + b * (int64_t)sizeof(float);"),
     ("host_chunk_index_off_by_one", "gs_tier.hip",
-     "            const int64_t b = hi * t->chunk;", "            const int64_t b = (hi ? hi - 1 : 0) * t->chunk;"),
+     "            const int64_t b = h_lo + hi * t->chunk;", "            const int64_t b = h_lo + (hi ? hi - 1 : 0) * t->chunk;"),
+    ("file_part_of_a_range_starts_at_the_host_boundary", "gs_tier.hip",
+     "const int64_t f_lo = begin > L->n_host ? begin : L->n_host, f_hi = end;", "const int64_t f_lo = L->n_host, f_hi = end;"),
     ("bounce_offset_forgotten_on_write_back", "gs_tier.hip",
      "        j.pad = (int)pad;", "        j.pad = 0;"),
 ]
