@@ -49,18 +49,47 @@ def test_every_mutation_site_exists_once():
         assert src.count(old) == 1, f"{name}: mutation site not found exactly once"
 
 
-@pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
-def test_pins_catch_mutant(tmp_path, name, old, new):
+def _run_mutant(work, name, old, new):
+    """Builds the mutant and runs the pin suite against it; returns (returncode, tail of stdout)."""
     src = open(SRC).read()
     assert src.count(old) == 1
-    csrc = tmp_path / "mutant.c"
-    csrc.write_text(src.replace(old, new))
-    lib = tmp_path / "libmutant.so"
+    d = os.path.join(work, name)
+    os.makedirs(d, exist_ok=True)
+    csrc = os.path.join(d, "mutant.c")
+    with open(csrc, "w") as f:
+        f.write(src.replace(old, new))
+    lib = os.path.join(d, "libmutant.so")
     subprocess.run(["gcc", "-O2", "-ffp-contract=off", "-fno-fast-math", "-std=c11", "-shared", "-fPIC",
-                    str(csrc), "-o", str(lib), "-lm"], check=True)
-    env = dict(os.environ, GS_ORACLE_LIB=str(lib))
-    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
+                    csrc, "-o", lib, "-lm"], check=True)
+    env = dict(os.environ, GS_ORACLE_LIB=lib)
+    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider", "-p", "no:xdist",
                         os.path.join(ROOT, "tests", "test_oracle_pins.py")],
                        cwd=ROOT, env=env, capture_output=True, text=True)
-    assert r.returncode != 0, f"mutant {name} survived the pins:\n{r.stdout[-2000:]}"
-    assert "failed" in r.stdout or "error" in r.stdout.lower()
+    return r.returncode, r.stdout[-2000:]
+
+
+@pytest.fixture(scope="module")
+def mutant_results(tmp_path_factory):
+    """All mutants are built and judged once, a few at a time (each run is a separate process that
+    mostly waits for its interpreter to start)."""
+    from concurrent.futures import ThreadPoolExecutor
+    work = str(tmp_path_factory.mktemp("oracle_mutants"))
+    table = {m[0]: m for m in MUTANTS}
+    if os.environ.get("PYTEST_XDIST_WORKER"):
+        # the test run is already spread over worker processes: each test judges its own mutant
+        class OnDemand(dict):
+            def __missing__(self, name):
+                self[name] = _run_mutant(work, *table[name])
+                return self[name]
+        return OnDemand()
+    workers = max(1, min(6, (os.cpu_count() or 2) - 1))
+    with ThreadPoolExecutor(workers) as ex:
+        futs = {name: ex.submit(_run_mutant, work, *m) for name, m in table.items()}
+        return {name: f.result() for name, f in futs.items()}
+
+
+@pytest.mark.parametrize("name", [m[0] for m in MUTANTS])
+def test_pins_catch_mutant(mutant_results, name):
+    rc, out = mutant_results[name]
+    assert rc != 0, f"mutant {name} survived the pins:\n{out}"
+    assert "failed" in out or "error" in out.lower()

@@ -103,23 +103,51 @@ def test_mutation_sites_exist_once():
         assert open(os.path.join(CSRC, fn)).read().count(old) == 1, name
 
 
-@pytest.mark.parametrize("name,fn,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
-def test_harness_notices_planted_pipeline_mistake(tmp_path, tsan_ok, name, fn, old, new):
+def _judge_mutant(work, tsan, name, fn, old, new):
+    """Builds the harness from a copy of the host sources with one planted mistake and runs it.
+    Returns True if the harness noticed (wrong result, sanitizer report, or a hang)."""
+    d = os.path.join(work, name)
+    src = os.path.join(d, "src")
+    os.makedirs(src, exist_ok=True)
+    for f in os.listdir(CSRC):
+        if f.endswith((".hip", ".h")):
+            shutil.copy(os.path.join(CSRC, f), os.path.join(src, f))
+    path = os.path.join(src, fn)
+    text = open(path).read()
+    assert text.count(old) == 1
+    with open(path, "w") as f:
+        f.write(text.replace(old, new))
+    exe = os.path.join(d, "harness")
+    _build(src, exe, tsan)
+    try:
+        r = _run(exe, os.path.join(d, "scratch"))
+    except subprocess.TimeoutExpired:
+        return True      # a hang is a failure of the mutant too
+    return r.returncode != 0 or "ThreadSanitizer" in r.stderr
+
+
+@pytest.fixture(scope="module")
+def mutant_verdicts(tmp_path_factory, tsan_ok):
+    """All mutants are built and run once, a few at a time; under pytest-xdist each test judges its
+    own mutant instead (the run is already spread over processes)."""
+    from concurrent.futures import ThreadPoolExecutor
+    work = str(tmp_path_factory.mktemp("pipeline_mutants"))
+    table = {m[0]: m for m in MUTANTS}
+    if os.environ.get("PYTEST_XDIST_WORKER"):
+        class OnDemand(dict):
+            def __missing__(self, name):
+                self[name] = _judge_mutant(work, tsan_ok, *table[name])
+                return self[name]
+        return OnDemand()
+    workers = max(1, min(6, (os.cpu_count() or 2) - 1))
+    with ThreadPoolExecutor(workers) as ex:
+        futs = {name: ex.submit(_judge_mutant, work, tsan_ok, *m) for name, m in table.items()}
+        return {name: f.result() for name, f in futs.items()}
+
+
+@pytest.mark.parametrize("name", [m[0] for m in MUTANTS])
+def test_harness_notices_planted_pipeline_mistake(mutant_verdicts, tsan_ok, name):
     if not tsan_ok and name in ("kernel_ignores_producer", "read_into_slot_still_being_written",
                                 "staged_upload_ignores_pending_download"):
         pytest.skip("without ThreadSanitizer this ordering mistake only shows by chance")
-    src = tmp_path / "src"
-    src.mkdir()
-    for f in os.listdir(CSRC):
-        if f.endswith((".hip", ".h")):
-            shutil.copy(os.path.join(CSRC, f), src / f)
-    text = (src / fn).read_text()
-    assert text.count(old) == 1
-    (src / fn).write_text(text.replace(old, new))
-    exe = str(tmp_path / "harness")
-    _build(str(src), exe, tsan_ok)
-    try:
-        r = _run(exe, str(tmp_path / "scratch"))
-    except subprocess.TimeoutExpired:
-        return      # a hang is a failure of the mutant too
-    assert r.returncode != 0 or "ThreadSanitizer" in r.stderr, f"mutant {name} went unnoticed"
+    assert mutant_verdicts[name], f"mutant {name} went unnoticed"
