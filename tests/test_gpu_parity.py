@@ -570,6 +570,44 @@ def test_tiered_split_ranges_equal_full(tmp_path, x):
             gs.gs_pinned_free(ptr)
 
 
+def test_tiered_two_layers_back_to_back_share_the_bounce_slots(tmp_path):
+    """Two layers with different host/file splits enqueued on one context without a sync in
+    between (the second layer's reads reuse bounce slots the first layer's write-backs release)."""
+    specs = [(512 * 500 + 9, 0.2, 120), (512 * 300 + 301, 0.6, 121)]
+    ctx = gs.gs_tier_ctx_create(40_000, 2, 16)
+    held = []
+    try:
+        for n, x, seed in specs:
+            case = DeviceCase(n, 2, seed=seed)
+            n_host = int(round(x * n))
+            init = [np_f32(t) for t in (case.p, case.m, case.v)]
+            fds, paths = _write_states(tmp_path, f"B{seed}", init, n_host, 16)
+            bufs = [gs.pinned_f32(max(n_host, 1)) for _ in range(3)]
+            for (tn, _), a in zip(bufs, init):
+                tn[:n_host].copy_(torch.from_numpy(a[:n_host]))
+            case.gpu_sqnorm()
+            w = torch.zeros_like(case.w)
+            gs.gs_tier_layer_step(ctx, bufs[0][1], bufs[1][1], bufs[2][1], n_host, fds, (16,) * 3, w, case.grads, n, HP,
+                                  case.sq)
+            held.append((case, n_host, fds, paths, bufs, w))
+        gs.gs_tier_ctx_sync(ctx)
+        assert gs.gs_tier_ctx_error(ctx) == ""
+        for case, n_host, fds, paths, bufs, w in held:
+            full = run_gpu_step(case, HP)
+            tail = _read_states(paths, case.n - n_host, 16)
+            for (tn, _), fl, r in zip(bufs, tail, full[:3]):
+                want = np_f32(r)
+                assert np.array_equal(tn[:n_host].numpy(), want[:n_host]) and np.array_equal(fl, want[n_host:])
+            assert torch.equal(w, full[3])
+    finally:
+        gs.gs_tier_ctx_destroy(ctx)
+        for _, _, fds, _, bufs, _ in held:
+            for fd in fds:
+                os.close(fd)
+            for _, ptr in bufs:
+                gs.gs_pinned_free(ptr)
+
+
 def test_tiered_with_direct_io_descriptors(tmp_path):
     """O_DIRECT descriptors, the way an SSD tier is read: with n_host, the chunk and the file share
     multiples of 1024 elements and block-aligned file offsets every transfer the tier makes is
