@@ -525,12 +525,16 @@ def bench_tiered(args, wl):
         ctx = gs.gs_tier_ctx_create(chunk, args.slots, args.stream_cus)
         cur = torch.cuda.current_stream()
 
+        issue_s = []         # time the caller spends inside the (queueing) calls of one pass
+
         def one_pass(i):
             hp = _hp_of(gs, wl, i)
+            t_issue = time.perf_counter()
             for L in range(layers):
                 (_, pp), (_, pm), (_, pv) = hosts[L]
                 gs.gs_tier_layer_step(ctx, pp, pm, pv, n_host, fds[L], (0, 0, 0), w_l[L], grads_l[L], nl, hp, sq,
                                       producer_stream=cur)
+            issue_s.append(time.perf_counter() - t_issue)
             gs.gs_tier_ctx_sync(ctx)
 
         print(f"[tiered] raw pwrite {write_gbs} GB/s; timing", file=sys.stderr, flush=True)
@@ -571,7 +575,8 @@ def bench_tiered(args, wl):
                            {"layers": layers, "n_params": n, "chunk_elems": chunk, "slots": args.slots,
                             "host_share_x": x, "file_bytes": layers * n_file * 12, "host_pinned_bytes": layers * n_host * 12,
                             "tier_dir": os.path.dirname(root), "o_direct": bool(args.tier_direct), "stream_cus": args.stream_cus,
-                            "tier_dir_fs_free_bytes": free})
+                            "tier_dir_fs_free_bytes": free,
+                            "caller_blocked_ms_per_pass": 1e3 * sum(issue_s[args.warmup:]) / max(1, args.steps)})
         file_dir = layers * n_file * 12 / per / 1e9
         # the pipeline reads and writes at once, so the both-at-once probe is the ceiling it is held against
         peak = duplex_gbs if duplex_gbs else (min(read_gbs, write_gbs) if write_gbs else read_gbs)

@@ -350,29 +350,37 @@ typedef struct {
 
 /*
  * Creates a context: a gs_stream_ctx (num_cus as for gs_stream_ctx_create_inplace), `slots` (2..64) bounce
- * slots of 3 x chunk_elems fp32 in pinned host memory (each array starts on a 4 KB boundary), and
- * one writer thread.  chunk_elems in [1, 2^34].  GS_ERR_NOMEM if the pinned memory cannot be had.
+ * slots of 3 x chunk_elems fp32 in pinned host memory (each array starts on a 4 KB boundary), one
+ * reader and one writer thread.  chunk_elems in [1, 2^34].  GS_ERR_NOMEM if the pinned memory
+ * cannot be had.
  */
 gs_status gs_tier_ctx_create(gs_tier_ctx **out, int64_t chunk_elems, int slots, int num_cus);
 
 /*
  * Applies the same update as gs_accum_adamw to all n elements of the layer described by *L.
  * The host share is stepped in place like gs_stream_layer_step, in launches of chunk_elems.  The
- * file share is walked in chunks of chunk_elems, interleaved with those launches: the CALLING
- * thread reads p/m/v of a chunk into a bounce slot (waiting, if need be, until the writer has
- * released that slot) and enqueues the kernel in place on the slot; the writer thread writes the
- * slot back to the same file offsets once the kernel has finished.
- * The call returns when the last chunk has been read and enqueued -- not when it has been
- * written; host arrays, files and device tensors must stay untouched until gs_tier_ctx_sync.
+ * file share is walked in chunks of chunk_elems, interleaved with those launches: the context's
+ * reader thread reads p/m/v of a chunk into a bounce slot (waiting, if need be, until the writer
+ * has released that slot) and enqueues the kernel in place on the slot; the writer thread writes
+ * the slot back to the same file offsets once the kernel has finished.
+ * The call itself does no I/O and never waits for any: it checks its arguments, records an event
+ * on producer_stream (the step runs after whatever that stream holds at this moment), copies *L,
+ * *hp and the k gradient pointers, queues the layer behind earlier ones and returns.  Host
+ * arrays, files, gradients and d_w_bf16 must stay valid and untouched until gs_tier_ctx_sync;
+ * L, hp and the d_grads table itself may go at once.  A range of a layer's file share must not
+ * be queued twice without a gs_tier_ctx_sync in between (the second read could overtake the
+ * first write-back).
  * Results are bit-identical to gs_accum_adamw on a device copy of the same states, for every
  * n_host and chunk size.  Other arguments as for gs_stream_layer_step.  The files must hold the
- * whole range (a short file is GS_ERR_IO).  Descriptors opened with O_DIRECT are recognised
+ * whole range (a short file is GS_ERR_IO, reported like every I/O failure: see below).  Descriptors opened with O_DIRECT are recognised
  * (fcntl): their transfers go through ordinary page-aligned memory of the bounce slots' size
  * (allocated on first use) and one extra host copy, because the kernel cannot do direct I/O on
  * page-locked memory that the GPU driver maps; offsets, n_host*4, chunk_elems*4 and (n-n_host)*4
  * then have to be multiples of the device's block size.  The descriptors are not closed.
- * One thread at a time per context.  After any failure of the file tier the context stays
- * failed: this call and gs_tier_ctx_sync return that status, gs_tier_ctx_error its text.
+ * One calling thread at a time per context.  Reads, writes and enqueues fail on the context's
+ * own threads, after the call that queued them has returned GS_OK: the first such failure makes
+ * the context failed for good -- layers still queued are dropped, gs_tier_ctx_sync and every
+ * later call return that status, gs_tier_ctx_error its text.
  */
 gs_status gs_tier_layer_step(gs_tier_ctx *ctx, const gs_tier_layer *L, uint16_t *d_w_bf16,
                              const uint16_t *const *d_grads, int k, int64_t n,
@@ -388,7 +396,7 @@ gs_status gs_tier_layer_step_range(gs_tier_ctx *ctx, const gs_tier_layer *L, uin
 /* Blocks until every enqueued chunk has been computed and written back to its host array or file
  * (the page cache counts as written; fsync is the caller's call). */
 gs_status gs_tier_ctx_sync(gs_tier_ctx *ctx);
-gs_status gs_tier_ctx_destroy(gs_tier_ctx *ctx); /* syncs, stops the writer, frees everything */
+gs_status gs_tier_ctx_destroy(gs_tier_ctx *ctx); /* syncs, stops both threads, frees everything */
 /* Text of the context's first file-tier failure ("" if none), e.g. "pwrite(m): No space left on
  * device".  The pointer is valid until the calling thread's next call of this function. */
 const char *gs_tier_ctx_error(gs_tier_ctx *ctx);

@@ -5,10 +5,12 @@
 // share of the states stays in CPU memory instead (Sec. 4.5).  Here a layer's fp32 p/m/v are
 // split the same way: elements [0,n_host) in pinned host memory, elements [n_host,n) in files.
 // The host share is stepped in place by the kernel, over the link.  The file share is walked in
-// chunks, interleaved with launches over the host share: for file chunk c the calling thread
-// reads p/m/v into a pinned bounce slot and enqueues the step kernel in place on that slot, and
-// a writer thread, woken by a host function that follows the kernel, writes the slot back to
-// the files.  Reading chunk c+1 overlaps the kernel of chunk c and the write-back of chunk c-1.
+// chunks, interleaved with launches over the host share: for file chunk c a reader thread reads
+// p/m/v into a pinned bounce slot and enqueues the step kernel in place on that slot, and a
+// writer thread, woken by a host function that follows the kernel, writes the slot back to the
+// files.  Reading chunk c+1 overlaps the kernel of chunk c and the write-back of chunk c-1, and
+// the caller is not held up by any of it: a call only checks its arguments, marks the producer
+// stream and queues the layer.
 //
 // Every element goes through the same kernel with the same absolute-index grouping as the
 // resident step, so the result is bit-identical for any n_host and chunk size.
@@ -45,6 +47,16 @@ struct WriteJob {
     bool direct;            // the descriptors are O_DIRECT: go through the slot's ordinary-memory twin
     int fd[3];
     int64_t off[3];         // byte offsets
+};
+
+// One queued call: everything the reader thread needs, copied at call time.
+struct LayerJob {
+    gs_tier_layer L;
+    StepArgs A;             // w, gradient table, step constants, norm pointer
+    int64_t h_lo, h_hi;     // the part of the range in the host share (empty if h_hi <= h_lo)
+    int64_t f_lo, f_hi;     // the part of the range in the file share
+    bool direct;
+    hipEvent_t ev_producer; // recorded on the caller's producer stream at call time
 };
 
 // Whole-buffer pread / pwrite (short transfers are continued; EOF on read is an error).
@@ -162,6 +174,11 @@ struct gs_tier_ctx {
     std::string err_text;                   // guarded by mu
     std::thread writer;
     bool writer_started = false;
+    std::deque<LayerJob> layers;            // queued calls (guarded by mu)
+    bool reader_active = false;             // the reader is inside a layer (guarded by mu)
+    std::thread reader;
+    bool reader_started = false;
+    std::vector<hipEvent_t> spare_events;   // producer events not in use (guarded by mu)
 
     float *slot_ptr(int slot, int which) const
     {
@@ -240,21 +257,24 @@ static void writer_main(gs_tier_ctx *t)
 static void tier_free(gs_tier_ctx *t)
 {
     if (!t) return;
-    if (t->writer_started) {
-        {
-            std::lock_guard<std::mutex> g(t->mu);
-            t->stop = true;
-        }
-        t->cv.notify_all();
-        t->writer.join();
+    {
+        std::lock_guard<std::mutex> g(t->mu);
+        t->stop = true;
     }
+    t->cv.notify_all();
+    if (t->reader_started) t->reader.join();
+    if (t->writer_started) t->writer.join();
     if (t->sc) (void)gs_stream_ctx_destroy(t->sc);
+    for (auto e : t->spare_events)
+        if (e) (void)hipEventDestroy(e);
     for (auto e : t->ev_done)
         if (e) (void)hipEventDestroy(e);
     if (t->bounce) (void)hipHostFree(t->bounce);
     free(t->plain);
     delete t;
 }
+
+static void reader_main(gs_tier_ctx *t);
 
 extern "C" {
 
@@ -299,6 +319,8 @@ gs_status gs_tier_ctx_create(gs_tier_ctx **out, int64_t chunk_elems, int slots, 
     try {
         t->writer = std::thread(writer_main, t);
         t->writer_started = true;
+        t->reader = std::thread(reader_main, t);
+        t->reader_started = true;
     } catch (...) {
         tier_free(t);
         return GS_ERR_NOMEM;
@@ -312,7 +334,7 @@ gs_status gs_tier_ctx_sync(gs_tier_ctx *t)
     if (!t) return GS_ERR_INVALID_ARG;
     {
         std::unique_lock<std::mutex> lk(t->mu);
-        t->cv.wait(lk, [&] { return t->jobs.empty() && !t->writer_active; });
+        t->cv.wait(lk, [&] { return t->layers.empty() && !t->reader_active && t->jobs.empty() && !t->writer_active; });
     }
     gs_status st = gs_stream_ctx_sync(t->sc);
     std::lock_guard<std::mutex> g(t->mu);
@@ -394,9 +416,73 @@ gs_status gs_tier_layer_step_range(gs_tier_ctx *t, const gs_tier_layer *L, uint1
     }
 
     gs_stream_ctx *c = t->sc;
-    StepArgs A;
-    st = stream_begin_layer(c, A, d_w_bf16, d_grads, k, hp, d_sqnorm, producer_stream);
-    if (st != GS_OK) return st;
+    int cur = -1;
+    hipError_t he = hipGetDevice(&cur);
+    if (he != hipSuccess) return hip_fail(he, "hipGetDevice");
+    if (cur != c->device) return GS_ERR_INVALID_ARG;   // the context lives on another GPU
+
+    LayerJob job;
+    memset(&job.A, 0, sizeof job.A);
+    job.L = *L;
+    job.A.w = d_w_bf16;
+    for (int j = 0; j < k; ++j) job.A.gt.g[j] = d_grads[j];
+    job.A.k = k;
+    job.A.c = make_consts(*hp);
+    job.A.max_norm = hp->max_grad_norm;
+    job.A.d_sqnorm = d_sqnorm;
+    job.h_lo = h_lo;
+    job.h_hi = h_hi;
+    job.f_lo = f_lo;
+    job.f_hi = f_hi;
+    job.direct = direct;
+    // gradients and the norm come from the caller's stream: mark where it stands now
+    job.ev_producer = nullptr;
+    {
+        std::lock_guard<std::mutex> g(t->mu);
+        if (!t->spare_events.empty()) {
+            job.ev_producer = t->spare_events.back();
+            t->spare_events.pop_back();
+        }
+    }
+    if (!job.ev_producer) {
+        he = hipEventCreateWithFlags(&job.ev_producer, hipEventDisableTiming);
+        if (he != hipSuccess) return hip_fail(he, "hipEventCreateWithFlags");
+    }
+    he = hipEventRecord(job.ev_producer, static_cast<hipStream_t>(producer_stream));
+    if (he != hipSuccess) {
+        std::lock_guard<std::mutex> g(t->mu);
+        t->spare_events.push_back(job.ev_producer);
+        return hip_fail(he, "hipEventRecord(producer)");
+    }
+    {
+        std::lock_guard<std::mutex> g(t->mu);
+        t->layers.push_back(job);
+    }
+    t->cv.notify_all();
+    return GS_OK;
+}
+
+}  // extern "C"
+
+// The reader thread's work for one queued call.  Failures are recorded in the context (the call
+// that queued the layer has long returned).
+static void run_layer(gs_tier_ctx *t, LayerJob &job)
+{
+    gs_stream_ctx *c = t->sc;
+    StepArgs &A = job.A;
+    const gs_tier_layer *L = &job.L;
+    const int64_t h_lo = job.h_lo, h_hi = job.h_hi, f_lo = job.f_lo, f_hi = job.f_hi;
+    const bool direct = job.direct;
+    gs_status st = GS_OK;
+    hipError_t we = hipStreamWaitEvent(c->s_comp, job.ev_producer, 0);
+    {
+        std::lock_guard<std::mutex> g(t->mu);
+        t->spare_events.push_back(job.ev_producer);   // the wait has captured the record: free for reuse
+    }
+    if (we != hipSuccess) {
+        t->fail(hip_fail(we, "hipStreamWaitEvent(producer)"), "hipStreamWaitEvent(producer)", 0);
+        return;
+    }
 
     // The two shares are walked together, each in proportion to its size, so that file reads and
     // write-backs run alongside the host share's PCIe traffic instead of after it.  (The update
@@ -415,7 +501,10 @@ gs_status gs_tier_layer_step_range(gs_tier_ctx *t, const gs_tier_layer *L, uint1
             const int64_t e = (b + t->chunk < h_hi) ? b + t->chunk : h_hi;
             ++hi;
             st = stream_range(c, A, L->h_p + b, L->h_m + b, L->h_v + b, b, e);
-            if (st != GS_OK) return st;
+            if (st != GS_OK) {
+                t->fail(st, "enqueue of a host chunk failed", 0);
+                return;
+            }
             continue;
         }
         const int64_t b = f_lo + fi * t->chunk;
@@ -427,7 +516,7 @@ gs_status gs_tier_layer_step_range(gs_tier_ctx *t, const gs_tier_layer *L, uint1
         {
             std::unique_lock<std::mutex> lk(t->mu);
             t->cv.wait(lk, [&] { return !t->busy[slot]; });
-            if (t->err != GS_OK) return t->err;
+            if (t->err != GS_OK) return;     // the writer failed: stop feeding it
         }
         int64_t off[3];
         for (int a = 0; a < 3; ++a) off[a] = base[a] + (b - L->n_host) * (int64_t)sizeof(float);
@@ -442,7 +531,7 @@ gs_status gs_tier_layer_step_range(gs_tier_ctx *t, const gs_tier_layer *L, uint1
         if (bad >= 0) {
             static const char *const names[3] = {"pread(p)", "pread(m)", "pread(v)"};
             t->fail(GS_ERR_IO, names[bad], rerr);
-            return GS_ERR_IO;
+            return;
         }
         st = stream_range(c, A, buf[0], buf[1], buf[2], b, e);
         if (st == GS_OK) {
@@ -455,7 +544,7 @@ gs_status gs_tier_layer_step_range(gs_tier_ctx *t, const gs_tier_layer *L, uint1
         }
         if (st != GS_OK) {
             t->fail(st, "enqueue of a file chunk failed", 0);
-            return st;
+            return;
         }
         WriteJob j;
         j.slot = slot;
@@ -473,7 +562,30 @@ gs_status gs_tier_layer_step_range(gs_tier_ctx *t, const gs_tier_layer *L, uint1
         }
         t->cv.notify_all();
     }
-    return GS_OK;
 }
 
-}  // extern "C"
+static void reader_main(gs_tier_ctx *t)
+{
+    const hipError_t de = hipSetDevice(t->device);
+    if (de != hipSuccess) t->fail(hip_fail(de, "hipSetDevice"), "hipSetDevice (reader thread)", 0);
+    for (;;) {
+        LayerJob job;
+        bool skip;
+        {
+            std::unique_lock<std::mutex> lk(t->mu);
+            t->cv.wait(lk, [&] { return t->stop || !t->layers.empty(); });
+            if (t->layers.empty()) return;  // stop requested and nothing left
+            job = t->layers.front();
+            t->layers.pop_front();
+            t->reader_active = true;
+            skip = t->err != GS_OK;         // a failed context steps nothing further
+            if (skip) t->spare_events.push_back(job.ev_producer);
+        }
+        if (!skip) run_layer(t, job);
+        {
+            std::lock_guard<std::mutex> g(t->mu);
+            t->reader_active = false;
+        }
+        t->cv.notify_all();
+    }
+}

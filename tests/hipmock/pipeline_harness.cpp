@@ -216,6 +216,8 @@ static void test_tier(const std::string &dir, int64_t n, int64_t n_host, int64_t
     int64_t nh[2] = {n_host, n_host > B.n ? B.n : n_host / 2};
     gs_tier_ctx *ctx = nullptr;
     CHECK(gs_tier_ctx_create(&ctx, chunk, slots, 0) == GS_OK, "tier create");
+    hipStream_t producer = nullptr;
+    CHECK(hipStreamCreateWithFlags(&producer, hipStreamNonBlocking) == hipSuccess, "producer stream");
     float *host[2][3] = {{nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr}};
     Files *files[2];
     gs_tier_layer desc[2];
@@ -233,8 +235,24 @@ static void test_tier(const std::string &dir, int64_t n, int64_t n_host, int64_t
         for (int l = 0; l < 2; ++l) {
             const uint16_t *gt[2] = {Ls[l]->g.data(), Ls[l]->g.data()};
             if (step == 1) {
-                CHECK(gs_tier_layer_step(ctx, &desc[l], Ls[l]->w.data(), gt, 2, Ls[l]->n, &HP, nullptr, nullptr) == GS_OK,
+                // the call copies what it was handed: the descriptor, the pointer table and the
+                // hyper-parameters may change as soon as it returns, long before the layer is read
+                gs_tier_layer d = desc[l];
+                gs_adamw_hparams hp = HP;
+                // ... and the gradients are "produced" late on the caller's stream: the reader thread's
+                // launches have to wait for the point that stream had reached at call time
+                std::vector<uint16_t> *g = &Ls[l]->g;
+                std::vector<uint16_t> real = *g;
+                std::fill(g->begin(), g->end(), (uint16_t)0x7777);
+                hipmock_enqueue(producer, [g, real] {
+                    std::this_thread::sleep_for(std::chrono::milliseconds(20));
+                    *g = real;
+                });
+                CHECK(gs_tier_layer_step(ctx, &d, Ls[l]->w.data(), gt, 2, Ls[l]->n, &hp, nullptr, producer) == GS_OK,
                       "tier layer step: %s", gs_tier_ctx_error(ctx));
+                memset(&d, 0xff, sizeof d);
+                memset(&hp, 0xff, sizeof hp);
+                gt[0] = gt[1] = nullptr;
             } else {
                 // the second step in three unaligned pieces (the cuts fall into either share, depending on n_host)
                 const int64_t cut[4] = {0, Ls[l]->n / 5 + 1, 3 * Ls[l]->n / 4 + 2, Ls[l]->n};
@@ -259,6 +277,7 @@ static void test_tier(const std::string &dir, int64_t n, int64_t n_host, int64_t
         }
     }
     CHECK(gs_tier_ctx_destroy(ctx) == GS_OK, "tier destroy");
+    CHECK(hipStreamDestroy(producer) == hipSuccess, "producer stream destroy");
     for (int l = 0; l < 2; ++l) {
         delete files[l];
         for (int a = 0; a < 3; ++a) gs_pinned_free(host[l][a]);
@@ -323,7 +342,9 @@ static void test_tier_failures(const std::string &dir)
         gs_tier_ctx *ctx = nullptr;
         CHECK(gs_tier_ctx_create(&ctx, 1024, 2, 0) == GS_OK, "create");
         gs_tier_layer d{nullptr, nullptr, nullptr, 0, f.fd[0], f.fd[1], f.fd[2], 0, 0, 0};
-        CHECK(gs_tier_layer_step(ctx, &d, A.w.data(), gt, 1, A.n, &HP, nullptr, nullptr) == GS_ERR_IO, "short file accepted");
+        // the call only queues the layer; the reader thread meets the short read
+        CHECK(gs_tier_layer_step(ctx, &d, A.w.data(), gt, 1, A.n, &HP, nullptr, nullptr) == GS_OK, "queueing failed");
+        CHECK(gs_tier_ctx_sync(ctx) == GS_ERR_IO, "short file accepted");
         CHECK(strstr(gs_tier_ctx_error(ctx), "pread") != nullptr, "error text: '%s'", gs_tier_ctx_error(ctx));
         CHECK(gs_tier_ctx_sync(ctx) == GS_ERR_IO, "sync after failure");
         CHECK(gs_tier_layer_step(ctx, &d, A.w.data(), gt, 1, 10, &HP, nullptr, nullptr) == GS_ERR_IO, "failed context reused");

@@ -95,6 +95,12 @@ MUTANTS = [
      "const int64_t f_lo = begin > L->n_host ? begin : L->n_host, f_hi = end;", "const int64_t f_lo = L->n_host, f_hi = end;"),
     ("bounce_offset_forgotten_on_write_back", "gs_tier.hip",
      "        j.pad = (int)pad;", "        j.pad = 0;"),
+    ("tier_kernel_ignores_producer", "gs_tier.hip",
+     "    hipError_t we = hipStreamWaitEvent(c->s_comp, job.ev_producer, 0);", "    hipError_t we = hipSuccess;"),
+    ("tier_sync_ignores_queued_layers", "gs_tier.hip",
+     "return t->layers.empty() && !t->reader_active && t->jobs.empty()", "return t->jobs.empty()"),
+    ("tier_sync_ignores_layer_being_read", "gs_tier.hip",
+     "return t->layers.empty() && !t->reader_active && t->jobs.empty()", "return t->layers.empty() && t->jobs.empty()"),
 ]
 
 
@@ -148,6 +154,6 @@ def mutant_verdicts(tmp_path_factory, tsan_ok):
 @pytest.mark.parametrize("name", [m[0] for m in MUTANTS])
 def test_harness_notices_planted_pipeline_mistake(mutant_verdicts, tsan_ok, name):
     if not tsan_ok and name in ("kernel_ignores_producer", "read_into_slot_still_being_written",
-                                "staged_upload_ignores_pending_download"):
+                                "staged_upload_ignores_pending_download", "tier_kernel_ignores_producer"):
         pytest.skip("without ThreadSanitizer this ordering mistake only shows by chance")
     assert mutant_verdicts[name], f"mutant {name} went unnoticed"
