@@ -738,6 +738,12 @@ def main():
     torch.cuda.synchronize()
     spec_ms = es[0].elapsed_time(es[-1]) / args.steps
     del B_, A_
+    # what this device gives a plain device-to-device copy of one state array (read + written bytes):
+    # the practical ceiling for a kernel that, like the step, both reads and writes
+    cp_dst = torch.empty_like(p)
+    copy_ms = timed(lambda: cp_dst.copy_(p), max(4, args.steps))
+    del cp_dst
+    copy_gbs = 8 * n / (copy_ms * 1e-3) / 1e9
     step_bytes = n * (2 * k + 26)
     norm_bytes = n * 2 * k
     achieved = step_bytes / (step_ms * 1e-3) / 1e9
@@ -762,7 +768,12 @@ def main():
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
                      "algorithmic_bytes_per_launch": step_bytes, "avg_launch_ms": step_ms,
-                     "params_per_s": n / (step_ms * 1e-3)},
+                     "params_per_s": n / (step_ms * 1e-3),
+                     "achievable": {"device_copy_GBps": copy_gbs, "frac_of_device_copy": achieved / copy_gbs,
+                                    "read_only_GBps": n * 4 / (acc_norm_ms * 1e-3) / 1e9,
+                                    "frac_of_read_only": achieved / (n * 4 / (acc_norm_ms * 1e-3) / 1e9),
+                                    "note": "measured here after the timed region: a device-to-device copy of one fp32 "
+                                            "state array (bytes read + written) and a read-only pass (gs_acc_sqnorm)"}},
         "kernels": {
             "gs_accum_adamw": {"avg_ms": step_ms, "bytes_per_param": 2 * k + 26, "GBps": achieved},
             "gs_grad_sqnorm": {"avg_ms": norm_ms, "bytes_per_param": 2 * k,
