@@ -89,9 +89,9 @@ typedef struct {
  * and k (about 2 MB). */
 size_t gs_sqnorm_workspace_bytes(void);
 
-/* Workspace size with which gs_grad_accum_sqnorm and gs_accum_adamw_spec run in their fastest
- * shape on a range of `range_elems` elements (one partial per 512-element tile: about
- * range_elems/64 bytes; never less than gs_sqnorm_workspace_bytes()).  Those two calls accept any
+/* Workspace size with which gs_grad_accum_sqnorm, gs_accum_adamw_spec and gs_accum_add (with a
+ * norm) run in their fastest shape on a range of `range_elems` elements (one partial per
+ * 256-element tile: about range_elems/32 bytes; never less than gs_sqnorm_workspace_bytes()).  Those calls accept any
  * workspace of at least the minimum size and pick the shape that fits; results do not depend on
  * it beyond fp64 summation order.  gs_grad_sqnorm itself gains nothing from a larger workspace. */
 size_t gs_sqnorm_workspace_bytes_for(int64_t range_elems);

@@ -74,8 +74,8 @@ size_t gs_sqnorm_workspace_bytes_for(int64_t range_elems)
 {
     const size_t base = gs_sqnorm_workspace_bytes();
     if (range_elems <= 0) return base;
-    // one partial per 512-element tile (+2 for ragged ends) and the folding slices
-    const size_t want = ((size_t)(range_elems / (GS_STEP_BLOCK * 4)) + 2 + GS_FINAL_SLICES) * sizeof(double);
+    // one partial per 256-element tile (+2 for ragged ends) and the folding slices
+    const size_t want = ((size_t)(range_elems / (GS_WAVE_BLOCK * 4)) + 2 + GS_FINAL_SLICES) * sizeof(double);
     return want > base ? want : base;
 }
 

@@ -7,7 +7,12 @@
 
 #include "gs.h"
 
-#define GS_STEP_BLOCK 128             // threads per workgroup of the step kernels (2 wave64)
+#define GS_STEP_BLOCK 128             // threads per workgroup of the step kernel for many gradient streams, and of the
+                                      // staged norm kernel (2 wave64)
+#define GS_WAVE_BLOCK 64              // single-wave workgroups: the step kernel otherwise, and the fast shapes of the
+                                      // kernels that step or add and leave a norm partial per workgroup
+#define GS_STEP_WIDE_MIN_K 15         // gradient streams from which the step kernel takes GS_STEP_BLOCK lanes
+#define GS_STATE_WAIT_MAX_K 7         // up to this many gradient streams each state load is waited for on its own
 #define GS_BLOCK 256                  // threads per workgroup of the norm kernel (4 wave64)
 #define GS_TILE (GS_BLOCK * 4)        // elements per norm tile: one group of 4 per lane
 #define GS_FINAL_BLOCK 1024           // threads of the partial-folding kernels

@@ -220,14 +220,14 @@ __device__ __forceinline__ void step_group(const StepArgs &A, int k, int64_t lo,
         } else {
             // State loads go first.  With many gradient streams they stay in flight while the
             // gradient loads are walked one by one (k = 16: 7.46 ms against 7.83 ms when each state
-            // load is waited for); with few (k <= 6, where reads and writes are nearly balanced)
-            // waiting for each wins by 2-4 %, as in the staged case above.
+            // load is waited for); with few (where reads and writes are nearly balanced) waiting
+            // for each wins by 2-4 %, as in the staged case above.
             p = ld_stream(reinterpret_cast<const f32x4 *>(A.p + lo));
-            if (DEPTH != 0 && k <= 6) wait_vm_idle();
+            if (DEPTH != 0 && k <= GS_STATE_WAIT_MAX_K) wait_vm_idle();
             m = ld_stream(reinterpret_cast<const f32x4 *>(A.m + lo));
-            if (DEPTH != 0 && k <= 6) wait_vm_idle();
+            if (DEPTH != 0 && k <= GS_STATE_WAIT_MAX_K) wait_vm_idle();
             v = ld_stream(reinterpret_cast<const f32x4 *>(A.v + lo));
-            if (DEPTH != 0 && k <= 6) wait_vm_idle();
+            if (DEPTH != 0 && k <= GS_STATE_WAIT_MAX_K) wait_vm_idle();
             accumulate_group<K, DEPTH>(A.gt, k, lo, a);
         }
         float P[4] = {p.x, p.y, p.z, p.w};
@@ -278,15 +278,17 @@ __device__ __forceinline__ void step_group(const StepArgs &A, int k, int64_t lo,
     }
 }
 
-// One workgroup = one tile of 512 consecutive elements (GS_STEP_BLOCK = 128 lanes x 4), one group of
-// 4 per lane.  Tiles start at multiples of the tile size counted from element 0 of the arrays, not from
+// One workgroup = one tile of BLOCK*4 consecutive elements, one group of 4 per lane.  BLOCK is 64
+// (one wave) up to 14 gradient streams and for the staged step, 128 from 15 on: measured on
+// 805 M elements, single-wave workgroups are 1-3.5 % faster for k = 1..14 (k = 8: 5.50 ms against
+// 5.70 ms) and level or 1 % slower at k = 16; 256 lanes lose 4-6 % everywhere.  Tiles start at multiples of the tile size counted from element 0 of the arrays, not from
 // `begin`: the grouping does not move with the range (partition independence), and a wave's
 // 1 KB accesses stay line-aligned for any `begin` (a split point in the middle of a layer would
 // otherwise make every wave straddle two extra lines).
-template <int K>
-__global__ __launch_bounds__(GS_STEP_BLOCK) void k_accum_adamw(StepArgs A)
+template <int K, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void k_accum_adamw(StepArgs A)
 {
-    constexpr int TILE = GS_STEP_BLOCK * 4;
+    constexpr int TILE = BLOCK * 4;
     const int k = (K > 0) ? K : A.k;     // K < 0: gradients come as one staged fp32 sum (A.acc)
     const int64_t lo = (A.begin / TILE + (int64_t)blockIdx.x) * TILE + (int64_t)threadIdx.x * 4;
     if (lo >= A.end || lo + 4 <= A.begin) return;
@@ -489,20 +491,25 @@ static int64_t tiles_of(int64_t begin, int64_t end, int64_t tile = GS_TILE)
 
 hipError_t launch_accum_adamw(const StepArgs &A, hipStream_t stream)
 {
-    const int64_t tiles = tiles_of(A.begin, A.end, (int64_t)GS_STEP_BLOCK * 4);
+    const bool wide = !A.acc && A.k >= GS_STEP_WIDE_MIN_K;
+    const int64_t tiles = tiles_of(A.begin, A.end, (int64_t)(wide ? GS_STEP_BLOCK : GS_WAVE_BLOCK) * 4);
     if (tiles < 1 || tiles > 0x7fffffff) return hipErrorInvalidValue;
     const int grid = (int)tiles;
     if (A.acc) {
-        k_accum_adamw<-1><<<grid, GS_STEP_BLOCK, 0, stream>>>(A);
+        k_accum_adamw<-1, GS_WAVE_BLOCK><<<grid, GS_WAVE_BLOCK, 0, stream>>>(A);
         return hipGetLastError();
     }
     // k = 1, 2 unrolled; every other k takes the runtime loop, which keeps one gradient load in
     // flight per wave with the fewest registers (27 VGPRs: full occupancy) and measured as fast
     // as or faster than unrolled bodies for k = 4, 8, 16
+    if (wide) {
+        k_accum_adamw<0, GS_STEP_BLOCK><<<grid, GS_STEP_BLOCK, 0, stream>>>(A);
+        return hipGetLastError();
+    }
     switch (A.k) {
-    case 1: k_accum_adamw<1><<<grid, GS_STEP_BLOCK, 0, stream>>>(A); break;
-    case 2: k_accum_adamw<2><<<grid, GS_STEP_BLOCK, 0, stream>>>(A); break;
-    default: k_accum_adamw<0><<<grid, GS_STEP_BLOCK, 0, stream>>>(A); break;
+    case 1: k_accum_adamw<1, GS_WAVE_BLOCK><<<grid, GS_WAVE_BLOCK, 0, stream>>>(A); break;
+    case 2: k_accum_adamw<2, GS_WAVE_BLOCK><<<grid, GS_WAVE_BLOCK, 0, stream>>>(A); break;
+    default: k_accum_adamw<0, GS_WAVE_BLOCK><<<grid, GS_WAVE_BLOCK, 0, stream>>>(A); break;
     }
     return hipGetLastError();
 }
@@ -517,10 +524,21 @@ hipError_t launch_accum_adamw_spec(const StepArgs &A, double *partials, size_t w
                                    int accumulate, hipStream_t stream)
 {
     const int64_t cap = partial_capacity(workspace_bytes);
-    int64_t tiles = tiles_of(A.begin, A.end, (int64_t)GS_STEP_BLOCK * 4);
+    // fastest shape the workspace has room for: one tile per workgroup, runtime gradient loop,
+    // shallow queues -- single-wave workgroups (k = 16: 7.42 ms, k = 8: 5.28 ms on 805 M elements),
+    // else two waves (7.58 / 5.54 ms)
+    int64_t tiles = tiles_of(A.begin, A.end, (int64_t)GS_WAVE_BLOCK * 4);
     if (tiles < 1) tiles = 1;
     if (tiles <= cap && tiles <= 0x7fffffff) {
-        // one 512-element tile per workgroup, runtime gradient loop, shallow queues
+        const int grid = (int)tiles;
+        k_accum_adamw_spec<0, GS_WAVE_BLOCK, 1><<<grid, GS_WAVE_BLOCK, 0, stream>>>(A, partials, 1);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        return launch_fold(partials, cap, grid, d_out, accumulate, stream);
+    }
+    tiles = tiles_of(A.begin, A.end, (int64_t)GS_STEP_BLOCK * 4);
+    if (tiles < 1) tiles = 1;
+    if (tiles <= cap && tiles <= 0x7fffffff) {
         const int grid = (int)tiles;
         k_accum_adamw_spec<0, GS_STEP_BLOCK, 1><<<grid, GS_STEP_BLOCK, 0, stream>>>(A, partials, 1);
         hipError_t e = hipGetLastError();
@@ -609,8 +627,6 @@ hipError_t launch_acc_sqnorm(const float *acc, int64_t begin, int64_t end, doubl
 hipError_t launch_accum_add(const AccumAddArgs &A, int first, size_t workspace_bytes, double *d_out, int accumulate,
                             hipStream_t stream)
 {
-    int64_t tiles = tiles_of(A.begin, A.end, (int64_t)GS_STEP_BLOCK * 4);
-    if (tiles < 1) tiles = 1;
     if (!d_out) {
         // no partials to leave behind: single-wave workgroups over 256-element tiles measured best
         // (1.17 ms against 1.23 ms with two waves per workgroup, 805 M elements)
@@ -623,7 +639,14 @@ hipError_t launch_accum_add(const AccumAddArgs &A, int first, size_t workspace_b
     }
     const int64_t cap = partial_capacity(workspace_bytes);
     int grid;
-    if (tiles <= cap && tiles <= 0x7fffffff) {
+    const int64_t tiles64 = tiles_of(A.begin, A.end, (int64_t)GS_WAVE_BLOCK * 4);
+    int64_t tiles = tiles_of(A.begin, A.end, (int64_t)GS_STEP_BLOCK * 4);
+    if (tiles64 >= 1 && tiles64 <= cap && tiles64 <= 0x7fffffff) {
+        // single-wave workgroups here too: 1.24 ms against 1.29 ms with two waves (805 M elements)
+        grid = (int)tiles64;
+        if (first) k_accum_add<true, true, GS_WAVE_BLOCK><<<grid, GS_WAVE_BLOCK, 0, stream>>>(A, 1);
+        else k_accum_add<false, true, GS_WAVE_BLOCK><<<grid, GS_WAVE_BLOCK, 0, stream>>>(A, 1);
+    } else if (tiles >= 1 && tiles <= cap && tiles <= 0x7fffffff) {
         grid = (int)tiles;
         if (first) k_accum_add<true, true, GS_STEP_BLOCK><<<grid, GS_STEP_BLOCK, 0, stream>>>(A, 1);
         else k_accum_add<false, true, GS_STEP_BLOCK><<<grid, GS_STEP_BLOCK, 0, stream>>>(A, 1);

@@ -217,7 +217,7 @@ def test_workspace_size_for_range():
     assert gs.gs_sqnorm_workspace_bytes_for(0) == base and gs.gs_sqnorm_workspace_bytes_for(-5) == base
     assert gs.gs_sqnorm_workspace_bytes_for(1 << 20) == base
     big = gs.gs_sqnorm_workspace_bytes_for(805_412_864)
-    assert big > base and big % 8 == 0 and 805_412_864 // 64 <= big <= 805_412_864 // 64 + 4096
+    assert big > base and big % 8 == 0 and 805_412_864 // 32 <= big <= 805_412_864 // 32 + 4096    # a double per 256 elements
     assert gs.gs_sqnorm_workspace_bytes_for(1 << 34) > big
 
 

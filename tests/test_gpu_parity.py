@@ -1020,6 +1020,49 @@ def test_staged_and_speculative_fast_shapes_with_large_workspace(k):
         assert torch.equal(a, b)
 
 
+def test_workspace_size_picks_the_shape_not_the_result():
+    """The norm-carrying kernels have three shapes (one 256-element tile per single-wave workgroup,
+    one 512-element tile per two-wave workgroup, 4096-element tiles with several per workgroup) and
+    take the fastest one whose partials fit the workspace.  On a range large enough that the
+    minimum workspace forces the third, all three must leave the same bits (the norm: the same
+    value up to fp64 summation order), and those bits are the fused step's with c = 1."""
+    n, k = 140_000_003, 1
+    g = torch.Generator(device=DEV).manual_seed(77)
+    p = torch.randn(n, device=DEV, generator=g) * 0.02
+    m = torch.randn(n, device=DEV, generator=g) * 1e-3
+    v = (torch.randn(n, device=DEV, generator=g) * 1e-3) ** 2
+    grads = [(torch.randn(n, device=DEV, generator=g) * 1e-3).to(torch.bfloat16)]
+    base = gs.gs_sqnorm_workspace_bytes()
+    mid = (n // 512 + 2 + 128) * 8
+    big = gs.gs_sqnorm_workspace_bytes_for(n)
+    assert base < (n // 512) * 8 and mid < (n // 256) * 8 <= big     # each size rules out the faster shapes
+    ref = [p.clone(), m.clone(), v.clone(), torch.zeros(n, dtype=torch.bfloat16, device=DEV)]
+    gs.gs_accum_adamw(ref[0], ref[1], ref[2], ref[3], grads, 0, n, HP, None)
+    sq_ref = torch.zeros(1, dtype=torch.float64, device=DEV)
+    gs.gs_grad_sqnorm(grads, 0, n, sq_ref, torch.empty(base, dtype=torch.uint8, device=DEV))
+    torch.cuda.synchronize()
+    S = float(sq_ref.item())
+    acc_ref = grads[0].float()
+    for nbytes in (base, mid, big):
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+        sq = torch.zeros(1, dtype=torch.float64, device=DEV)
+        out = [torch.empty_like(p), torch.empty_like(m), torch.empty_like(v), torch.zeros(n, dtype=torch.bfloat16, device=DEV)]
+        gs.gs_accum_adamw_spec(p, m, v, out[0], out[1], out[2], out[3], grads, 0, n, HP, sq, ws)
+        torch.cuda.synchronize()
+        assert abs(float(sq.item()) - S) <= 1e-12 * S, nbytes
+        for a, b, nm in zip(out, ref, "pmvw"):
+            assert torch.equal(a, b), f"spec with a {nbytes}-byte workspace differs in {nm}"
+        del out
+        acc = torch.full((n,), float("nan"), dtype=torch.float32, device=DEV)
+        gs.gs_accum_add(acc, grads[0], True, 0, n, sq, ws)
+        torch.cuda.synchronize()
+        assert abs(float(sq.item()) - S) <= 1e-12 * S and torch.equal(acc, acc_ref), nbytes
+        gs.gs_grad_accum_sqnorm(grads, 5, n - 3, acc, sq, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(acc, acc_ref)
+        del acc, ws
+
+
 # ----------------------------------------------------------------------------- the ABI from plain C
 def test_c_program_drives_the_abi_without_python_or_torch():
     """tests/c_abi/step_demo.c (C99, built by the package's build step) allocates with the HIP
