@@ -78,7 +78,7 @@ def test_sqnorm_exact_patterns():
 
 
 # ----------------------------------------------------------------------------- a1,a3-a6 fused step
-@pytest.mark.parametrize("k", [1, 2, 3, 4, 7, 8, 16, 17, 32])
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 7, 8, 14, 15, 16, 17, 32])     # 14 | 15: the workgroup shape changes
 def test_step_matches_oracle_all_k(k):
     n = 2 * 2048 * 256 + 2048 * 3 + 5           # ~1000 tiles, ragged tail
     case = DeviceCase(n, k, seed=10 + k)
@@ -166,7 +166,7 @@ def test_first_step_closed_form_on_gpu():
 
 
 # ----------------------------------------------------------------------------- a7 split == full
-@pytest.mark.parametrize("k", [4, 5])
+@pytest.mark.parametrize("k", [4, 5, 16])
 def test_split_equals_full_bitwise(k):
     n = 2048 * 300 + 11
     case = DeviceCase(n, k, seed=50)
