@@ -102,8 +102,8 @@ bool write_all(int fd, const void *buf, size_t bytes, int64_t off, int *err)
     return true;
 }
 
-// p, m and v of one chunk move concurrently (two helper threads + the caller); if a thread cannot
-// be started its transfer runs on the caller instead.  via != nullptr: the file side of each
+// p, m and v of one chunk move concurrently (two helper threads + the thread that asks); if a thread cannot
+// be started its transfer runs on the asking thread instead.  via != nullptr: the file side of each
 // transfer uses via[a] (ordinary page-aligned memory) and the data is copied between via[a] and
 // buf[a] -- descriptors opened with O_DIRECT cannot transfer to or from page-locked memory that
 // the GPU driver maps (EFAULT).  Returns the index of the first array that failed (errno in *err),
@@ -228,8 +228,8 @@ static void writer_main(gs_tier_ctx *t)
             t->writer_active = true;
         }
         // The chunk's completion is announced by a host function enqueued behind its kernel;
-        // this thread makes no HIP call, so it cannot get in the way of the
-        // caller's enqueues.
+        // this thread makes no HIP call, so it cannot get in the way of the reader thread's
+        // (or the caller's own) enqueues.
         {
             std::unique_lock<std::mutex> lk(t->mu);
             t->cv.wait(lk, [&] { return t->finished[j.slot] != 0; });
