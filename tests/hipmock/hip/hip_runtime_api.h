@@ -67,5 +67,8 @@ void hipmock_enqueue(hipStream_t s, std::function<void()> fn);
 /* copies issued / bytes moved since process start, and a per-copy delay to widen race windows */
 extern "C" uint64_t hipmock_copy_count(void);
 extern "C" void hipmock_set_copy_delay_us(int us);
+/* the nth call from now of the named API (hipEventRecord, hipStreamWaitEvent, hipLaunchHostFunc,
+ * hipMemcpyAsync) returns hipErrorUnknown and does nothing; api == NULL disarms */
+extern "C" void hipmock_fail_nth(const char *api, int nth);
 #endif
 #endif

@@ -9,6 +9,7 @@
 #include <deque>
 #include <map>
 #include <mutex>
+#include <string>
 #include <thread>
 
 struct hipmock_stream {
@@ -77,6 +78,18 @@ struct hipmock_event {
 static std::atomic<uint64_t> g_copies{0};
 static std::atomic<int> g_delay_us{0};
 
+// Planted failure: the nth call (counted from the moment it is armed) of one API returns an error
+// and does nothing else.
+static std::mutex g_fault_mu;
+static std::string g_fault_api;
+static int g_fault_countdown = 0;
+static bool fault_now(const char *api)
+{
+    std::lock_guard<std::mutex> g(g_fault_mu);
+    if (g_fault_countdown <= 0 || g_fault_api != api) return false;
+    return --g_fault_countdown == 0;
+}
+
 void hipmock_enqueue(hipStream_t s, std::function<void()> fn)
 {
     if (!s) {
@@ -90,6 +103,12 @@ extern "C" {
 
 uint64_t hipmock_copy_count(void) { return g_copies.load(); }
 void hipmock_set_copy_delay_us(int us) { g_delay_us.store(us); }
+void hipmock_fail_nth(const char *api, int nth)
+{
+    std::lock_guard<std::mutex> g(g_fault_mu);
+    g_fault_api = api ? api : "";
+    g_fault_countdown = api ? nth : 0;
+}
 
 const char *hipGetErrorString(hipError_t e) { return e == hipSuccess ? "no error" : "mock error"; }
 hipError_t hipGetLastError(void) { return hipSuccess; }
@@ -167,6 +186,7 @@ hipError_t hipEventDestroy(hipEvent_t e)
 
 hipError_t hipEventRecord(hipEvent_t e, hipStream_t s)
 {
+    if (fault_now("hipEventRecord")) return hipErrorUnknown;
     uint64_t seq;
     {
         std::lock_guard<std::mutex> g(e->mu);
@@ -184,6 +204,7 @@ hipError_t hipEventRecord(hipEvent_t e, hipStream_t s)
 
 hipError_t hipStreamWaitEvent(hipStream_t s, hipEvent_t e, unsigned)
 {
+    if (fault_now("hipStreamWaitEvent")) return hipErrorUnknown;
     uint64_t target;
     {
         std::lock_guard<std::mutex> g(e->mu);
@@ -206,12 +227,14 @@ hipError_t hipEventSynchronize(hipEvent_t e)
 
 hipError_t hipLaunchHostFunc(hipStream_t s, hipHostFn_t fn, void *userData)
 {
+    if (fault_now("hipLaunchHostFunc")) return hipErrorUnknown;
     hipmock_enqueue(s, [fn, userData] { fn(userData); });
     return hipSuccess;
 }
 
 hipError_t hipMemcpyAsync(void *dst, const void *src, size_t bytes, hipMemcpyKind, hipStream_t s)
 {
+    if (fault_now("hipMemcpyAsync")) return hipErrorUnknown;
     hipmock_enqueue(s, [=] {
         int d = g_delay_us.load();
         if (d > 0) std::this_thread::sleep_for(std::chrono::microseconds(d));

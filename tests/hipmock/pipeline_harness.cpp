@@ -18,15 +18,20 @@
 #include <string>
 #include <thread>
 #include <unistd.h>
+#include <atomic>
 #include <vector>
 
 #include "gs_internal.h"
 
 namespace gs {
 
+// planted launch failure: the nth launch from the moment it is armed fails (0: disarmed)
+static std::atomic<int> g_launch_fault{0};
+
 // stand-in "kernel": p' = p + 1, m' = 2 m, v' = v + g_0, w = low 16 bits of (i + k)
 hipError_t launch_accum_adamw(const StepArgs &A, hipStream_t stream)
 {
+    if (g_launch_fault.load() > 0 && g_launch_fault.fetch_sub(1) == 1) return hipErrorUnknown;
     StepArgs a = A;
     hipmock_enqueue(stream, [a] {
         for (int64_t i = a.begin; i < a.end; ++i) {
@@ -387,6 +392,90 @@ static void test_tier_failures(const std::string &dir)
     }
 }
 
+// HIP calls that fail in the middle of a layer: the status comes back (from the call, or from sync
+// for work done on the context's own threads), nothing hangs, everything can still be destroyed.
+static void test_hip_failures(const std::string &dir)
+{
+    Layer A(5000, 31);
+    const uint16_t *gt[1] = {A.g.data()};
+    float *h[3];
+    const std::vector<float> *src[3] = {&A.p0, &A.m0, &A.v0};
+    for (int a = 0; a < 3; ++a) {
+        h[a] = (float *)gs_pinned_alloc((size_t)A.n * 4);
+        memcpy(h[a], src[a]->data(), (size_t)A.n * 4);
+    }
+    // staged pipeline: a copy in the middle of the layer fails
+    {
+        gs_stream_ctx *ctx = nullptr;
+        CHECK(gs_stream_ctx_create(&ctx, 1000, 2) == GS_OK, "create staged");
+        hipmock_fail_nth("hipMemcpyAsync", 8);
+        CHECK(gs_stream_layer_step(ctx, h[0], h[1], h[2], A.w.data(), gt, 1, A.n, &HP, nullptr, nullptr) == GS_ERR_HIP,
+              "failed copy not reported");
+        hipmock_fail_nth(nullptr, 0);
+        CHECK(strstr(gs_last_hip_error(), "hipMemcpyAsync") != nullptr, "error text: '%s'", gs_last_hip_error());
+        CHECK(gs_stream_ctx_sync(ctx) == GS_OK, "sync after a failed enqueue");
+        CHECK(gs_stream_ctx_destroy(ctx) == GS_OK, "destroy after a failed enqueue");
+    }
+    // in place: the launch itself fails
+    {
+        gs_stream_ctx *ctx = nullptr;
+        CHECK(gs_stream_ctx_create_inplace(&ctx, 0) == GS_OK, "create in place");
+        gs::g_launch_fault.store(1);
+        CHECK(gs_stream_layer_step(ctx, h[0], h[1], h[2], A.w.data(), gt, 1, A.n, &HP, nullptr, nullptr) == GS_ERR_HIP,
+              "failed launch not reported");
+        gs::g_launch_fault.store(0);
+        CHECK(gs_stream_ctx_destroy(ctx) == GS_OK, "destroy after a failed launch");
+    }
+    // file tier: each of these fails on the reader thread, after the call has returned
+    struct Case {
+        const char *api;   // nullptr: the kernel launch
+        int nth;
+        int64_t n_host;
+    };
+    const Case cases[] = {{"hipLaunchHostFunc", 2, 0}, {"hipStreamWaitEvent", 1, 0}, {"hipStreamWaitEvent", 3, 0},
+                          {"hipEventRecord", 3, 0},    {nullptr, 1, 2048},           {nullptr, 3, 0}};
+    for (const Case &cs : cases) {
+        Files f(dir, "hipfail", A, cs.n_host, 0);
+        gs_tier_ctx *ctx = nullptr;
+        CHECK(gs_tier_ctx_create(&ctx, 1024, 2, 0) == GS_OK, "tier create");
+        gs_tier_layer d{h[0], h[1], h[2], cs.n_host, f.fd[0], f.fd[1], f.fd[2], 0, 0, 0};
+        // armed after the call's own event record, so that the failure falls on the reader thread
+        gs_status st = GS_OK;
+        if (cs.api && strcmp(cs.api, "hipEventRecord") == 0) {
+            hipmock_fail_nth(cs.api, cs.nth);      // 1st record: the call's; later ones: the reader's per chunk
+            st = gs_tier_layer_step(ctx, &d, A.w.data(), gt, 1, A.n, &HP, nullptr, nullptr);
+        } else {
+            if (cs.api) hipmock_fail_nth(cs.api, cs.nth);
+            else gs::g_launch_fault.store(cs.nth);
+            st = gs_tier_layer_step(ctx, &d, A.w.data(), gt, 1, A.n, &HP, nullptr, nullptr);
+        }
+        CHECK(st == GS_OK, "queueing failed (%s #%d)", cs.api ? cs.api : "launch", cs.nth);
+        CHECK(gs_tier_ctx_sync(ctx) == GS_ERR_HIP, "%s #%d failing on the reader thread was not reported", cs.api ? cs.api : "launch", cs.nth);
+        hipmock_fail_nth(nullptr, 0);
+        gs::g_launch_fault.store(0);
+        CHECK(gs_tier_ctx_error(ctx)[0] != 0, "no error text");
+        CHECK(gs_tier_layer_step(ctx, &d, A.w.data(), gt, 1, A.n, &HP, nullptr, nullptr) == GS_ERR_HIP, "failed context reused");
+        CHECK(gs_tier_ctx_destroy(ctx) == GS_ERR_HIP, "destroy after failure");
+    }
+    // the call's own event record fails: reported by the call, the context stays usable
+    {
+        Files f(dir, "hipfail2", A, 0, 0);
+        gs_tier_ctx *ctx = nullptr;
+        CHECK(gs_tier_ctx_create(&ctx, 1024, 2, 0) == GS_OK, "tier create");
+        gs_tier_layer d{nullptr, nullptr, nullptr, 0, f.fd[0], f.fd[1], f.fd[2], 0, 0, 0};
+        hipmock_fail_nth("hipEventRecord", 1);
+        CHECK(gs_tier_layer_step(ctx, &d, A.w.data(), gt, 1, A.n, &HP, nullptr, nullptr) == GS_ERR_HIP, "failed record not reported");
+        hipmock_fail_nth(nullptr, 0);
+        CHECK(gs_tier_layer_step(ctx, &d, A.w.data(), gt, 1, A.n, &HP, nullptr, nullptr) == GS_OK, "context unusable after a rejected call");
+        CHECK(gs_tier_ctx_sync(ctx) == GS_OK, "sync: %s", gs_tier_ctx_error(ctx));
+        bool ok[3];
+        std::vector<float> fp = f.load(0, 0, A.n, &ok[0]), fm = f.load(1, 0, A.n, &ok[1]), fv = f.load(2, 0, A.n, &ok[2]);
+        if (ok[0] && ok[1] && ok[2]) A.check(fp.data(), fm.data(), fv.data(), 0, A.n, 0, 1, "after a rejected call");
+        CHECK(gs_tier_ctx_destroy(ctx) == GS_OK, "destroy");
+    }
+    for (int a = 0; a < 3; ++a) gs_pinned_free(h[a]);
+}
+
 int main(int argc, char **argv)
 {
     if (argc < 2) {
@@ -407,6 +496,7 @@ int main(int argc, char **argv)
     test_tier(dir, 30000, 29999, 1024, 4);
     test_tier_direct_io(dir);
     test_tier_failures(dir);
+    test_hip_failures(dir);
     printf(g_fail ? "FAILED (%d)\n" : "PIPELINE OK\n", g_fail);
     return g_fail ? 1 : 0;
 }

@@ -5,8 +5,10 @@ a small stand-in for the HIP runtime (tests/hipmock: streams are real concurrent
 order them, copies are memcpy) and run under ThreadSanitizer.  The step kernel is replaced by a
 trivial element-wise stand-in, so this checks plumbing only: every element is staged, updated
 exactly once and written back to its host address or file offset; file-tier failures come back
-as GS_ERR_IO.  The mutants show that the harness notices a dropped event wait, a dropped slot
-hand-over or a wrong file offset.
+as GS_ERR_IO, and HIP calls that the stand-in makes fail in the middle of a layer (a copy, a launch,
+an event record or wait, a host-function enqueue) come back as GS_ERR_HIP without a hang or a leak.
+The mutants show that the harness notices a dropped event wait, a dropped slot hand-over, a wrong
+file offset, a lost failure status.
 """
 import os
 import shutil
@@ -95,6 +97,11 @@ MUTANTS = [
      "const int64_t f_lo = begin > L->n_host ? begin : L->n_host, f_hi = end;", "const int64_t f_lo = L->n_host, f_hi = end;"),
     ("bounce_offset_forgotten_on_write_back", "gs_tier.hip",
      "        j.pad = (int)pad;", "        j.pad = 0;"),
+    ("failed_chunk_still_queued_for_write_back", "gs_tier.hip",
+     '            t->fail(st, "enqueue of a file chunk failed", 0);\n            return;\n',
+     '            t->fail(st, "enqueue of a file chunk failed", 0);\n'),
+    ("failure_on_the_context_threads_dropped", "gs_tier.hip",
+     "            err = st;\n", "            (void)st;\n"),
     ("tier_kernel_ignores_producer", "gs_tier.hip",
      "    hipError_t we = hipStreamWaitEvent(c->s_comp, job.ev_producer, 0);", "    hipError_t we = hipSuccess;"),
     ("tier_sync_ignores_queued_layers", "gs_tier.hip",
