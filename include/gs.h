@@ -397,8 +397,9 @@ gs_status gs_tier_layer_step_range(gs_tier_ctx *ctx, const gs_tier_layer *L, uin
  * (the page cache counts as written; fsync is the caller's call). */
 gs_status gs_tier_ctx_sync(gs_tier_ctx *ctx);
 gs_status gs_tier_ctx_destroy(gs_tier_ctx *ctx); /* syncs, stops both threads, frees everything */
-/* Text of the context's first file-tier failure ("" if none), e.g. "pwrite(m): No space left on
- * device".  The pointer is valid until the calling thread's next call of this function. */
+/* Text of the context's first failure ("" if none), e.g. "pwrite(m): No space left on device", or,
+ * for a HIP call that failed on one of the context's threads, what was being done followed by the
+ * runtime's message (gs_last_hip_error is per thread and would not show it).  The pointer is valid until the calling thread's next call of this function. */
 const char *gs_tier_ctx_error(gs_tier_ctx *ctx);
 
 /* Page-locked host memory without power-of-two padding (Sec. 5 notes that a framework's

@@ -188,6 +188,17 @@ struct gs_tier_ctx {
     {
         return plain + ((size_t)slot * 3u + (size_t)which) * (size_t)bounce_elems;
     }
+    // a failed HIP call on one of the context's threads: keep the runtime's own text too (the
+    // per-thread text of gs_last_hip_error would stay behind on that thread)
+    void fail_hip(gs_status st, const char *what)
+    {
+        std::string text = what;
+        if (st == GS_ERR_HIP) {
+            text += ": ";
+            text += gs_last_hip_error();
+        }
+        fail(st, text.c_str(), 0);
+    }
     void fail(gs_status st, const char *what, int err_no)
     {
         std::lock_guard<std::mutex> g(mu);
@@ -480,7 +491,7 @@ static void run_layer(gs_tier_ctx *t, LayerJob &job)
         t->spare_events.push_back(job.ev_producer);   // the wait has captured the record: free for reuse
     }
     if (we != hipSuccess) {
-        t->fail(hip_fail(we, "hipStreamWaitEvent(producer)"), "hipStreamWaitEvent(producer)", 0);
+        t->fail_hip(hip_fail(we, "hipStreamWaitEvent(producer)"), "waiting for the producer stream failed");
         return;
     }
 
@@ -502,7 +513,7 @@ static void run_layer(gs_tier_ctx *t, LayerJob &job)
             ++hi;
             st = stream_range(c, A, L->h_p + b, L->h_m + b, L->h_v + b, b, e);
             if (st != GS_OK) {
-                t->fail(st, "enqueue of a host chunk failed", 0);
+                t->fail_hip(st, "enqueue of a host chunk failed");
                 return;
             }
             continue;
@@ -543,7 +554,7 @@ static void run_layer(gs_tier_ctx *t, LayerJob &job)
             if (he != hipSuccess) st = hip_fail(he, "hipLaunchHostFunc(chunk done)");
         }
         if (st != GS_OK) {
-            t->fail(st, "enqueue of a file chunk failed", 0);
+            t->fail_hip(st, "enqueue of a file chunk failed");
             return;
         }
         WriteJob j;
@@ -567,7 +578,7 @@ static void run_layer(gs_tier_ctx *t, LayerJob &job)
 static void reader_main(gs_tier_ctx *t)
 {
     const hipError_t de = hipSetDevice(t->device);
-    if (de != hipSuccess) t->fail(hip_fail(de, "hipSetDevice"), "hipSetDevice (reader thread)", 0);
+    if (de != hipSuccess) t->fail_hip(hip_fail(de, "hipSetDevice"), "the reader thread could not select the device");
     for (;;) {
         LayerJob job;
         bool skip;

@@ -98,8 +98,8 @@ MUTANTS = [
     ("bounce_offset_forgotten_on_write_back", "gs_tier.hip",
      "        j.pad = (int)pad;", "        j.pad = 0;"),
     ("failed_chunk_still_queued_for_write_back", "gs_tier.hip",
-     '            t->fail(st, "enqueue of a file chunk failed", 0);\n            return;\n',
-     '            t->fail(st, "enqueue of a file chunk failed", 0);\n'),
+     '            t->fail_hip(st, "enqueue of a file chunk failed");\n            return;\n',
+     '            t->fail_hip(st, "enqueue of a file chunk failed");\n'),
     ("failure_on_the_context_threads_dropped", "gs_tier.hip",
      "            err = st;\n", "            (void)st;\n"),
     ("tier_kernel_ignores_producer", "gs_tier.hip",
