@@ -383,7 +383,9 @@ def gs_tier_layer_step(ctx, h_p, h_m, h_v, n_host: int, fds, offsets, d_w_bf16, 
                        d_sqnorm=None, producer_stream=None, check: bool = True, k: int | None = None,
                        layer: "gs_tier_layer | None" = None) -> int:
     """fds = (fd_p, fd_m, fd_v) and offsets = (off_p, off_m, off_v) in bytes; `layer` passes a
-    ready-made descriptor (or None with check=False to exercise the rejection)."""
+    ready-made descriptor (or None with check=False to exercise the rejection).  The call queues
+    the layer and returns: keep the tensors alive and untouched until gs_tier_ctx_sync, which also
+    reports I/O failures."""
     tab, kk = _table(d_grads) if d_grads is not None else (None, 0)
     for j, g in enumerate(d_grads or ()):
         _need(g, n, 2, f"d_grads[{j}]")
