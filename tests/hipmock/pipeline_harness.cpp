@@ -336,6 +336,39 @@ static void test_tier_direct_io(const std::string &dir)
     for (int a = 0; a < 3; ++a) gs_pinned_free(host[a]);
 }
 
+// The call only queues the layer: with the gradients still 300 ms away on the producer stream (so that
+// no kernel can finish and no bounce slot can be handed back) it must return long before that.
+static void test_tier_call_does_not_wait(const std::string &dir)
+{
+    Layer A(6000, 41);
+    Files f(dir, "nowait", A, 0, 0);
+    gs_tier_ctx *ctx = nullptr;
+    CHECK(gs_tier_ctx_create(&ctx, 1024, 2, 0) == GS_OK, "tier create");
+    hipStream_t producer = nullptr;
+    CHECK(hipStreamCreateWithFlags(&producer, hipStreamNonBlocking) == hipSuccess, "producer stream");
+    std::vector<uint16_t> *g = &A.g;
+    std::vector<uint16_t> real = *g;
+    std::fill(g->begin(), g->end(), (uint16_t)0x7777);
+    hipmock_enqueue(producer, [g, real] {
+        std::this_thread::sleep_for(std::chrono::milliseconds(300));
+        *g = real;
+    });
+    const uint16_t *gt[1] = {g->data()};
+    gs_tier_layer d{nullptr, nullptr, nullptr, 0, f.fd[0], f.fd[1], f.fd[2], 0, 0, 0};
+    const auto t0 = std::chrono::steady_clock::now();
+    CHECK(gs_tier_layer_step(ctx, &d, A.w.data(), gt, 1, A.n, &HP, nullptr, producer) == GS_OK, "tier layer step");
+    const double ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    CHECK(ms < 150.0, "the call took %.1f ms: it waited for the pipeline", ms);
+    CHECK(gs_tier_ctx_sync(ctx) == GS_OK, "sync: %s", gs_tier_ctx_error(ctx));
+    bool ok[3];
+    std::vector<float> fp = f.load(0, 0, A.n, &ok[0]), fm = f.load(1, 0, A.n, &ok[1]), fv = f.load(2, 0, A.n, &ok[2]);
+    CHECK(ok[0] && ok[1] && ok[2], "file framing damaged");
+    if (ok[0] && ok[1] && ok[2]) A.check(fp.data(), fm.data(), fv.data(), 0, A.n, 0, 1, "queued layer");
+    A.check_w(1, "queued layer");
+    CHECK(gs_tier_ctx_destroy(ctx) == GS_OK, "destroy");
+    CHECK(hipStreamDestroy(producer) == hipSuccess, "producer stream destroy");
+}
+
 static void test_tier_failures(const std::string &dir)
 {
     Layer A(5000, 21);
@@ -496,6 +529,7 @@ int main(int argc, char **argv)
     test_tier(dir, 5000, 1, 100000, 2);
     test_tier(dir, 30000, 29999, 1024, 4);
     test_tier_direct_io(dir);
+    test_tier_call_does_not_wait(dir);
     test_tier_failures(dir);
     test_hip_failures(dir);
     printf(g_fail ? "FAILED (%d)\n" : "PIPELINE OK\n", g_fail);

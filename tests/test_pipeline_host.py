@@ -102,6 +102,11 @@ MUTANTS = [
      '            t->fail_hip(st, "enqueue of a file chunk failed");\n'),
     ("failure_on_the_context_threads_dropped", "gs_tier.hip",
      "            err = st;\n", "            (void)st;\n"),
+    ("tier_call_waits_for_the_reader", "gs_tier.hip",
+     "        t->layers.push_back(job);\n    }\n    t->cv.notify_all();\n    return GS_OK;\n",
+     "        t->layers.push_back(job);\n    }\n    t->cv.notify_all();\n"
+     "    {\n        std::unique_lock<std::mutex> lk(t->mu);\n"
+     "        t->cv.wait(lk, [&] { return t->layers.empty() && !t->reader_active; });\n    }\n    return GS_OK;\n"),
     ("tier_kernel_ignores_producer", "gs_tier.hip",
      "    hipError_t we = hipStreamWaitEvent(c->s_comp, job.ev_producer, 0);", "    hipError_t we = hipSuccess;"),
     ("tier_sync_ignores_queued_layers", "gs_tier.hip",
