@@ -1063,6 +1063,60 @@ def test_workspace_size_picks_the_shape_not_the_result():
         del acc, ws
 
 
+# ----------------------------------------------------------------------------- seeded random sweep
+def test_random_sweep_of_sizes_ranges_k_and_hparams():
+    """48 seeded cases: n, k, the range, the step count and the hyper-parameters drawn at random; each
+    case runs the norm, then one of the four ways to take the step (fused in place, out of place,
+    staged through the fp32 sum, accumulate-as-you-go + step) on [begin,end), and must match the
+    oracle to the stated bar, leave everything outside the range untouched, and agree bit for bit
+    with the fused in-place result."""
+    rng = np.random.default_rng(20251217)
+    for case_no in range(48):
+        n = int(rng.choice([1, 3, 255, 256, 257, 511, 513, 1023, 4097, 70_001, 200_003]))
+        k = int(rng.choice([1, 2, 3, 6, 7, 8, 9, 14, 15, 16, 31, 32]))
+        begin = int(rng.integers(0, n))
+        end = int(rng.integers(begin, n + 1))
+        hp = gs.HParams(lr=float(rng.choice([0.0, 1e-5, 3e-4, 1e-2])), beta1=float(rng.choice([0.0, 0.9, 0.95])),
+                        beta2=float(rng.choice([0.0, 0.98, 0.999])), eps=float(rng.choice([1e-8, 1e-6])),
+                        weight_decay=float(rng.choice([0.0, 0.01, 0.1])),
+                        max_grad_norm=float(rng.choice([0.0, 0.05, 1.0, 100.0])), step=int(rng.integers(1, 5000)))
+        tag = f"case {case_no}: n={n} k={k} [{begin},{end}) {hp}"
+        case = DeviceCase(n, k, seed=1000 + case_no, sigma=float(rng.choice([1e-4, 1e-3, 3e-2])))
+        S = case.gpu_sqnorm()
+        So = O.grad_sqnorm(case.h_g)
+        assert abs(S - So) <= 1e-12 * max(So, 1e-300), tag
+        c = O.clip_coef(So, hp.max_grad_norm)
+        assert gs.gs_clip_coefficient(S, hp.max_grad_norm) == c, tag
+        want = case.oracle_step(hp, c, begin, end)
+        fused = case.clone_states()
+        gs.gs_accum_adamw(*fused, case.grads, begin, end, hp, case.sq)
+        torch.cuda.synchronize()
+        compare_states(fused, want, tag)
+        for a, h in zip(fused[:3], (case.h_p, case.h_m, case.h_v)):            # outside the range: untouched
+            got = np_f32(a)
+            assert np.array_equal(got[:begin], h[:begin]) and np.array_equal(got[end:], h[end:]), tag
+        assert not np_bf16(fused[3])[:begin].any() and not np_bf16(fused[3])[end:].any(), tag
+        how = case_no % 3
+        other = case.clone_states()
+        if how == 0:        # out of place into buffers that start as copies
+            src = case.clone_states()
+            gs.gs_accum_adamw_oop(src[0], src[1], src[2], other[0], other[1], other[2], other[3], case.grads, begin, end, hp,
+                                  case.sq)
+        elif how == 1:      # staged through the fp32 sum
+            acc = torch.full((n,), float("nan"), dtype=torch.float32, device=DEV)
+            sq2 = torch.zeros(1, dtype=torch.float64, device=DEV)
+            gs.gs_grad_accum_sqnorm(case.grads, begin, end, acc, sq2, case.ws)
+            gs.gs_adamw_from_acc(*other, acc, begin, end, hp, case.sq)
+        else:               # one gs_accum_add per micro-batch, then the step from the buffer
+            acc = torch.full((n,), float("nan"), dtype=torch.float32, device=DEV)
+            for j in range(k):
+                gs.gs_accum_add(acc, case.grads[j], j == 0, begin, end)
+            gs.gs_adamw_from_acc(*other, acc, begin, end, hp, case.sq)
+        torch.cuda.synchronize()
+        for a, b, nm in zip(fused, other, "pmvw"):
+            assert torch.equal(a, b), f"{tag}: way {how} differs from the fused step in {nm}"
+
+
 # ----------------------------------------------------------------------------- the ABI from plain C
 def test_c_program_drives_the_abi_without_python_or_torch():
     """tests/c_abi/step_demo.c (C99, built by the package's build step) allocates with the HIP
