@@ -1117,6 +1117,70 @@ def test_random_sweep_of_sizes_ranges_k_and_hparams():
             assert torch.equal(a, b), f"{tag}: way {how} differs from the fused step in {nm}"
 
 
+def test_random_sweep_of_host_resident_and_tiered_layouts(tmp_path):
+    """24 seeded cases over the host-resident paths: the layer size, k, the chunk size, the slot count,
+    the host share and a range split in three pieces queued in random order are drawn at random;
+    staged, in-place and tiered runs must all leave bit for bit what the resident step leaves."""
+    rng = np.random.default_rng(4242)
+    for case_no in range(24):
+        n = int(rng.choice([5, 1023, 4097, 70_001, 300_007]))
+        k = int(rng.choice([1, 2, 8, 15, 16]))
+        chunk = int(rng.choice([1, 7, 1000, 4096, 65_537, 1 << 20])) if n < 5000 else int(rng.choice([1000, 4096, 65_537, 1 << 20]))
+        slots = int(rng.integers(2, 5))
+        cuts = sorted(int(c) for c in rng.integers(0, n + 1, size=2))
+        pieces = [(0, cuts[0]), (cuts[0], cuts[1]), (cuts[1], n)]
+        order = [int(i) for i in rng.permutation(3)]
+        tag = f"case {case_no}: n={n} k={k} chunk={chunk} slots={slots} pieces={pieces} order={order}"
+        case = DeviceCase(n, k, seed=2000 + case_no)
+        case.gpu_sqnorm()
+        ref = case.clone_states()
+        gs.gs_accum_adamw(*ref, case.grads, 0, n, HP, case.sq)
+        torch.cuda.synchronize()
+        want = [np_f32(r) for r in ref[:3]]
+        init = [np_f32(x) for x in (case.p, case.m, case.v)]
+        mode = case_no % 3
+        bufs = [gs.pinned_f32(n) for _ in range(3)]
+        w = torch.zeros_like(case.w)
+        try:
+            for (tn, _), a in zip(bufs, init):
+                tn.copy_(torch.from_numpy(a))
+            if mode < 2:
+                ctx = gs.gs_stream_ctx_create(chunk, slots) if mode == 0 else gs.gs_stream_ctx_create_inplace(0)
+                try:
+                    for i in order:
+                        b, e = pieces[i]
+                        gs.gs_stream_layer_step_range(ctx, bufs[0][1], bufs[1][1], bufs[2][1], w, case.grads, b, e, HP, case.sq)
+                    gs.gs_stream_ctx_sync(ctx)
+                finally:
+                    gs.gs_stream_ctx_destroy(ctx)
+                for (tn, _), wv in zip(bufs, want):
+                    assert np.array_equal(tn.numpy(), wv), tag
+            else:
+                n_host = int(rng.integers(0, n + 1))
+                header = int(rng.choice([0, 4, 24]))
+                fds, paths = _write_states(tmp_path, f"R{case_no}", init, n_host, header)
+                ctx = gs.gs_tier_ctx_create(chunk, slots, 0)
+                try:
+                    for i in order:
+                        b, e = pieces[i]
+                        gs.gs_tier_layer_step_range(ctx, bufs[0][1], bufs[1][1], bufs[2][1], n_host, fds, (header,) * 3, w,
+                                                    case.grads, n, b, e, HP, case.sq)
+                    gs.gs_tier_ctx_sync(ctx)
+                    assert gs.gs_tier_ctx_error(ctx) == "", tag
+                finally:
+                    gs.gs_tier_ctx_destroy(ctx)
+                    for fd in fds:
+                        os.close(fd)
+                tail = _read_states(paths, n - n_host, header)
+                for (tn, _), fl, wv in zip(bufs, tail, want):
+                    assert np.array_equal(tn[:n_host].numpy(), wv[:n_host]), tag + f" n_host={n_host}"
+                    assert np.array_equal(fl, wv[n_host:]), tag + f" n_host={n_host}"
+            assert torch.equal(w, ref[3]), tag
+        finally:
+            for _, ptr in bufs:
+                gs.gs_pinned_free(ptr)
+
+
 # ----------------------------------------------------------------------------- the ABI from plain C
 def test_c_program_drives_the_abi_without_python_or_torch():
     """tests/c_abi/step_demo.c (C99, built by the package's build step) allocates with the HIP
