@@ -52,7 +52,8 @@ typedef enum {
     GS_ERR_WORKSPACE = -2,   /* workspace missing or smaller than gs_sqnorm_workspace_bytes() */
     GS_ERR_HIP = -3,         /* a HIP runtime call failed; see gs_last_hip_error() */
     GS_ERR_NOMEM = -4,       /* host or device allocation failed */
-    GS_ERR_IO = -5           /* a file read or write of the file tier failed; see gs_tier_ctx_error() */
+    GS_ERR_IO = -5,          /* a file read or write of the file tier failed; see gs_tier_ctx_error() */
+    GS_ERR_TOO_LARGE = -6    /* range longer than the fixed scratch array of gs_grad_sqnorm_noalloc covers */
 } gs_status;
 
 /* Largest number of micro-batch gradient buffers one call accepts. */
@@ -111,6 +112,26 @@ size_t gs_sqnorm_workspace_bytes_for(int64_t range_elems);
 gs_status gs_grad_sqnorm(const uint16_t *const *grads, int k, int64_t begin, int64_t end,
                          double *d_sqnorm, int accumulate,
                          void *d_workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * gs_grad_sqnorm for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels,
+ * same arguments minus the workspace, same value bit for bit as gs_grad_sqnorm with a workspace of
+ * gs_sqnorm_workspace_bytes() bytes; the workgroup partials live in a fixed device array of the
+ * library's own (2 098 176 bytes, held by every GPU the library runs on until the process ends).
+ * The call makes no hipMalloc/hipFree and uses no allocating library routine.
+ *   - end - begin may be at most GS_NOALLOC_MAX_ELEMS; a longer range is GS_ERR_TOO_LARGE and
+ *     nothing is enqueued (split it and accumulate).
+ *   - The first call on a device looks up that device's copy of the array (one runtime query,
+ *     kept afterwards); make that call outside stream capture.
+ *   - All calls on one GPU share the one array, which keeps the last call's partials: nothing in
+ *     it needs clearing (each launch overwrites what it later reads), but calls that overlap in
+ *     time on one GPU -- different streams, different host threads -- race on it.  Order them on
+ *     one stream, or use gs_grad_sqnorm with a workspace per stream.
+ */
+#define GS_NOALLOC_MAX_ELEMS ((int64_t)1 << 33)
+gs_status gs_grad_sqnorm_noalloc(const uint16_t *const *grads, int k, int64_t begin, int64_t end,
+                                 double *d_sqnorm, int accumulate, void *stream);
 
 /* ------------------------------------------------------------------------------------------
  * Fused accumulate + clip + AdamW + bf16 emit (Sec. 2.1 gradient accumulation in full

@@ -339,6 +339,7 @@ const char *gs_strerror(gs_status s)
     case GS_ERR_HIP: return "HIP runtime error";
     case GS_ERR_NOMEM: return "out of memory";
     case GS_ERR_IO: return "file read or write failed";
+    case GS_ERR_TOO_LARGE: return "range longer than the no-allocation entry point's fixed scratch array covers";
     }
     return "unknown status";
 }

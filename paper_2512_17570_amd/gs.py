@@ -23,6 +23,8 @@ GS_ERR_WORKSPACE = -2
 GS_ERR_HIP = -3
 GS_ERR_NOMEM = -4
 GS_ERR_IO = -5
+GS_ERR_TOO_LARGE = -6
+GS_NOALLOC_MAX_ELEMS = 1 << 33
 GS_MAX_K = 32
 
 if not os.path.exists(LIB_PATH):
@@ -69,6 +71,8 @@ _lib.gs_sqnorm_workspace_bytes_for.argtypes = [_i64]
 _lib.gs_sqnorm_workspace_bytes_for.restype = ctypes.c_size_t
 _lib.gs_grad_sqnorm.argtypes = [_pp, ctypes.c_int, _i64, _i64, _vp, ctypes.c_int, _vp, ctypes.c_size_t, _vp]
 _lib.gs_grad_sqnorm.restype = ctypes.c_int
+_lib.gs_grad_sqnorm_noalloc.argtypes = [_pp, ctypes.c_int, _i64, _i64, _vp, ctypes.c_int, _vp]
+_lib.gs_grad_sqnorm_noalloc.restype = ctypes.c_int
 _lib.gs_accum_adamw.argtypes = [_vp, _vp, _vp, _vp, _pp, ctypes.c_int, _i64, _i64,
                                 ctypes.POINTER(gs_adamw_hparams), _vp, _vp]
 _lib.gs_accum_adamw.restype = ctypes.c_int
@@ -193,6 +197,16 @@ def gs_grad_sqnorm(grads, begin: int, end: int, d_sqnorm, d_workspace, workspace
     st = _lib.gs_grad_sqnorm(tab, kk if k is None else k, begin, end, _addr(d_sqnorm), int(bool(accumulate)),
                              _addr(d_workspace), workspace_bytes, _stream(stream))
     return _check(st, "gs_grad_sqnorm", check)
+
+
+def gs_grad_sqnorm_noalloc(grads, begin: int, end: int, d_sqnorm, accumulate: bool = False, stream=None,
+                           check: bool = True, k: int | None = None) -> int:
+    tab, kk = _table(grads) if grads is not None else (None, 0)
+    for j, g in enumerate(grads or ()):
+        _need(g, end, 2, f"grads[{j}]")
+    st = _lib.gs_grad_sqnorm_noalloc(tab, kk if k is None else k, begin, end, _addr(d_sqnorm), int(bool(accumulate)),
+                                     _stream(stream))
+    return _check(st, "gs_grad_sqnorm_noalloc", check)
 
 
 def gs_accum_adamw(p, m, v, w_bf16, grads, begin: int, end: int, hp, d_sqnorm=None, stream=None,

@@ -114,6 +114,22 @@ def test_grad_sqnorm_empty_accumulate_is_noop():
     assert _sqnorm(begin=7, end=7, accumulate=True) == gs.GS_OK
 
 
+def test_grad_sqnorm_noalloc_rejects_without_gpu():
+    ok = dict(grads=[FAKE], begin=0, end=100, d_sqnorm=FAKE, accumulate=False, stream=0, check=False)
+    for kw, want in ((dict(grads=None, k=1), gs.GS_ERR_INVALID_ARG), (dict(grads=[FAKE] * 33), gs.GS_ERR_INVALID_ARG),
+                     (dict(grads=[FAKE + 6]), gs.GS_ERR_INVALID_ARG), (dict(begin=-3), gs.GS_ERR_INVALID_ARG),
+                     (dict(begin=5, end=4), gs.GS_ERR_INVALID_ARG), (dict(d_sqnorm=None), gs.GS_ERR_INVALID_ARG),
+                     (dict(d_sqnorm=FAKE + 4), gs.GS_ERR_INVALID_ARG),
+                     (dict(end=gs.GS_NOALLOC_MAX_ELEMS + 1), gs.GS_ERR_TOO_LARGE),
+                     (dict(begin=7, end=8 + gs.GS_NOALLOC_MAX_ELEMS), gs.GS_ERR_TOO_LARGE)):
+        assert gs.gs_grad_sqnorm_noalloc(**{**ok, **kw}) == want, kw
+    assert gs.gs_grad_sqnorm_noalloc(**{**ok, "begin": 7, "end": 7, "accumulate": True}) == gs.GS_OK
+    assert gs.gs_strerror(gs.GS_ERR_TOO_LARGE) not in ("ok", "unknown status")
+    hdr = open(HEADER).read()
+    assert gs.GS_NOALLOC_MAX_ELEMS == 1 << int(re.search(r"#define\s+GS_NOALLOC_MAX_ELEMS\s+\(\(int64_t\)1\s*<<\s*(\d+)\)", hdr).group(1))
+    assert gs.GS_ERR_TOO_LARGE == int(re.search(r"GS_ERR_TOO_LARGE\s*=\s*(-\d+)", hdr).group(1))
+
+
 def test_stream_api_rejects_without_gpu():
     st, ctx = gs.gs_stream_ctx_create_inplace(-1, check=False)
     assert st == gs.GS_ERR_INVALID_ARG and not ctx
