@@ -42,25 +42,22 @@ def build(verbose: bool = True, extra_flags=(), out: str | None = None) -> str:
     return out
 
 
-C_DEMO = os.path.join(PKG, "gs_c_demo")
+PROBE_LIB = os.path.join(PKG, "libgs_mixprobe.so")
 
 
-def build_c_demo(verbose: bool = True) -> str:
-    """The plain-C program that drives the library through its C ABI (tests/c_abi/step_demo.c, C99,
-    gcc): HIP runtime C API for memory, libgs.so for the step, the C oracle for the expected values.
-    A test program; the GPU tests run it."""
-    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
-    cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-Wextra", "-Wno-unused-parameter", "-ffp-contract=off",
-           "-I", os.path.join(rocm, "include"), "-I", os.path.join(ROOT, "include"),
-           os.path.join(ROOT, "tests", "c_abi", "step_demo.c"), os.path.join(ROOT, "oracle", "gs_oracle.c"),
-           "-L", PKG, "-lgs", "-L", os.path.join(rocm, "lib"), "-lamdhip64", "-lm",
-           "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", C_DEMO]
+def build_probe(verbose: bool = True) -> str:
+    """The stream-mix probe bench.py times next to the step kernel (probe/gs_mixprobe.hip): its own
+    shared library, so that libgs.so holds the product path only."""
+    cmd = [HIPCC, *FLAGS, os.path.join(PKG, "probe", "gs_mixprobe.hip"), "-o", PROBE_LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
-    return C_DEMO
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        sys.stderr.write(r.stderr)
+        raise RuntimeError("hipcc failed (mix probe)")
+    return PROBE_LIB
 
 
 if __name__ == "__main__":
     build()
-    build_c_demo()
+    build_probe()

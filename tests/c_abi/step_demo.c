@@ -2,10 +2,14 @@
  * The C boundary used from plain C, without Python or PyTorch: device memory and copies come from
  * the HIP runtime's C API, the step from libgs.so, the expected values from the CPU oracle linked
  * into this test program.  One small layer, device-resident: squared norm accumulated over two
- * ranges, then the fused step over the range split in two at an unaligned point.  Prints its
- * stages as it goes (unbuffered) and "C ABI OK", and exits 0 when everything matches bit for bit.
+ * ranges, then the fused step over the range split in two at an unaligned point.  With the
+ * argument --host-resident it goes on to the host-resident step on pinned memory: in place on a
+ * stream confined to a sixteenth of the compute units, then staged through device slots, both
+ * with the null stream as the producer stream.  Prints its stages as it goes (unbuffered) and
+ * "C ABI OK", and exits 0 when everything matches bit for bit.
  *
- * Built by the package's build step (gcc, C99); run by a GPU test.
+ * Built by tests/c_abi/build_demo.py (gcc, C99) and run by a GPU test; the same source is also
+ * built against the host-only HIP stand-in (tests/hipmock) and run on the CPU.
  */
 #define __HIP_PLATFORM_AMD__ 1
 #include <hip/hip_runtime_api.h>
@@ -58,9 +62,43 @@ static int same(const void *a, const void *b, size_t bytes, const char *what)
     return 1;
 }
 
-int main(void)
+/* one host-resident pass over pinned copies of the states; returns 1 if it matches the oracle */
+static int host_resident_pass(gs_stream_ctx *ctx, const char *what, int64_t n, const float *p, const float *m,
+                              const float *v, const float *ep, const float *em, const float *ev, const uint16_t *ew,
+                              const uint16_t *const *gt_dev, int k, const gs_adamw_hparams *hp, const double *d_sq,
+                              uint16_t *d_w, uint16_t *rw)
+{
+    const size_t f4 = (size_t)n * 4, b2 = (size_t)n * 2;
+    float *hp_ = gs_pinned_alloc(f4), *hm_ = gs_pinned_alloc(f4), *hv_ = gs_pinned_alloc(f4);
+    if (!hp_ || !hm_ || !hv_) {
+        printf("gs_pinned_alloc failed: %s\n", gs_last_hip_error());
+        return 0;
+    }
+    memcpy(hp_, p, f4); memcpy(hm_, m, f4); memcpy(hv_, v, f4);
+    if (hipMemset(d_w, 0, b2) != hipSuccess) return 0;
+    printf("stage: %s: enqueue\n", what);
+    gs_status st = gs_stream_layer_step(ctx, hp_, hm_, hv_, d_w, gt_dev, k, n, hp, d_sq, NULL);
+    if (st != GS_OK) {
+        printf("gs_stream_layer_step -> %s (%s)\n", gs_strerror(st), gs_last_hip_error());
+        return 0;
+    }
+    printf("stage: %s: sync\n", what);
+    st = gs_stream_ctx_sync(ctx);
+    if (st != GS_OK) {
+        printf("gs_stream_ctx_sync -> %s (%s)\n", gs_strerror(st), gs_last_hip_error());
+        return 0;
+    }
+    printf("stage: %s: compare\n", what);
+    if (hipMemcpy(rw, d_w, b2, hipMemcpyDeviceToHost) != hipSuccess) return 0;
+    int ok = same(hp_, ep, f4, what) & same(hm_, em, f4, what) & same(hv_, ev, f4, what) & same(rw, ew, b2, what);
+    gs_pinned_free(hp_); gs_pinned_free(hm_); gs_pinned_free(hv_);
+    return ok;
+}
+
+int main(int argc, char **argv)
 {
     enum { K = 3 };
+    const int host_resident = argc > 1 && strcmp(argv[1], "--host-resident") == 0;
     setvbuf(stdout, NULL, _IONBF, 0);
     printf("stage: inputs and oracle\n");
     const int64_t n = 512 * 37 + 11, split = 7001;
@@ -131,6 +169,21 @@ int main(void)
     if (gs_accum_adamw(d_p, d_m, d_v, d_w, gt_dev, 0, 0, n, &hp, d_sq, NULL) != GS_ERR_INVALID_ARG) {
         printf("MISMATCH: k = 0 accepted\n");
         ok = 0;
+    }
+    if (host_resident) {
+        /* the norm of the whole layer is in d_sq; the null stream is the producer stream */
+        int dev = 0, cus = 0;
+        HIP(hipGetDevice(&dev));
+        HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        gs_stream_ctx *ctx = NULL;
+        printf("stage: in-place context on %d of %d compute units\n", (cus + 15) / 16, cus);
+        GS(gs_stream_ctx_create_inplace(&ctx, (cus + 15) / 16));
+        ok &= host_resident_pass(ctx, "host-resident in place", n, p, m, v, ep, em, ev, ew, gt_dev, K, &hp, d_sq, d_w, rw);
+        GS(gs_stream_ctx_destroy(ctx));
+        printf("stage: staged context\n");
+        GS(gs_stream_ctx_create(&ctx, 4099, 3));
+        ok &= host_resident_pass(ctx, "host-resident staged", n, p, m, v, ep, em, ev, ew, gt_dev, K, &hp, d_sq, d_w, rw);
+        GS(gs_stream_ctx_destroy(ctx));
     }
     printf(ok ? "C ABI OK: n=%lld k=%d S=%.9e\n" : "C ABI FAILED: n=%lld k=%d S=%.9e\n", (long long)n, K, S);
     return ok ? 0 : 1;

@@ -3,7 +3,9 @@
  * staging slots) be built with g++ and run under ThreadSanitizer without a GPU.
  *
  * Streams are real FIFO queues, each drained by its own thread; events complete when the stream
- * reaches them; copies are memcpy tasks.  Because every stream runs concurrently, an ordering
+ * reaches them; copies are memcpy tasks.  The null stream runs its work in place unless
+ * HIPMOCK_LEGACY_NULL is set in the environment: then it is a queue with HIP's legacy ordering
+ * against blocking streams (see hipmock.cpp).  Because every stream runs concurrently, an ordering
  * that the pipeline forgets to express with an event shows up as a data race on the staging
  * memory (ThreadSanitizer) or as a wrong result. */
 #ifndef HIPMOCK_RUNTIME_API_H
@@ -39,6 +41,7 @@ hipError_t hipStreamCreateWithFlags(hipStream_t *s, unsigned flags);
 hipError_t hipExtStreamCreateWithCUMask(hipStream_t *s, uint32_t words, const uint32_t *mask);
 hipError_t hipStreamDestroy(hipStream_t s);
 hipError_t hipStreamSynchronize(hipStream_t s);
+hipError_t hipDeviceSynchronize(void);
 hipError_t hipStreamWaitEvent(hipStream_t s, hipEvent_t e, unsigned flags);
 hipError_t hipEventCreateWithFlags(hipEvent_t *e, unsigned flags);
 hipError_t hipEventDestroy(hipEvent_t e);
@@ -58,6 +61,8 @@ hipError_t hipPointerGetAttributes(hipPointerAttribute_t *attr, const void *ptr)
 typedef void (*hipHostFn_t)(void *userData);
 hipError_t hipLaunchHostFunc(hipStream_t s, hipHostFn_t fn, void *userData);
 hipError_t hipMemcpyAsync(void *dst, const void *src, size_t bytes, hipMemcpyKind kind, hipStream_t s);
+hipError_t hipMemcpy(void *dst, const void *src, size_t bytes, hipMemcpyKind kind);
+hipError_t hipMemset(void *dst, int value, size_t bytes);
 
 #ifdef __cplusplus
 }

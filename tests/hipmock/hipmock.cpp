@@ -8,9 +8,12 @@
 #include <cstring>
 #include <deque>
 #include <map>
+#include <memory>
 #include <mutex>
+#include <set>
 #include <string>
 #include <thread>
+#include <vector>
 
 struct hipmock_stream {
     std::mutex mu;
@@ -90,13 +93,85 @@ static bool fault_now(const char *api)
     return --g_fault_countdown == 0;
 }
 
+// ---- legacy null-stream semantics (HIPMOCK_LEGACY_NULL=1 in the environment) --------------------
+// As in HIP's default ("legacy") mode: the null stream is a queue of its own; work enqueued on it
+// starts only after everything enqueued earlier on every BLOCKING stream (one created without
+// hipStreamNonBlocking, or by hipExtStreamCreateWithCUMask) has finished, and work enqueued on a
+// blocking stream starts only after everything enqueued earlier on the null stream.  Non-blocking
+// streams take no part.  Without the variable the null stream runs its work in place, at the call.
+struct hipmock_token {
+    std::mutex mu;
+    std::condition_variable cv;
+    bool done = false;
+    void set()
+    {
+        {
+            std::lock_guard<std::mutex> g(mu);
+            done = true;
+        }
+        cv.notify_all();
+    }
+    void wait()
+    {
+        std::unique_lock<std::mutex> lk(mu);
+        cv.wait(lk, [&] { return done; });
+    }
+};
+
+static bool legacy_null()
+{
+    static const bool on = getenv("HIPMOCK_LEGACY_NULL") != nullptr;
+    return on;
+}
+static std::mutex g_streams_mu;
+static std::set<hipmock_stream *> g_all_streams, g_blocking_streams;
+static hipmock_stream *null_stream()
+{
+    static hipmock_stream *n = new hipmock_stream();   // lives until the process ends
+    return n;
+}
+
 void hipmock_enqueue(hipStream_t s, std::function<void()> fn)
 {
-    if (!s) {
-        fn();   // the null stream runs in place
+    if (!legacy_null()) {
+        if (!s) {
+            fn();   // the null stream runs in place
+            return;
+        }
+        s->push(std::move(fn));
         return;
     }
-    s->push(std::move(fn));
+    if (!s) {
+        std::vector<std::shared_ptr<hipmock_token>> toks;
+        {
+            std::lock_guard<std::mutex> g(g_streams_mu);
+            for (hipmock_stream *b : g_blocking_streams) {
+                auto t = std::make_shared<hipmock_token>();
+                b->push([t] { t->set(); });
+                toks.push_back(t);
+            }
+        }
+        null_stream()->push([toks, fn] {
+            for (auto &t : toks) t->wait();
+            fn();
+        });
+        return;
+    }
+    bool blocking;
+    {
+        std::lock_guard<std::mutex> g(g_streams_mu);
+        blocking = g_blocking_streams.count(s) != 0;
+    }
+    if (!blocking) {
+        s->push(std::move(fn));
+        return;
+    }
+    auto t = std::make_shared<hipmock_token>();
+    null_stream()->push([t] { t->set(); });
+    s->push([t, fn] {
+        t->wait();
+        fn();
+    });
 }
 
 extern "C" {
@@ -165,12 +240,66 @@ hipError_t hipPointerGetAttributes(hipPointerAttribute_t *attr, const void *ptr)
     return hipSuccess;
 }
 
-hipError_t hipStreamCreateWithFlags(hipStream_t *s, unsigned) { *s = new hipmock_stream(); return hipSuccess; }
-hipError_t hipExtStreamCreateWithCUMask(hipStream_t *s, uint32_t, const uint32_t *) { *s = new hipmock_stream(); return hipSuccess; }
-hipError_t hipStreamDestroy(hipStream_t s) { delete s; return hipSuccess; }
+static hipmock_stream *new_stream(bool blocking)
+{
+    hipmock_stream *s = new hipmock_stream();
+    std::lock_guard<std::mutex> g(g_streams_mu);
+    g_all_streams.insert(s);
+    if (blocking) g_blocking_streams.insert(s);
+    return s;
+}
+hipError_t hipStreamCreateWithFlags(hipStream_t *s, unsigned flags)
+{
+    *s = new_stream(!(flags & hipStreamNonBlocking));
+    return hipSuccess;
+}
+// a CU-masked stream is a blocking stream, as in HIP (the call takes no flags)
+hipError_t hipExtStreamCreateWithCUMask(hipStream_t *s, uint32_t, const uint32_t *) { *s = new_stream(true); return hipSuccess; }
+hipError_t hipStreamDestroy(hipStream_t s)
+{
+    s->drain();
+    {
+        std::lock_guard<std::mutex> g(g_streams_mu);
+        g_all_streams.erase(s);
+        g_blocking_streams.erase(s);
+    }
+    delete s;
+    return hipSuccess;
+}
 hipError_t hipStreamSynchronize(hipStream_t s)
 {
-    if (s) s->drain();
+    if (s) {
+        s->drain();
+    } else if (legacy_null()) {
+        hipmock_enqueue(nullptr, [] {});
+        null_stream()->drain();
+    }
+    return hipSuccess;
+}
+hipError_t hipDeviceSynchronize(void)
+{
+    for (int pass = 0; pass < 2; ++pass) {
+        std::vector<hipmock_stream *> all;
+        {
+            std::lock_guard<std::mutex> g(g_streams_mu);
+            all.assign(g_all_streams.begin(), g_all_streams.end());
+        }
+        for (hipmock_stream *s : all) s->drain();
+        if (legacy_null()) null_stream()->drain();
+    }
+    return hipSuccess;
+}
+hipError_t hipMemset(void *dst, int value, size_t bytes)
+{
+    hipmock_enqueue(nullptr, [=] { memset(dst, value, bytes); });
+    if (legacy_null()) null_stream()->drain();
+    return hipSuccess;
+}
+hipError_t hipMemcpy(void *dst, const void *src, size_t bytes, hipMemcpyKind)
+{
+    // synchronous copy on the null stream
+    hipmock_enqueue(nullptr, [=] { memcpy(dst, src, bytes); });
+    if (legacy_null()) null_stream()->drain();
     return hipSuccess;
 }
 

@@ -72,6 +72,46 @@ def test_pipelines_under_address_and_undefined_behaviour_sanitizers(tmp_path, ts
     assert "ERROR: AddressSanitizer" not in r.stderr and "runtime error" not in r.stderr, r.stderr[-3000:]
 
 
+def _build_c_sequence(out_dir: str, tsan: bool) -> str:
+    """tests/c_abi/step_demo.c (the plain-C program over the C ABI) built against the HIP stand-in:
+    gcc for the C file and the C oracle, g++ for the library's host sources, the stand-in and the
+    scalar stand-ins for the kernel launchers."""
+    san = ["-fsanitize=thread", "-fno-omit-frame-pointer"] if tsan else []
+    inc = ["-I", MOCK, "-I", os.path.join(ROOT, "include")]
+    demo_o, oracle_o = os.path.join(out_dir, "demo.o"), os.path.join(out_dir, "oracle.o")
+    subprocess.run(["gcc", "-std=c99", "-O1", "-g", "-ffp-contract=off", *san, *inc, "-c",
+                    os.path.join(ROOT, "tests", "c_abi", "step_demo.c"), "-o", demo_o], check=True, capture_output=True, text=True)
+    subprocess.run(["gcc", "-std=c99", "-O2", "-ffp-contract=off", "-c", os.path.join(ROOT, "oracle", "gs_oracle.c"),
+                    "-o", oracle_o], check=True, capture_output=True, text=True)
+    exe = os.path.join(out_dir, "c_sequence")
+    cmd = ["g++", "-std=c++17", "-O1", "-g", "-ffp-contract=off", *san, *inc, "-I", CSRC]
+    for s in HOST_SOURCES:
+        cmd += ["-x", "c++", os.path.join(CSRC, s)]
+    cmd += ["-x", "none", os.path.join(MOCK, "hipmock.cpp"), os.path.join(MOCK, "scalar_kernels.cpp"), demo_o, oracle_o,
+            "-o", exe, "-lpthread", "-lm"]
+    subprocess.run(cmd, check=True, capture_output=True, text=True)
+    return exe
+
+
+@pytest.mark.parametrize("legacy_null_stream", [False, True])
+def test_c_program_sequence_completes_under_null_stream_orderings(tmp_path, tsan_ok, legacy_null_stream):
+    """The whole plain-C sequence -- resident norm and split step on the null stream, then the
+    host-resident step in place on a CU-masked (blocking) stream and staged on three non-blocking
+    streams, null stream as the producer -- against the stand-in, with the null stream run in place
+    and with HIP's legacy ordering between the null stream and blocking streams: it has to finish
+    (no wait cycle in the library's event logic) and match the oracle bit for bit."""
+    exe = _build_c_sequence(str(tmp_path), tsan_ok)
+    env = dict(os.environ, TSAN_OPTIONS="halt_on_error=0 exitcode=66")
+    env.pop("HIPMOCK_LEGACY_NULL", None)
+    if legacy_null_stream:
+        env["HIPMOCK_LEGACY_NULL"] = "1"
+    for argv in ([exe], [exe, "--host-resident"]):
+        r = subprocess.run(argv, capture_output=True, text=True, timeout=60, env=env)
+        assert r.returncode == 0 and "C ABI OK" in r.stdout, r.stdout[-3000:] + r.stderr[-3000:]
+        assert "ThreadSanitizer" not in r.stderr, r.stderr[-3000:]
+    assert "host-resident staged: compare" in r.stdout and "host-resident in place: compare" in r.stdout
+
+
 MUTANTS = [
     ("kernel_ignores_producer", "gs_stream.hip",
      '    GS_TRY(hipStreamWaitEvent(c->s_comp, c->ev_producer, 0), "hipStreamWaitEvent(producer)");\n', ""),
