@@ -14,6 +14,7 @@ import torch
 from oracle import gs_oracle as O
 from paper_2512_17570_amd import gs
 from paper_2512_17570_amd import inputs as I
+from tolerances import f64_truth_check  # noqa: F401  (re-exported for the GPU tests)
 
 DEV = "cuda:0"
 
@@ -103,3 +104,4 @@ class DeviceCase:
         w = np.zeros(self.n, np.uint16)
         O.accum_adamw(p, m, v, w, self.h_g, ohp(hp), c, begin, self.n if end is None else end)
         return p, m, v, w
+

@@ -1,10 +1,13 @@
 """GPU parity at the full workload sizes, in the launch configuration bench.py times.
 
-Where the oracle can take the whole tensor (h=4096) it does; at h=8192 / h=12288 / 8 layers the
-HIP path runs on the full range and is compared with the oracle on sampled windows (head, tail,
-windows at random unaligned offsets, windows straddling split and chunk boundaries), plus
-properties that hold at any size: split == full and streamed == resident bit for bit, w ==
-bf16_rne(p'), additivity of the norm, and the norm against a torch evaluation of its definition.
+The resident workloads are compared with the oracle over their WHOLE range: h=4096 in one piece,
+the headline h=8192 layer and both halves of the h=12288 split step in 2^26-element chunks on the
+host's threads (norm first, from the oracle's own sum; then every element of p, m, v, w).  The
+widened entry points, the GPT-30B-shaped layer and the host-resident workloads run on the full
+range and are compared with the oracle on sampled windows (head, tail, windows at random unaligned
+offsets, windows straddling split and chunk boundaries), plus properties that hold at any size:
+split == full and streamed == resident bit for bit, w == bf16_rne(p'), additivity of the norm, and
+the norm against a torch evaluation of its definition.
 """
 from concurrent.futures import ThreadPoolExecutor
 
@@ -12,7 +15,8 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_util import DEV, O, assert_bf16_close, assert_f32_close, assert_w_is_rne_of_p, gs, np_bf16, np_f32, ohp
+from gpu_util import (DEV, O, assert_bf16_close, assert_f32_close, assert_w_is_rne_of_p, f64_truth_check, gs, np_bf16,
+                      np_f32, ohp)
 from paper_2512_17570_amd import inputs as I
 
 pytestmark = pytest.mark.gpu
@@ -65,6 +69,94 @@ def check_windows(wins, before, after, grads, hp, c, tag):
     return worst
 
 
+def whole_range_oracle_compare(tag, orig, result, w, grads, hp, S_gpu, chunk=1 << 26, threads=16):
+    """Oracle over every element of [0,n), chunk by chunk on `threads` host threads: the squared
+    norm from the oracle's own sums (held against the GPU's), the clip coefficient from it, then
+    the step on host copies of the ORIGINAL states, compared element by element with the GPU's
+    p, m, v (4 ulp or 1e-6) and w (1 bf16 ulp).  Returns (oracle S, c, worst ulp seen)."""
+    n = grads[0].numel()
+    cuts = list(range(0, n, chunk)) + [n]
+    host_g = []
+    S_o = 0.0
+    with ThreadPoolExecutor(threads) as ex:
+        for lo, hi in zip(cuts[:-1], cuts[1:]):
+            hg = [np_bf16(g[lo:hi]) for g in grads]
+            host_g.append(hg)
+            b = [(hi - lo) * i // threads for i in range(threads + 1)]
+            S_o += sum(ex.map(lambda i: O.grad_sqnorm(hg, b[i], b[i + 1]), range(threads)))
+        assert abs(S_gpu - S_o) <= 1e-5 * S_o, (S_gpu, S_o)
+        c = O.clip_coef(S_o, hp.max_grad_norm)
+        assert c == O.clip_coef(S_gpu, hp.max_grad_norm)      # both sides clip with the same fp32 coefficient
+        print(f"[{tag}] oracle norm over {n} elements done: S={S_o:.9e} (GPU {S_gpu:.9e}) c={c:.6f}", flush=True)
+        worst = 0
+        for ci, (lo, hi) in enumerate(zip(cuts[:-1], cuts[1:])):
+            hg = host_g[ci]
+            h_p, h_m, h_v = (np_f32(t[lo:hi]) for t in orig)
+            h_w = np.zeros(hi - lo, np.uint16)
+            b = [(hi - lo) * i // threads for i in range(threads + 1)]
+            list(ex.map(lambda i: O.accum_adamw(h_p, h_m, h_v, h_w, hg, ohp(hp), c, b[i], b[i + 1]), range(threads)))
+            for want, t, nm in ((h_p, result[0], "p"), (h_m, result[1], "m"), (h_v, result[2], "v")):
+                got = np_f32(t[lo:hi])
+                if not np.array_equal(got.view(np.uint32), want.view(np.uint32)):     # fast path: same bits
+                    worst = max(worst, assert_f32_close(got, want, f"{tag}.{nm}[{lo}:{hi}]"))
+            gw = np_bf16(w[lo:hi])
+            if not np.array_equal(gw, h_w):
+                assert_bf16_close(gw, h_w, f"{tag}.w[{lo}:{hi}]")
+            host_g[ci] = None
+            if ci % 4 == 3 or hi == n:
+                print(f"[{tag}] oracle step compared through element {hi} of {n}", flush=True)
+    return S_o, c, worst
+
+
+@pytest.mark.timeout(900)
+def test_h8192_k16_whole_layer_against_the_oracle():
+    """The headline workload in the configuration bench.py times (norm, then the fused step over
+    the whole layer: 3.1 M workgroups), every one of its 805 412 864 elements against the oracle."""
+    wl = I.WORKLOADS["gpt65b_layer_h8192_k16"]
+    n, k = wl.n, wl.k
+    print(f"[h8192 whole] n={n} k={k}", flush=True)
+    p, m, v, grads = I.make_workload_tensors(wl, DEV)
+    orig = (p.clone(), m.clone(), v.clone())
+    w = torch.zeros(n, dtype=torch.bfloat16, device=DEV)
+    sq = torch.zeros(1, dtype=torch.float64, device=DEV)
+    ws = torch.empty(gs.gs_sqnorm_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    hp = hp_of(wl)
+    gs.gs_grad_sqnorm(grads, 0, n, sq, ws)
+    gs.gs_accum_adamw(p, m, v, w, grads, 0, n, hp, sq)
+    torch.cuda.synchronize()
+    S_o, c, worst = whole_range_oracle_compare("h8192 whole", orig, (p, m, v), w, grads, hp, float(sq.item()))
+    assert c < 1.0
+    assert_w_is_rne_of_p(p, w, 0, n)
+    print(f"[h8192 whole] every element within tolerance, worst ulp {worst}", flush=True)
+
+
+@pytest.mark.timeout(1200)
+def test_h12288_k8_both_halves_of_the_split_against_the_oracle():
+    """The split step as bench.py times it -- immediate part [0,s) and deferred part [s,n) as two
+    calls on two streams, s = 724 839 628 unaligned -- with all 1 812 099 072 elements of both
+    halves against the oracle."""
+    wl = I.WORKLOADS["gpt175b_layer_h12288_k8_split"]
+    n, k = wl.n, wl.k
+    s_pt = int(wl.extra["immediate_frac"] * n)
+    print(f"[h12288 whole] n={n} k={k} split at {s_pt}", flush=True)
+    p, m, v, grads = I.make_workload_tensors(wl, DEV)
+    orig = (p.clone(), m.clone(), v.clone())
+    w = torch.zeros(n, dtype=torch.bfloat16, device=DEV)
+    sq = torch.zeros(1, dtype=torch.float64, device=DEV)
+    ws = torch.empty(gs.gs_sqnorm_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    hp = hp_of(wl)
+    gs.gs_grad_sqnorm(grads, 0, n, sq, ws)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    cur = torch.cuda.current_stream()
+    sa.wait_stream(cur); sb.wait_stream(cur)
+    gs.gs_accum_adamw(p, m, v, w, grads, 0, s_pt, hp, sq, stream=sa)      # immediate part
+    gs.gs_accum_adamw(p, m, v, w, grads, s_pt, n, hp, sq, stream=sb)      # deferred part, other stream
+    torch.cuda.synchronize()
+    S_o, c, worst = whole_range_oracle_compare("h12288 whole", orig, (p, m, v), w, grads, hp, float(sq.item()))
+    assert_w_is_rne_of_p(p, w, 0, n)
+    print(f"[h12288 whole] both halves within tolerance, worst ulp {worst}", flush=True)
+
+
 def test_h4096_k8_full_oracle_with_clipping():
     wl = I.WORKLOADS["gpt_h4096_k8"]
     n, k = wl.n, wl.k
@@ -76,6 +168,8 @@ def test_h4096_k8_full_oracle_with_clipping():
     h_p, h_m, h_v = np_f32(p), np_f32(m), np_f32(v)
     h_g = [np_bf16(g) for g in grads]
     hp = hp_of(wl)
+    nn = 1 << 25
+    o_p, o_m, o_v = h_p[:nn].copy(), h_m[:nn].copy(), h_v[:nn].copy()      # originals, for the fp64 evaluation below
     gs.gs_grad_sqnorm(grads, 0, n, sq, ws)
     gs.gs_accum_adamw(p, m, v, w, grads, 0, n, hp, sq)
     torch.cuda.synchronize()
@@ -96,6 +190,13 @@ def test_h4096_k8_full_oracle_with_clipping():
     uw = assert_bf16_close(np_bf16(w), h_w, "h4096.w")
     assert_w_is_rne_of_p(p, w, 0, n)
     print(f"[h4096] S={S:.6e} oracle={So:.6e} c={c:.4e} max ulp p/m/v/w={up, um, uv, uw}", flush=True)
+    # GPU against the fp64 evaluation of the same formulas, with clipping active, on the first 2^25
+    # elements: the stated tolerance wherever the final add does not cancel, the operand-aware bound elsewhere
+    tp, tm, tv = O.accum_adamw_f64(o_p, o_m, o_v, [g[:nn] for g in h_g], ohp(hp), So)
+    for nm, t, truth, old in (("p", p, tp, o_p), ("m", m, tm, o_m), ("v", v, tv, o_v)):
+        share, worst_rel, worst_sp = f64_truth_check(np_f32(t[:nn]), truth, old, f"h4096 vs fp64 {nm}")
+        print(f"[h4096] {nm} vs fp64: {100 * share:.2f} % of elements judged by 4 ulp / 1e-6 (worst rel {worst_rel:.2e}); "
+              f"worst error {worst_sp:.2f} spacings of the larger operand", flush=True)
 
 
 @pytest.mark.parametrize("name", ["gpt65b_layer_h8192_k16", "gpt30b_layer_h7168_k16"])
