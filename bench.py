@@ -10,8 +10,14 @@ micro-batch gradient buffers), synthetic seeded tensors.
 Prints ONE JSON line.  `value` is parameters per second over the timed region (wall clock
 between two device synchronisations).  `roofline` is for the dominant kernel
 (gs_accum_adamw): algorithmic bytes (2k+26 per parameter) divided by its average duration
-measured with HIP events on the launch stream, against the 8 TB/s HBM peak.  `cpu_baseline`
-times the CPU oracle on a bounded sample of the same tensors on the host's cores.
+measured with HIP events on the launch stream (median and minimum beside it), against the
+8 TB/s HBM peak; `roofline.achievable` holds what the same device gives simpler traffic and the
+step's own mix of streams without arithmetic.  `cpu_baseline` times the CPU oracle on a bounded
+sample of the same tensors on the host's cores, all of them and one.  With the default workload,
+`other_workloads` adds short runs of the other configurations: the h = 1024 layer (cold caches:
+rotating tensor sets), h = 4096, the GPT-30B-shaped layer, the split step of the GPT-175B-shaped
+layer beside a GEMM, and the host-resident step (staged and in place).  `--workload NAME` runs
+one of them in full instead.
 """
 from __future__ import annotations
 
@@ -42,6 +48,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default=HEADLINE)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="headline workload only: skip the short runs of the other configurations")
+    ap.add_argument("--no-ceiling", action="store_true", help="skip the no-arithmetic stream-mix probe kernels")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise copy of 2^28 floats (1 GiB in, 1 GiB out) three times before the "
                          "timed region, as the known-size reference for rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
@@ -57,8 +66,9 @@ def parse():
 
 
 def cpu_baseline(wl, p, m, v, grads, hp, sample: int):
-    """Time the oracle (norm pass + fused step, as it stands) on the first `sample` elements,
-    split over the host's cores in disjoint ranges."""
+    """Time the oracle (norm pass + fused step, as it stands) on the first `sample` elements of the
+    workload's tensors: once split over the host's cores in disjoint ranges (the reported `value`),
+    once on one thread over a quarter of that sample (`single_thread`)."""
     import numpy as np
     from concurrent.futures import ThreadPoolExecutor
 
@@ -72,21 +82,30 @@ def cpu_baseline(wl, p, m, v, grads, hp, sample: int):
     h_g = [I.bf16_bits(g[:sample]).copy() for g in grads]
     h_w = np.zeros(sample, np.uint16)
     ohp = O.HParams(hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, hp.max_grad_norm, hp.step)
-    bounds = [sample * i // cores for i in range(cores + 1)]
     O.lib()
 
-    def norm_part(i):
-        return O.grad_sqnorm(h_g, bounds[i], bounds[i + 1])
+    def run(threads, count):
+        bounds = [count * i // threads for i in range(threads + 1)]
+        t0 = time.perf_counter()
+        with ThreadPoolExecutor(threads) as ex:
+            S = sum(ex.map(lambda i: O.grad_sqnorm(h_g, bounds[i], bounds[i + 1]), range(threads)))
+            c = O.clip_coef(S, hp.max_grad_norm)
+            list(ex.map(lambda i: O.accum_adamw(h_p, h_m, h_v, h_w, h_g, ohp, c, bounds[i], bounds[i + 1]), range(threads)))
+        return time.perf_counter() - t0
 
-    t0 = time.perf_counter()
-    with ThreadPoolExecutor(cores) as ex:
-        S = sum(ex.map(norm_part, range(cores)))
-        c = O.clip_coef(S, hp.max_grad_norm)
-        list(ex.map(lambda i: O.accum_adamw(h_p, h_m, h_v, h_w, h_g, ohp, c, bounds[i], bounds[i + 1]), range(cores)))
-    dt = time.perf_counter() - t0
+    dt = run(cores, sample)
+    single = max(1, sample // 4)
+    dt1 = run(1, single)
+    try:
+        model = next(l.split(":", 1)[1].strip() for l in open("/proc/cpuinfo") if l.startswith("model name"))
+    except Exception:
+        model = "unknown"
     return {"value": sample / dt, "unit": "params/s", "cores": cores, "kind": "oracle",
             "sample": f"first {sample} of {wl.n} parameters of the same tensors, norm pass + fused step, "
-                      f"{cores} threads over disjoint ranges, {dt:.2f} s wall"}
+                      f"{cores} threads over disjoint ranges, {dt:.2f} s wall",
+            "single_thread": {"value": single / dt1, "unit": "params/s", "cores": 1,
+                              "sample": f"first {single} parameters, norm pass + fused step, one thread, {dt1:.2f} s wall"},
+            "host_cpu": model, "host_logical_cpus": os.cpu_count()}
 
 
 def _hp_of(gs, wl, i=0):
@@ -103,105 +122,46 @@ def _base_record(wl, props, value, steps, warmup, ms_per_step, extra_cfg=None):
             "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic", "config": cfg}
 
 
-def bench_split(args, wl):
-    """Split step (delay ratio alpha, Sec. 4.4 of the paper): the immediate part of the range is
-    updated right away, the deferred part on a second stream while a bf16 GEMM standing in for the
-    next iteration's forward runs on the first.  Reports the step's and the GEMM's slowdown under
-    contention.  Timing only; split == full is checked bit for bit by the GPU tests."""
-    import torch
+def concurrent_streams(torch, count=2, tries=24):
+    """`count` torch streams that the runtime really runs side by side.  HIP multiplexes a process's
+    streams onto a few hardware queues (4 here), and two streams that land on one queue run their
+    work in turn, which would turn every "beside" measurement below into a serial one.  A candidate
+    is accepted when a tiny kernel launched on it AFTER a few-millisecond burst on each stream
+    already chosen finishes BEFORE that burst does."""
+    big = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0")
+    small = torch.zeros(1 << 10, dtype=torch.float32, device="cuda:0")
+    big.zero_()
+    chosen = [torch.cuda.Stream()]
+    for _ in range(tries):
+        if len(chosen) == count:
+            break
+        cand = torch.cuda.Stream()
+        if any(cand.cuda_stream == c.cuda_stream for c in chosen):
+            continue
+        ok = True
+        for c in chosen:
+            torch.cuda.synchronize()
+            e_long, e_short = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            with torch.cuda.stream(c):
+                for _ in range(8):
+                    big.add_(1.0)
+                e_long.record(c)
+            with torch.cuda.stream(cand):
+                small.add_(1.0)
+                e_short.record(cand)
+            torch.cuda.synchronize()
+            if e_short.elapsed_time(e_long) < 0.5:      # the tiny kernel did not overtake the burst
+                ok = False
+                break
+        if ok:
+            chosen.append(cand)
+    del big, small
+    if len(chosen) < count:
+        raise RuntimeError("bench.py: could not find streams that run concurrently")
+    return chosen
 
-    from paper_2512_17570_amd import gs
-    from paper_2512_17570_amd import inputs as I
 
-    dev = "cuda:0"
-    props = torch.cuda.get_device_properties(0)
-    n, k = wl.n, wl.k
-    s_pt = int(wl.extra["immediate_frac"] * n)
-    p, m, v, grads = I.make_workload_tensors(wl, dev)
-    w = torch.zeros(n, dtype=torch.bfloat16, device=dev)
-    sq = torch.zeros(1, dtype=torch.float64, device=dev)
-    ws = torch.empty(gs.gs_sqnorm_workspace_bytes(), dtype=torch.uint8, device=dev)
-    tokens = wl.extra["gemm_tokens"]
-    ga = torch.randn(tokens, wl.h, dtype=torch.bfloat16, device=dev)
-    gb = torch.randn(wl.h, wl.h, dtype=torch.bfloat16, device=dev)
-    gc = torch.empty(tokens, wl.h, dtype=torch.bfloat16, device=dev)
-    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
-    hp = _hp_of(gs, wl)
-    gs.gs_grad_sqnorm(grads, 0, n, sq, ws)
-    torch.cuda.synchronize()
-
-    def timed(fn, stream, reps):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        with torch.cuda.stream(stream):
-            e0.record(stream)
-            for _ in range(reps):
-                fn(stream)
-            e1.record(stream)
-        return e0, e1
-
-    def full(st):
-        gs.gs_accum_adamw(p, m, v, w, grads, 0, n, hp, sq, stream=st)
-
-    def immediate(st):
-        gs.gs_accum_adamw(p, m, v, w, grads, 0, s_pt, hp, sq, stream=st)
-
-    def deferred(st):
-        gs.gs_accum_adamw(p, m, v, w, grads, s_pt, n, hp, sq, stream=st)
-
-    def gemm(st):
-        torch.matmul(ga, gb, out=gc)
-
-    def alone(fn, stream, reps):
-        for _ in range(args.warmup):
-            with torch.cuda.stream(stream):
-                fn(stream)
-        torch.cuda.synchronize()
-        e0, e1 = timed(fn, stream, reps)
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps
-
-    t_full = alone(full, sb, args.steps)
-    t_imm = alone(immediate, sb, args.steps)
-    t_def = alone(deferred, sb, args.steps)
-    t_gemm = alone(gemm, sa, 4 * args.steps)
-    reps_gemm = max(1, int(round(t_def / t_gemm)))     # GEMMs that cover one deferred step
-    # concurrent: each iteration = one deferred step on sb || reps_gemm GEMMs on sa
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    pairs = []
-    for _ in range(args.steps):
-        eg = timed(gemm, sa, reps_gemm)
-        ed = timed(deferred, sb, 1)
-        pairs.append((eg, ed))
-    torch.cuda.synchronize()
-    wall = (time.perf_counter() - t0) / args.steps * 1e3
-    t_gemm_c = sum(a.elapsed_time(b) for (a, b), _ in pairs) / args.steps / reps_gemm
-    t_def_c = sum(a.elapsed_time(b) for _, (a, b) in pairs) / args.steps
-    # the same with the deferred part on a stream confined to half of the compute units
-    budget = {}
-    cus = props.multi_processor_count
-    for ncu in (cus // 2, (3 * cus) // 4):
-        raw = gs.gs_cu_stream_create(ncu)
-        sc = torch.cuda.ExternalStream(raw)
-        t_def_b = alone(deferred, sc, args.steps)
-        reps_b = reps_gemm
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        pairs_b = []
-        for _ in range(args.steps):
-            eg = timed(gemm, sa, reps_b)
-            ed = timed(deferred, sc, 1)
-            pairs_b.append((eg, ed))
-        torch.cuda.synchronize()
-        wall_b = (time.perf_counter() - t0) / args.steps * 1e3
-        budget[str(ncu)] = {
-            "deferred_alone_ms": t_def_b,
-            "deferred_concurrent_ms": sum(a.elapsed_time(b) for _, (a, b) in pairs_b) / args.steps,
-            "gemm_concurrent_ms": sum(a.elapsed_time(b) for (a, b), _ in pairs_b) / args.steps / reps_b,
-            "concurrent_wall_ms_per_iter": wall_b}
-        budget[str(ncu)]["gemm_slowdown"] = budget[str(ncu)]["gemm_concurrent_ms"] / t_gemm
-        del sc
-        gs.gs_cu_stream_destroy(raw)
+def _layer_sequence(args, wl, gs, torch, dev, tokens, ga, gb, gc, sa, sb, deferred, t_def, cus):
     # A sequence of layers (Sec. 4.4: a layer's deferred update only has to be finished before that
     # layer's forward of the next iteration): the forward of layer i (its four bf16 GEMMs for
     # `tokens` tokens) waits for the event of layer i's deferred step; the deferred steps run in
@@ -277,6 +237,112 @@ def bench_split(args, wl):
     seq["note"] = ("forward of layer i waits for layer i's deferred step; steps run in layer order on their own stream. "
                    "bound = one exposed deferred step + the forwards at their solo speed")
 
+    return seq
+
+
+def bench_split(args, wl, brief=False):
+    """Split step (delay ratio alpha, Sec. 4.4 of the paper): the immediate part of the range is
+    updated right away, the deferred part on a second stream while a bf16 GEMM standing in for the
+    next iteration's forward runs on the first.  Reports the step's and the GEMM's slowdown under
+    contention.  Timing only; split == full is checked bit for bit by the GPU tests."""
+    import torch
+
+    from paper_2512_17570_amd import gs
+    from paper_2512_17570_amd import inputs as I
+
+    dev = "cuda:0"
+    props = torch.cuda.get_device_properties(0)
+    n, k = wl.n, wl.k
+    s_pt = int(wl.extra["immediate_frac"] * n)
+    p, m, v, grads = I.make_workload_tensors(wl, dev)
+    w = torch.zeros(n, dtype=torch.bfloat16, device=dev)
+    sq = torch.zeros(1, dtype=torch.float64, device=dev)
+    ws = torch.empty(gs.gs_sqnorm_workspace_bytes(), dtype=torch.uint8, device=dev)
+    tokens = wl.extra["gemm_tokens"]
+    ga = torch.randn(tokens, wl.h, dtype=torch.bfloat16, device=dev)
+    gb = torch.randn(wl.h, wl.h, dtype=torch.bfloat16, device=dev)
+    gc = torch.empty(tokens, wl.h, dtype=torch.bfloat16, device=dev)
+    sa, sb = concurrent_streams(torch, 2)
+    hp = _hp_of(gs, wl)
+    gs.gs_grad_sqnorm(grads, 0, n, sq, ws)
+    torch.cuda.synchronize()
+
+    def timed(fn, stream, reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(stream):
+            e0.record(stream)
+            for _ in range(reps):
+                fn(stream)
+            e1.record(stream)
+        return e0, e1
+
+    def full(st):
+        gs.gs_accum_adamw(p, m, v, w, grads, 0, n, hp, sq, stream=st)
+
+    def immediate(st):
+        gs.gs_accum_adamw(p, m, v, w, grads, 0, s_pt, hp, sq, stream=st)
+
+    def deferred(st):
+        gs.gs_accum_adamw(p, m, v, w, grads, s_pt, n, hp, sq, stream=st)
+
+    def gemm(st):
+        torch.matmul(ga, gb, out=gc)
+
+    def alone(fn, stream, reps):
+        for _ in range(args.warmup):
+            with torch.cuda.stream(stream):
+                fn(stream)
+        torch.cuda.synchronize()
+        e0, e1 = timed(fn, stream, reps)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    t_full = alone(full, sb, args.steps)
+    t_imm = alone(immediate, sb, args.steps)
+    t_def = alone(deferred, sb, args.steps)
+    t_gemm = alone(gemm, sa, 4 * args.steps)
+    reps_gemm = max(1, int(round(t_def / t_gemm)))     # GEMMs that cover one deferred step
+    # concurrent: each iteration = one deferred step on sb || reps_gemm GEMMs on sa
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    pairs = []
+    for _ in range(args.steps):
+        eg = timed(gemm, sa, reps_gemm)
+        ed = timed(deferred, sb, 1)
+        pairs.append((eg, ed))
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / args.steps * 1e3
+    t_gemm_c = sum(a.elapsed_time(b) for (a, b), _ in pairs) / args.steps / reps_gemm
+    t_def_c = sum(a.elapsed_time(b) for _, (a, b) in pairs) / args.steps
+    # the same with the deferred part on a stream confined to half of the compute units
+    budget = {}
+    cus = props.multi_processor_count
+    for ncu in (() if brief else (cus // 2, (3 * cus) // 4)):
+        raw = gs.gs_cu_stream_create(ncu)
+        sc = torch.cuda.ExternalStream(raw)
+        t_def_b = alone(deferred, sc, args.steps)
+        reps_b = reps_gemm
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        pairs_b = []
+        for _ in range(args.steps):
+            eg = timed(gemm, sa, reps_b)
+            ed = timed(deferred, sc, 1)
+            pairs_b.append((eg, ed))
+        torch.cuda.synchronize()
+        wall_b = (time.perf_counter() - t0) / args.steps * 1e3
+        budget[str(ncu)] = {
+            "deferred_alone_ms": t_def_b,
+            "deferred_concurrent_ms": sum(a.elapsed_time(b) for _, (a, b) in pairs_b) / args.steps,
+            "gemm_concurrent_ms": sum(a.elapsed_time(b) for (a, b), _ in pairs_b) / args.steps / reps_b,
+            "concurrent_wall_ms_per_iter": wall_b}
+        budget[str(ncu)]["gemm_slowdown"] = budget[str(ncu)]["gemm_concurrent_ms"] / t_gemm
+        del sc
+        gs.gs_cu_stream_destroy(raw)
+    seq = None
+    if not brief:
+        seq = _layer_sequence(args, wl, gs, torch, dev, tokens, ga, gb, gc, sa, sb, deferred, t_def, cus)
+
     bpp = 2 * k + 26
     rec = _base_record(wl, props, n / ((t_imm + t_def) * 1e-3), args.steps, args.warmup, t_imm + t_def,
                        {"split_point": s_pt, "immediate_frac": wl.extra["immediate_frac"],
@@ -296,10 +362,10 @@ def bench_split(args, wl):
         "layer_sequence": seq,
     }
     rec["cpu_baseline"] = None
-    print(json.dumps(rec))
+    return rec
 
 
-def bench_streamed(args, wl):
+def bench_streamed(args, wl, brief=False):
     """Host-resident step (Sec. 2.2 chunk loop / Sec. 4.3 pipeline of the paper, with host<->GPU
     PCIe as the slow link): fp32 p/m/v of all layers live in pinned host memory and are stepped in
     2^26-element chunks, upload | kernel | download overlapped on three streams (12 B up + 12 B down
@@ -315,6 +381,9 @@ def bench_streamed(args, wl):
     props = torch.cuda.get_device_properties(0)
     chunk = wl.extra["chunk_elems"]
     layers, nl, k = wl.layers, I.layer_numel(wl.h), wl.k
+    steps, warmup = (min(args.steps, 3), 1) if brief else (args.steps, args.warmup)
+    if brief:
+        layers = min(layers, 2)
     # pin as many layers as the host allows
     bufs = None
     while layers > 0:
@@ -351,12 +420,12 @@ def bench_streamed(args, wl):
                 gs.gs_stream_layer_step(ctx, hp_p + o, hm_p + o, hv_p + o, w_l[L], grads_l[L], nl, hp, sq,
                                         producer_stream=cur)
             gs.gs_stream_ctx_sync(ctx)
-        for i in range(args.warmup):
+        for i in range(warmup):
             one_pass(i)
         t0 = time.perf_counter()
-        for i in range(args.steps):
-            one_pass(args.warmup + i)
-        return (time.perf_counter() - t0) / args.steps
+        for i in range(steps):
+            one_pass(warmup + i)
+        return (time.perf_counter() - t0) / steps
 
     # the configuration as named: 2^26-element chunks, upload | kernel in an HBM slot | download
     ctx = gs.gs_stream_ctx_create(chunk, args.slots)
@@ -392,13 +461,14 @@ def bench_streamed(args, wl):
         return nchunks * chunk * 4 / (time.perf_counter() - t0) / 1e9
 
     copy_pass(8, True, True)                      # warm the copy engines and both streams
-    h2d_only_gbs = copy_pass(32, True, False)
-    d2h_only_gbs = copy_pass(32, False, True)
-    duplex_dir_gbs = copy_pass(48, True, True)
+    h2d_only_gbs = copy_pass(16 if brief else 32, True, False)
+    d2h_only_gbs = copy_pass(16 if brief else 32, False, True)
+    duplex_dir_gbs = copy_pass(24 if brief else 48, True, True)
     del stage
 
-    rec = _base_record(wl, props, n / per, args.steps, args.warmup, per * 1e3,
-                       {"layers_pinned": layers, "n_params": n, "chunk_elems": chunk, "slots": args.slots,
+    rec = _base_record(wl, props, n / per, steps, warmup, per * 1e3,
+                       {"layers": layers, "layers_in_workload": wl.layers, "n_params": n, "chunk_elems": chunk,
+                        "slots": args.slots,
                         "host_pinned_bytes": 12 * n, "device_staging_bytes": args.slots * 3 * (chunk + 64) * 4})
     pcie_dir = 12 * n / per / 1e9
     link = min(h2d_only_gbs, d2h_only_gbs)
@@ -418,9 +488,9 @@ def bench_streamed(args, wl):
                 "over the link per parameter), one stream limited to stream_cus compute units, no copies; same results "
                 "bit for bit; its rate does not depend on the runtime's copy path or on hardware-queue assignment"}
     rec["cpu_baseline"] = None
-    print(json.dumps(rec))
     for t, ptr in bufs:
         gs.gs_pinned_free(ptr)
+    return rec
 
 
 def bench_tiered(args, wl):
@@ -592,7 +662,7 @@ def bench_tiered(args, wl):
                            "duplex_probe_GBps_per_direction": duplex_gbs,
                            "pcie_GBps_per_direction": 12 * n / per / 1e9}
         rec["cpu_baseline"] = None
-        print(json.dumps(rec))
+        return rec
     finally:
         for lf in fds:
             for fd in lf:
@@ -603,63 +673,139 @@ def bench_tiered(args, wl):
                 gs.gs_pinned_free(ptr)
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print(f"bench.py: this build measures one GPU only (no sharding or collectives); --gpus {args.gpus} is not supported",
-              file=sys.stderr)
-        sys.exit(2)
+CACHE_BYTES = 256 << 20        # last-level (memory-side) cache of the device; L2 is 8 x 4 MB on top
+COLD_SETS = 8
 
+
+def _stats(ms):
+    """Mean, median and minimum of a list of per-launch durations (ms)."""
+    xs = sorted(ms)
+    nn = len(xs)
+    med = xs[nn // 2] if nn % 2 else 0.5 * (xs[nn // 2 - 1] + xs[nn // 2])
+    return {"avg_ms": sum(xs) / nn, "median_ms": med, "min_ms": xs[0]}
+
+
+def _kernel_entry(ms, bytes_per_param, n):
+    st = _stats(ms)
+    nbytes = n * bytes_per_param
+    st.update({"bytes_per_param": bytes_per_param, "GBps": nbytes / (st["avg_ms"] * 1e-3) / 1e9,
+               "frac": nbytes / (st["avg_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+               "GBps_median": nbytes / (st["median_ms"] * 1e-3) / 1e9, "GBps_best": nbytes / (st["min_ms"] * 1e-3) / 1e9})
+    return st
+
+
+def same_mix_ceiling(torch, grads, p, m, v, w, n, k, reps, block):
+    """What this device gives the fused step's own mix of streams (k bf16 + 3 fp32 in, 3 fp32 + 1 bf16
+    out) when no arithmetic is attached: the probe kernels of probe/gs_mixprobe.hip, out of place
+    into scratch outputs.  (a) the step kernel's shape; (b) the same tile with all loads in flight;
+    (c) the read half and the write half as two kernels running at once on two streams."""
+    from paper_2512_17570_amd import mixprobe as MP
+
+    dev = p.device
+    n4 = n - n % 4
+    po, mo, vo = torch.empty_like(p), torch.empty_like(m), torch.empty_like(v)
+    wo = torch.empty_like(w)
+    sink = torch.zeros(16, dtype=torch.int32, device=dev)
+    s1, s2 = concurrent_streams(torch, 2)
+    total = n4 * (2 * k + 26)
+
+    def timed_one(mode, blk):
+        def go():
+            MP.launch(mode, blk, p, m, v, po, mo, vo, wo, grads, n4, sink, s1)
+        go()
+        s1.synchronize()
+        out = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(s1)
+            go()
+            e1.record(s1)
+            s1.synchronize()
+            out.append(e0.elapsed_time(e1))
+        return out
+
+    fused = timed_one(MP.FUSED_SHALLOW, block)
+    deep = timed_one(MP.FUSED_ALL_IN_FLIGHT, 256)
+    rd = timed_one(MP.READ_HALF, block)
+    wr = timed_one(MP.WRITE_HALF, block)
+    # both halves at once: the read kernel on s1, the write kernel on s2, started together
+    pair = []
+    for it in range(reps + 1):
+        torch.cuda.synchronize()
+        e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        e0.record(s1)
+        s2.wait_event(e0)
+        MP.launch(MP.READ_HALF, block, p, m, v, po, mo, vo, wo, grads, n4, sink, s1)
+        MP.launch(MP.WRITE_HALF, block, p, m, v, po, mo, vo, wo, grads, n4, sink, s2)
+        e1.record(s1)
+        e2.record(s2)
+        torch.cuda.synchronize()
+        if it:
+            pair.append(max(e0.elapsed_time(e1), e0.elapsed_time(e2)))
+    del po, mo, vo, wo
+
+    def gbs(ms):
+        return total / (_stats(ms)["avg_ms"] * 1e-3) / 1e9
+    r_ms, w_ms = _stats(rd)["avg_ms"], _stats(wr)["avg_ms"]
+    res = {"same_mix_step_shape_GBps": gbs(fused), "same_mix_all_loads_in_flight_GBps": gbs(deep),
+           "same_mix_read_kernel_beside_write_kernel_GBps": gbs(pair),
+           "read_half_alone_GBps": n4 * (2 * k + 12) / (r_ms * 1e-3) / 1e9,
+           "write_half_alone_GBps": n4 * 14 / (w_ms * 1e-3) / 1e9,
+           "read_then_write_serial_GBps": total / ((r_ms + w_ms) * 1e-3) / 1e9}
+    res["same_mix_ceiling_GBps"] = max(res["same_mix_step_shape_GBps"], res["same_mix_all_loads_in_flight_GBps"],
+                                       res["same_mix_read_kernel_beside_write_kernel_GBps"])
+    return res
+
+
+def bench_resident(args, wl, full=True):
+    """One layer resident in HBM: norm pass + fused step, timed per launch with events.  full: also the
+    widened variants (staged two-pass, accumulate-as-you-go, speculative), the achievable ceilings
+    and the CPU baseline (the headline record); otherwise the two kernels only."""
     import torch
 
     from paper_2512_17570_amd import gs
     from paper_2512_17570_amd import inputs as I
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    if args.workload not in I.WORKLOADS:
-        print(f"unknown workload {args.workload}; have {list(I.WORKLOADS)}", file=sys.stderr)
-        sys.exit(2)
-    wl = I.WORKLOADS[args.workload]
     dev = "cuda:0"
-    torch.cuda.set_device(0)
-    if "immediate_frac" in wl.extra:
-        return bench_split(args, wl)
-    if "host_share" in wl.extra:
-        return bench_tiered(args, wl)
-    if "chunk_elems" in wl.extra:
-        return bench_streamed(args, wl)
     props = torch.cuda.get_device_properties(0)
+    n, k = wl.n, wl.k
+    working_set = n * (12 + 2 + 2 * k)
+    # A working set near the size of the last-level cache would be timed warm on one tensor set, so
+    # small workloads rotate over independent sets (one per iteration, round robin): by the time a
+    # set comes round again, COLD_SETS-1 others have streamed through the caches.
+    nsets = COLD_SETS if working_set < 4 * CACHE_BYTES else 1
 
     t_gen = time.perf_counter()
-    p, m, v, grads = I.make_workload_tensors(wl, dev)
-    w = torch.zeros(wl.n, dtype=torch.bfloat16, device=dev)
+    sets = []
+    for r in range(nsets):
+        p, m, v = I.make_states(n, wl.seed + 1000 * r, dev)
+        grads = I.make_grads(n, k, wl.grad_sigma, wl.seed + 1000 * r, dev, wl.outlier_frac, wl.outlier_scale)
+        sets.append((p, m, v, torch.zeros(n, dtype=torch.bfloat16, device=dev), grads))
     sq = torch.zeros(1, dtype=torch.float64, device=dev)
     ws = torch.empty(gs.gs_sqnorm_workspace_bytes(), dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
-
-    n, k = wl.n, wl.k
+    p, m, v, w, grads = sets[0]
 
     def hp_at(i):
         return gs.HParams(wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay, wl.max_grad_norm, wl.step + i)
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if full and not args.no_cpu_baseline:
         cpu = cpu_baseline(wl, p, m, v, grads, hp_at(0), args.cpu_sample)
 
-    def one_step(i, evs=None):
+    def one_step(i, evs=None, which=None):
+        sp, sm, sv, sw, sg = sets[(i if which is None else which) % nsets]
         if evs:
             evs[0].record()
-        gs.gs_grad_sqnorm(grads, 0, n, sq, ws)
+        gs.gs_grad_sqnorm(sg, 0, n, sq, ws)
         if evs:
             evs[1].record()
-        gs.gs_accum_adamw(p, m, v, w, grads, 0, n, hp_at(i), sq)
+        gs.gs_accum_adamw(sp, sm, sv, sw, sg, 0, n, hp_at(i), sq)
         if evs:
             evs[2].record()
 
-    if args.calibrate_copy:
+    if full and args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
         for _ in range(3):
@@ -667,7 +813,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for i in range(args.warmup):
+    warm = max(args.warmup, nsets if nsets > 1 else 0)      # every set is touched once before timing
+    for i in range(warm):
         one_step(i)
     torch.cuda.synchronize()
 
@@ -675,12 +822,56 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        one_step(args.warmup + i, events[i])
+        one_step(warm + i, events[i])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
-    norm_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
-    step_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
+    norm_l = [e[0].elapsed_time(e[1]) for e in events]
+    step_l = [e[1].elapsed_time(e[2]) for e in events]
+    both_l = [e[0].elapsed_time(e[2]) for e in events]
+    k_step = _kernel_entry(step_l, 2 * k + 26, n)
+    k_norm = _kernel_entry(norm_l, 2 * k, n)
+
+    warm_ref = None
+    if nsets > 1:
+        # the same on ONE tensor set, i.e. with whatever the caches keep from the previous iteration
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+        for i in range(3):
+            one_step(i, which=0)
+        torch.cuda.synchronize()
+        for i in range(args.steps):
+            one_step(i, ev[i], which=0)
+        torch.cuda.synchronize()
+        warm_ref = {"gs_accum_adamw": _kernel_entry([e[1].elapsed_time(e[2]) for e in ev], 2 * k + 26, n),
+                    "gs_grad_sqnorm": _kernel_entry([e[0].elapsed_time(e[1]) for e in ev], 2 * k, n),
+                    "note": "one tensor set reused every iteration (warm caches); not the reported figures"}
+
+    step_bytes = n * (2 * k + 26)
+    cache_protocol = (f"cold: rotation over {nsets} independent tensor sets of {working_set / 1e6:.0f} MB each, one per "
+                      f"iteration ({nsets * working_set / 1e9:.2f} GB in all against a {CACHE_BYTES >> 20} MB last-level cache)"
+                      if nsets > 1 else
+                      f"one tensor set: its {working_set / 1e9:.1f} GB working set is {working_set / CACHE_BYTES:.0f}x the "
+                      f"{CACHE_BYTES >> 20} MB last-level cache, so every pass is cold")
+    out = _base_record(wl, props, n * args.steps / elapsed, args.steps, args.warmup, elapsed / args.steps * 1e3,
+                       {"input_gen_s": round(t_gen, 2), "tensor_sets": nsets, "cache_protocol": cache_protocol})
+    out["timing"] = {"per_step": _stats(both_l), "protocol": "HIP events around every launch on the launch stream; "
+                     "mean, median and minimum over the timed steps; `value` is wall clock over all of them"}
+    traffic = MEASURED_TRAFFIC_BYTES.get(wl.name)
+    out["roofline"] = {"bound": "hbm", "kernel": "gs_accum_adamw", "achieved": k_step["GBps"], "peak": HBM_PEAK_GBS,
+                       "unit": "GB/s", "frac": k_step["frac"], "traffic": traffic,
+                       "traffic_source": (None if traffic is None else
+                                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this kernel on this workload, from the "
+                                          "summary under profiles/ (a stored figure, not measured by this run)"),
+                       "algorithmic_bytes_per_launch": step_bytes, "avg_launch_ms": k_step["avg_ms"],
+                       "median_launch_ms": k_step["median_ms"], "min_launch_ms": k_step["min_ms"],
+                       "frac_median": k_step["GBps_median"] / HBM_PEAK_GBS, "frac_best": k_step["GBps_best"] / HBM_PEAK_GBS,
+                       "params_per_s": n / (k_step["avg_ms"] * 1e-3)}
+    out["kernels"] = {"gs_accum_adamw": k_step, "gs_grad_sqnorm": k_norm}
+    if warm_ref:
+        out["warm_cache_reference"] = warm_ref
+    if not full:
+        out["cpu_baseline"] = None
+        return out
 
     # the staged two-pass variant of the same step (norm pass leaves the fp32 sum behind): reported
     # beside the headline, never as `value`
@@ -700,25 +891,26 @@ def main():
         ev2[i][2].record()
     torch.cuda.synchronize()
     staged_elapsed = time.perf_counter() - t1
-    st_norm_ms = sum(e[0].elapsed_time(e[1]) for e in ev2) / args.steps
-    st_step_ms = sum(e[1].elapsed_time(e[2]) for e in ev2) / args.steps
 
     # accumulate as you go: one micro-batch added into the resident fp32 buffer per call, the
     # last call also reducing the norm; then the step from the buffer
     def timed(fn, reps):
         fn()
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
+        out_ms = []
         for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
             fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps
-    add_first_ms = timed(lambda: gs.gs_accum_add(acc, grads[0], True, 0, n), args.steps)
-    add_ms = timed(lambda: gs.gs_accum_add(acc, grads[1 % k], False, 0, n), args.steps)
-    add_norm_ms = timed(lambda: gs.gs_accum_add(acc, grads[k - 1], False, 0, n, sq, ws_big), args.steps)
-    acc_norm_ms = timed(lambda: gs.gs_acc_sqnorm(acc, 0, n, sq, ws), args.steps)
+            e1.record()
+            torch.cuda.synchronize()
+            out_ms.append(e0.elapsed_time(e1))
+        return out_ms
+    add_first = timed(lambda: gs.gs_accum_add(acc, grads[0], True, 0, n), args.steps)
+    add = timed(lambda: gs.gs_accum_add(acc, grads[1 % k], False, 0, n), args.steps)
+    add_norm = timed(lambda: gs.gs_accum_add(acc, grads[k - 1], False, 0, n, sq, ws_big), args.steps)
+    acc_norm = timed(lambda: gs.gs_acc_sqnorm(acc, 0, n, sq, ws), args.steps)
+    noalloc_norm = timed(lambda: gs.gs_grad_sqnorm_noalloc(grads, 0, n, sq), args.steps)
     del acc
 
     # speculative single pass (c = 1 step + norm in one read of the gradients), out of place with
@@ -737,72 +929,173 @@ def main():
         A_, B_ = B_, A_
         es[i + 1].record()
     torch.cuda.synchronize()
-    spec_ms = es[0].elapsed_time(es[-1]) / args.steps
+    spec_l = [es[i].elapsed_time(es[i + 1]) for i in range(args.steps)]
+    if A_[0] is not p:                       # leave the states in the caller-visible p, m, v
+        for dst, src in zip((p, m, v), A_):
+            dst.copy_(src)
     del B_, A_
-    # what this device gives a plain device-to-device copy of one state array (read + written bytes):
-    # the practical ceiling for a kernel that, like the step, both reads and writes
+
+    # what this device gives simpler traffic, and the step's own mix of streams without arithmetic
     cp_dst = torch.empty_like(p)
-    copy_ms = timed(lambda: cp_dst.copy_(p), max(4, args.steps))
+    copy_ms = _stats(timed(lambda: cp_dst.copy_(p), max(4, args.steps // 2)))["avg_ms"]
     del cp_dst
     copy_gbs = 8 * n / (copy_ms * 1e-3) / 1e9
-    step_bytes = n * (2 * k + 26)
-    norm_bytes = n * 2 * k
-    achieved = step_bytes / (step_ms * 1e-3) / 1e9
-    out = {
-        "metric": "params/s, fused grad-norm + accumulate + AdamW step",
-        "value": n * args.steps / elapsed,
-        "unit": "params/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": elapsed / args.steps * 1e3,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "f32",
-        "data": "synthetic",
-        "config": {"workload": wl.name, "h": wl.h, "layers": wl.layers, "n_params": n, "k_grad_buffers": k,
-                   "grad_dtype": "bf16", "state_dtype": "f32", "clip_max_norm": wl.max_grad_norm,
-                   "device": props.name, "compute_units": props.multi_processor_count,
-                   "hbm_bytes": props.total_memory, "input_gen_s": round(t_gen, 2)},
-        "roofline": {"bound": "hbm", "kernel": "gs_accum_adamw", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
-                     "algorithmic_bytes_per_launch": step_bytes, "avg_launch_ms": step_ms,
-                     "params_per_s": n / (step_ms * 1e-3),
-                     "achievable": {"device_copy_GBps": copy_gbs, "frac_of_device_copy": achieved / copy_gbs,
-                                    "read_only_GBps": n * 4 / (acc_norm_ms * 1e-3) / 1e9,
-                                    "frac_of_read_only": achieved / (n * 4 / (acc_norm_ms * 1e-3) / 1e9),
-                                    "note": "measured here after the timed region: a device-to-device copy of one fp32 "
-                                            "state array (bytes read + written) and a read-only pass (gs_acc_sqnorm)"}},
-        "kernels": {
-            "gs_accum_adamw": {"avg_ms": step_ms, "bytes_per_param": 2 * k + 26, "GBps": achieved},
-            "gs_grad_sqnorm": {"avg_ms": norm_ms, "bytes_per_param": 2 * k,
-                               "GBps": norm_bytes / (norm_ms * 1e-3) / 1e9,
-                               "frac": norm_bytes / (norm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
-        },
-        "staged_two_pass": {
-            "params_per_s": n * args.steps / staged_elapsed, "ms_per_step": staged_elapsed / args.steps * 1e3,
-            "gs_grad_accum_sqnorm": {"avg_ms": st_norm_ms, "bytes_per_param": 2 * k + 4,
-                                     "GBps": n * (2 * k + 4) / (st_norm_ms * 1e-3) / 1e9},
-            "gs_adamw_from_acc": {"avg_ms": st_step_ms, "bytes_per_param": 30,
-                                  "GBps": n * 30 / (st_step_ms * 1e-3) / 1e9},
-            "note": "same results bit for bit; (2k+4)+30 B/param in total instead of 2k+(2k+26)"},
-        "accumulate_as_you_go": {
-            "gs_accum_add_first": {"avg_ms": add_first_ms, "bytes_per_param": 6,
-                                   "GBps": n * 6 / (add_first_ms * 1e-3) / 1e9},
-            "gs_accum_add": {"avg_ms": add_ms, "bytes_per_param": 10, "GBps": n * 10 / (add_ms * 1e-3) / 1e9},
-            "gs_accum_add_with_norm": {"avg_ms": add_norm_ms, "bytes_per_param": 10,
-                                       "GBps": n * 10 / (add_norm_ms * 1e-3) / 1e9},
-            "gs_acc_sqnorm": {"avg_ms": acc_norm_ms, "bytes_per_param": 4, "GBps": n * 4 / (acc_norm_ms * 1e-3) / 1e9},
-            "note": "one call per micro-batch into the resident fp32 buffer; the step then runs gs_adamw_from_acc"},
-        "speculative_single_pass": {"avg_ms": spec_ms, "bytes_per_param": 2 * k + 26,
-                                    "GBps": step_bytes / (spec_ms * 1e-3) / 1e9, "params_per_s": n / (spec_ms * 1e-3),
-                                    "note": "gs_accum_adamw_spec, out of place, step with c=1 plus squared norm; "
-                                            "valid as the whole step only when no clipping turns out to be needed"},
-        "cpu_baseline": cpu,
-    }
-    print(json.dumps(out))
+    read_gbs = n * 4 / (_stats(acc_norm)["avg_ms"] * 1e-3) / 1e9
+    achieved = k_step["GBps"]
+    achievable = {"device_copy_GBps": copy_gbs, "frac_of_device_copy": achieved / copy_gbs,
+                  "read_only_GBps": read_gbs, "frac_of_read_only": achieved / read_gbs,
+                  "note": "measured here after the timed region: torch's device-to-device copy of one fp32 state array "
+                          "(bytes read + written), a read-only pass (gs_acc_sqnorm)"}
+    if not args.no_ceiling:
+        block = 128 if k >= 15 else 64           # the step kernel's own workgroup size for this k
+        mix = same_mix_ceiling(torch, grads, p, m, v, w, n, k, max(4, args.steps // 2), block)
+        achievable.update(mix)
+        achievable["frac_of_same_mix"] = achieved / mix["same_mix_ceiling_GBps"]
+        achievable["note"] += ("; and kernels with the step's own mix of streams and no arithmetic (probe/gs_mixprobe.hip): "
+                               "in the step kernel's shape, with all loads in flight, and as a read-only kernel running "
+                               "beside a write-only kernel on a second stream.  same_mix_ceiling is the best of the three")
+    out["roofline"]["achievable"] = achievable
+    out["staged_two_pass"] = {
+        "params_per_s": n * args.steps / staged_elapsed, "ms_per_step": staged_elapsed / args.steps * 1e3,
+        "gs_grad_accum_sqnorm": _kernel_entry([e[0].elapsed_time(e[1]) for e in ev2], 2 * k + 4, n),
+        "gs_adamw_from_acc": _kernel_entry([e[1].elapsed_time(e[2]) for e in ev2], 30, n),
+        "note": "same results bit for bit; (2k+4)+30 B/param in total instead of 2k+(2k+26)"}
+    out["accumulate_as_you_go"] = {
+        "gs_accum_add_first": _kernel_entry(add_first, 6, n), "gs_accum_add": _kernel_entry(add, 10, n),
+        "gs_accum_add_with_norm": _kernel_entry(add_norm, 10, n), "gs_acc_sqnorm": _kernel_entry(acc_norm, 4, n),
+        "note": "one call per micro-batch into the resident fp32 buffer; the step then runs gs_adamw_from_acc"}
+    out["no_alloc_norm"] = dict(_kernel_entry(noalloc_norm, 2 * k, n),
+                                note="gs_grad_sqnorm_noalloc: partials in the library's fixed device array")
+    sp = _kernel_entry(spec_l, 2 * k + 26, n)
+    sp.update({"params_per_s": n / (sp["avg_ms"] * 1e-3),
+               "note": "gs_accum_adamw_spec, out of place, step with c=1 plus squared norm; valid as the whole step only "
+                       "when no clipping turns out to be needed"})
+    out["speculative_single_pass"] = sp
+    out["cpu_baseline"] = cpu
+    return out
+
+
+def _brief(rec, keys):
+    return {k: rec[k] for k in keys if k in rec}
+
+
+def streamed_short(args):
+    """Short form of the host-resident workload (fewer layers and passes, same chunking and
+    pipeline).  Run FIRST in the process: the staged pipeline's rate depends on which hardware
+    queues the runtime gives the context's three streams, and streams created earlier in the
+    process change that assignment (upload and download on one queue halve the rate)."""
+    import gc
+
+    import torch
+
+    from paper_2512_17570_amd import inputs as I
+
+    res = {}
+    t0 = time.perf_counter()
+    r = bench_streamed(args, I.WORKLOADS["gpt65b_8layers_streamed_k8"], brief=True)
+    res["gpt65b_8layers_streamed_k8"] = {
+        "layers": r["config"]["layers"], "layers_in_workload": r["config"]["layers_in_workload"],
+        "n_params": r["config"]["n_params"], "passes_timed": r["steps"],
+        "staged": {"params_per_s": r["value"], "ms_per_pass": r["ms_per_step"],
+                   "GBps_per_direction": r["roofline"]["achieved"], "frac_of_link": r["roofline"]["frac"]},
+        "in_place": _brief(r["in_place"], ("params_per_s", "ms_per_step", "GBps_per_direction", "frac_of_link", "stream_cus")),
+        "link": _brief(r["roofline"], ("h2d_only_GBps", "d2h_only_GBps", "duplex_copy_probe_GBps_per_direction",
+                                       "params_per_s_bound")),
+        "note": "short form of --workload gpt65b_8layers_streamed_k8: fewer layers and passes, same chunking and pipeline; "
+                "run first in the process, before any other stream exists (the staged pipeline's rate depends on which "
+                "hardware queues its three streams are given)",
+        "wall_s": round(time.perf_counter() - t0, 1)}
+    del r
+    gc.collect()
+    torch.cuda.empty_cache()
+    return res["gpt65b_8layers_streamed_k8"]
+
+
+def other_workloads(args):
+    """The other configurations of the workload list, each in a short run, for the record that the
+    default invocation prints: the two smaller layers and the GPT-30B-shaped one (norm + step) and the
+    split step of the GPT-175B-shaped layer beside a GEMM (the host-resident one is streamed_short)."""
+    import gc
+
+    import torch
+
+    from paper_2512_17570_amd import inputs as I
+
+    res = {}
+
+    def free():
+        gc.collect()
+        torch.cuda.empty_cache()
+
+    for name in ("gpt_h1024_k4", "gpt_h4096_k8", "gpt30b_layer_h7168_k16"):
+        t0 = time.perf_counter()
+        r = bench_resident(args, I.WORKLOADS[name], full=False)
+        res[name] = {"params_per_s": r["value"], "ms_per_step": r["ms_per_step"], "n_params": r["config"]["n_params"],
+                     "k": r["config"]["k_grad_buffers"], "cache_protocol": r["config"]["cache_protocol"],
+                     "per_step": r["timing"]["per_step"], "kernels": r["kernels"], "wall_s": None}
+        if "warm_cache_reference" in r:
+            res[name]["warm_cache_reference"] = r["warm_cache_reference"]
+        res[name]["wall_s"] = round(time.perf_counter() - t0, 1)
+        del r
+        free()
+    t0 = time.perf_counter()
+    r = bench_split(args, I.WORKLOADS["gpt175b_layer_h12288_k8_split"], brief=True)
+    sp = r["split"]
+    res["gpt175b_layer_h12288_k8_split"] = {
+        "n_params": r["config"]["n_params"], "k": r["config"]["k_grad_buffers"], "split_point": r["config"]["split_point"],
+        "full_ms": sp["full_ms"], "immediate_ms": sp["immediate_ms"], "deferred_alone_ms": sp["deferred_alone_ms"],
+        "full_GBps": r["roofline"]["achieved"], "full_frac": r["roofline"]["frac"],
+        "split_vs_full": (sp["immediate_ms"] + sp["deferred_alone_ms"]) / sp["full_ms"],
+        "gemm": r["config"]["gemm"], "gemms_per_deferred_step": r["config"]["gemms_per_deferred_step"],
+        "gemm_alone_ms": sp["gemm_alone_ms"], "gemm_alone_TFLOPs": sp["gemm_alone_TFLOPs"],
+        "deferred_beside_gemm_ms": sp["deferred_concurrent_ms"], "gemm_beside_deferred_ms": sp["gemm_concurrent_ms"],
+        "deferred_slowdown": sp["deferred_slowdown"], "gemm_slowdown": sp["gemm_slowdown"],
+        "concurrent_wall_ms_per_iter": sp["concurrent_wall_ms_per_iter"], "serial_ms_per_iter": sp["serial_ms_per_iter"],
+        "wall_s": round(time.perf_counter() - t0, 1)}
+    del r
+    free()
+    return res
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build measures one GPU only (no sharding or collectives); --gpus {args.gpus} is not supported",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2512_17570_amd import gs  # noqa: F401  (fails loudly if libgs.so is missing)
+    from paper_2512_17570_amd import inputs as I
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    if args.workload not in I.WORKLOADS:
+        print(f"unknown workload {args.workload}; have {list(I.WORKLOADS)}", file=sys.stderr)
+        sys.exit(2)
+    wl = I.WORKLOADS[args.workload]
+    torch.cuda.set_device(0)
+    if "immediate_frac" in wl.extra:
+        rec = bench_split(args, wl)
+    elif "host_share" in wl.extra:
+        rec = bench_tiered(args, wl)
+    elif "chunk_elems" in wl.extra:
+        rec = bench_streamed(args, wl)
+    else:
+        others = wl.name == HEADLINE and not args.no_other_workloads
+        streamed = streamed_short(args) if others else None
+        rec = bench_resident(args, wl, full=True)
+        if others:
+            import gc
+            gc.collect()
+            torch.cuda.empty_cache()
+            t0 = time.perf_counter()
+            rec["other_workloads"] = other_workloads(args)
+            rec["other_workloads"]["gpt65b_8layers_streamed_k8"] = streamed
+            rec["other_workloads"]["wall_s"] = round(time.perf_counter() - t0 + streamed["wall_s"], 1)
+    print(json.dumps(rec))
 
 
 if __name__ == "__main__":
