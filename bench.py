@@ -429,6 +429,7 @@ def bench_streamed(args, wl, brief=False):
 
     # the configuration as named: 2^26-element chunks, upload | kernel in an HBM slot | download
     ctx = gs.gs_stream_ctx_create(chunk, args.slots)
+    copies_overlap = gs.gs_stream_ctx_copies_overlap(ctx)
     per = timed_passes(ctx)
     gs.gs_stream_ctx_destroy(ctx)
     # the same passes with the kernel in place on the pinned host arrays: reported beside `value`
@@ -442,7 +443,7 @@ def bench_streamed(args, wl, brief=False):
     hip = ctypes.CDLL(os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so"))
     hip.hipMemcpyAsync.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
     hip.hipMemcpyAsync.restype = ctypes.c_int
-    up, dn = torch.cuda.Stream(), torch.cuda.Stream()
+    up, dn = concurrent_streams(torch, 2)          # two streams on different hardware queues
     stage = [torch.empty(chunk, dtype=torch.float32, device=dev) for _ in range(2)]
     stage[1].zero_()
 
@@ -469,7 +470,8 @@ def bench_streamed(args, wl, brief=False):
     rec = _base_record(wl, props, n / per, steps, warmup, per * 1e3,
                        {"layers": layers, "layers_in_workload": wl.layers, "n_params": n, "chunk_elems": chunk,
                         "slots": args.slots,
-                        "host_pinned_bytes": 12 * n, "device_staging_bytes": args.slots * 3 * (chunk + 64) * 4})
+                        "host_pinned_bytes": 12 * n, "device_staging_bytes": args.slots * 3 * (chunk + 64) * 4,
+                        "copies_overlap_check": copies_overlap})
     pcie_dir = 12 * n / per / 1e9
     link = min(h2d_only_gbs, d2h_only_gbs)
     rec["roofline"] = {"bound": "pcie", "kernel": "gs_stream_layer_step, staged (H2D 12 B + D2H 12 B per parameter)",
@@ -752,8 +754,7 @@ def same_mix_ceiling(torch, grads, p, m, v, w, n, k, reps, block):
            "read_half_alone_GBps": n4 * (2 * k + 12) / (r_ms * 1e-3) / 1e9,
            "write_half_alone_GBps": n4 * 14 / (w_ms * 1e-3) / 1e9,
            "read_then_write_serial_GBps": total / ((r_ms + w_ms) * 1e-3) / 1e9}
-    res["same_mix_ceiling_GBps"] = max(res["same_mix_step_shape_GBps"], res["same_mix_all_loads_in_flight_GBps"],
-                                       res["same_mix_read_kernel_beside_write_kernel_GBps"])
+    res["same_mix_ceiling_GBps"] = max(res["same_mix_step_shape_GBps"], res["same_mix_all_loads_in_flight_GBps"])
     return res
 
 
@@ -951,9 +952,11 @@ def bench_resident(args, wl, full=True):
         mix = same_mix_ceiling(torch, grads, p, m, v, w, n, k, max(4, args.steps // 2), block)
         achievable.update(mix)
         achievable["frac_of_same_mix"] = achieved / mix["same_mix_ceiling_GBps"]
+        achievable["frac_of_read_kernel_beside_write_kernel"] = achieved / mix["same_mix_read_kernel_beside_write_kernel_GBps"]
         achievable["note"] += ("; and kernels with the step's own mix of streams and no arithmetic (probe/gs_mixprobe.hip): "
-                               "in the step kernel's shape, with all loads in flight, and as a read-only kernel running "
-                               "beside a write-only kernel on a second stream.  same_mix_ceiling is the best of the three")
+                               "in the step kernel's shape and with all loads in flight (same_mix_ceiling = the better of "
+                               "the two single kernels), and split into a read-only kernel running beside a write-only "
+                               "kernel on a second stream (the same bytes issued from separate workgroups)")
     out["roofline"]["achievable"] = achievable
     out["staged_two_pass"] = {
         "params_per_s": n * args.steps / staged_elapsed, "ms_per_step": staged_elapsed / args.steps * 1e3,
@@ -997,6 +1000,7 @@ def streamed_short(args):
         "layers": r["config"]["layers"], "layers_in_workload": r["config"]["layers_in_workload"],
         "n_params": r["config"]["n_params"], "passes_timed": r["steps"],
         "staged": {"params_per_s": r["value"], "ms_per_pass": r["ms_per_step"],
+                   "copies_overlap_check": r["config"]["copies_overlap_check"],
                    "GBps_per_direction": r["roofline"]["achieved"], "frac_of_link": r["roofline"]["frac"]},
         "in_place": _brief(r["in_place"], ("params_per_s", "ms_per_step", "GBps_per_direction", "frac_of_link", "stream_cus")),
         "link": _brief(r["roofline"], ("h2d_only_GBps", "d2h_only_GBps", "duplex_copy_probe_GBps_per_direction",

@@ -295,6 +295,17 @@ typedef struct gs_stream_ctx gs_stream_ctx;
 gs_status gs_stream_ctx_create(gs_stream_ctx **out, int64_t chunk_elems, int slots);
 
 /*
+ * What a staged context found when it was created.  The pipeline of Sec. 4.3 only pays if uploads
+ * and downloads run at the same time, but the runtime may put the two copy streams on one
+ * hardware queue, where they take turns (half the rate).  gs_stream_ctx_create therefore times a
+ * short burst of copies each way, alone and together, and swaps the download stream for a fresh
+ * one (up to six times) while the two still take turns.  Returns 1 if the copies ran side by side
+ * in the end, 0 if they still took turns, -1 if the check was skipped (slots under 1 MB, in-place
+ * context) or ctx is NULL.  No HIP call.
+ */
+int gs_stream_ctx_copies_overlap(const gs_stream_ctx *ctx);
+
+/*
  * In place: the context owns one stream, and the step kernel runs on the pinned host arrays
  * themselves -- each wave loads its tile of p, m, v over the link, updates it and stores it
  * back.  Nothing is staged in device memory and no copy engine is used: 44-45 GB/s each way,

@@ -24,6 +24,7 @@
 // device-resident step.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -177,6 +178,71 @@ static gs_status staged_chunk(gs_stream_ctx *c, StepArgs &A, float *host_p, floa
 
 }  // namespace gs
 
+// Staged mode lives on its upload and download copies running at the same time.  HIP multiplexes a
+// process's streams onto a few hardware queues, and when the two copy streams share one, the two
+// directions take turns: half the rate, with nothing else to show for it.  Which queue a new stream
+// gets depends on the streams the process already has, so the context checks: a burst of uploads
+// and a burst of downloads of `bytes` each, timed one after the other and then together (the
+// download stream released by an event on the upload stream).  Together in clearly less than the
+// sum means side by side.  Returns 1 (side by side), 0 (in turns) or -1 (a HIP call failed; the
+// error text is set).
+static int copies_run_side_by_side(hipStream_t up, hipStream_t down, float *dev, float *host, size_t bytes)
+{
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    int verdict = -1;
+    float t_up = 0.f, t_down = 0.f, t_a = 0.f, t_b = 0.f;
+    char *d = reinterpret_cast<char *>(dev), *h = reinterpret_cast<char *>(host);
+    const int reps = 2;
+    auto fail = [&](hipError_t e, const char *what) {
+        hip_fail(e, what);
+        return -1;
+    };
+    hipError_t e = hipSuccess;
+    for (auto &x : ev)
+        if ((e = hipEventCreateWithFlags(&x, 0)) != hipSuccess) {
+            x = nullptr;
+            verdict = fail(e, "hipEventCreateWithFlags(copy check)");
+            goto done;
+        }
+    // warm both paths, then each direction alone
+    if ((e = hipMemcpyAsync(d, h, bytes, hipMemcpyHostToDevice, up)) != hipSuccess ||
+        (e = hipMemcpyAsync(h + bytes, d + bytes, bytes, hipMemcpyDeviceToHost, down)) != hipSuccess ||
+        (e = hipStreamSynchronize(up)) != hipSuccess || (e = hipStreamSynchronize(down)) != hipSuccess) {
+        verdict = fail(e, "copy check (warm-up)");
+        goto done;
+    }
+    if ((e = hipEventRecord(ev[0], up)) != hipSuccess) { verdict = fail(e, "hipEventRecord(copy check)"); goto done; }
+    for (int r = 0; r < reps; ++r)
+        if ((e = hipMemcpyAsync(d, h, bytes, hipMemcpyHostToDevice, up)) != hipSuccess) { verdict = fail(e, "hipMemcpyAsync(copy check)"); goto done; }
+    if ((e = hipEventRecord(ev[1], up)) != hipSuccess || (e = hipStreamSynchronize(up)) != hipSuccess ||
+        (e = hipEventElapsedTime(&t_up, ev[0], ev[1])) != hipSuccess) { verdict = fail(e, "copy check (upload alone)"); goto done; }
+    if ((e = hipEventRecord(ev[2], down)) != hipSuccess) { verdict = fail(e, "hipEventRecord(copy check)"); goto done; }
+    for (int r = 0; r < reps; ++r)
+        if ((e = hipMemcpyAsync(h + bytes, d + bytes, bytes, hipMemcpyDeviceToHost, down)) != hipSuccess) { verdict = fail(e, "hipMemcpyAsync(copy check)"); goto done; }
+    if ((e = hipEventRecord(ev[3], down)) != hipSuccess || (e = hipStreamSynchronize(down)) != hipSuccess ||
+        (e = hipEventElapsedTime(&t_down, ev[2], ev[3])) != hipSuccess) { verdict = fail(e, "copy check (download alone)"); goto done; }
+    // both at once
+    if ((e = hipEventRecord(ev[0], up)) != hipSuccess || (e = hipStreamWaitEvent(down, ev[0], 0)) != hipSuccess) { verdict = fail(e, "copy check (start)"); goto done; }
+    for (int r = 0; r < reps; ++r)
+        if ((e = hipMemcpyAsync(d, h, bytes, hipMemcpyHostToDevice, up)) != hipSuccess ||
+            (e = hipMemcpyAsync(h + bytes, d + bytes, bytes, hipMemcpyDeviceToHost, down)) != hipSuccess) { verdict = fail(e, "hipMemcpyAsync(copy check)"); goto done; }
+    if ((e = hipEventRecord(ev[1], up)) != hipSuccess || (e = hipEventRecord(ev[3], down)) != hipSuccess ||
+        (e = hipStreamSynchronize(up)) != hipSuccess || (e = hipStreamSynchronize(down)) != hipSuccess ||
+        (e = hipEventElapsedTime(&t_a, ev[0], ev[1])) != hipSuccess || (e = hipEventElapsedTime(&t_b, ev[0], ev[3])) != hipSuccess) {
+        verdict = fail(e, "copy check (both)");
+        goto done;
+    }
+    {
+        const float both = t_a > t_b ? t_a : t_b;
+        // too short to tell (a runtime without a clock, tiny slots): take the streams as they are
+        verdict = (t_up + t_down < 0.05f) ? 1 : (both < 0.8f * (t_up + t_down) ? 1 : 0);
+    }
+done:
+    for (auto x : ev)
+        if (x) (void)hipEventDestroy(x);
+    return verdict;
+}
+
 // the compute stream and the producer event, common to both modes
 static gs_status create_common(gs_stream_ctx *c, int num_cus)
 {
@@ -273,6 +339,40 @@ gs_status gs_stream_ctx_create(gs_stream_ctx **out, int64_t chunk_elems, int slo
         destroy_partial(c);
         return GS_ERR_NOMEM;
     }
+    // Make sure upload and download really overlap; if they take turns, try further download streams
+    // (the rejected ones stay alive meanwhile, so each new one is handed another hardware queue).
+    const size_t probe_bytes = std::min<size_t>((size_t)64 << 20, bytes / 2) & ~(size_t)255;
+    if (probe_bytes >= ((size_t)1 << 20)) {
+        void *host = nullptr;
+        e = hipHostMalloc(&host, 2 * probe_bytes, hipHostMallocDefault);
+        if (e != hipSuccess) {
+            hip_fail(e, "hipHostMalloc(copy check)");
+            (void)hipGetLastError();
+            destroy_partial(c);
+            return GS_ERR_NOMEM;
+        }
+        memset(host, 0, 2 * probe_bytes);
+        std::vector<hipStream_t> rejected;
+        int verdict = copies_run_side_by_side(c->s_h2d, c->s_d2h, c->pool, static_cast<float *>(host), probe_bytes);
+        for (int attempt = 0; verdict == 0 && attempt < 6; ++attempt) {
+            hipStream_t cand = nullptr;
+            if ((e = hipStreamCreateWithFlags(&cand, hipStreamNonBlocking)) != hipSuccess) {
+                hip_fail(e, "hipStreamCreateWithFlags");
+                verdict = -1;
+                break;
+            }
+            rejected.push_back(c->s_d2h);
+            c->s_d2h = cand;
+            verdict = copies_run_side_by_side(c->s_h2d, c->s_d2h, c->pool, static_cast<float *>(host), probe_bytes);
+        }
+        for (hipStream_t r : rejected) (void)hipStreamDestroy(r);
+        (void)hipHostFree(host);
+        if (verdict < 0) {
+            destroy_partial(c);
+            return GS_ERR_HIP;
+        }
+        c->copies_overlap = verdict;
+    }
     c->ev_h2d.assign(slots, nullptr);
     c->ev_comp.assign(slots, nullptr);
     c->ev_d2h.assign(slots, nullptr);
@@ -288,6 +388,8 @@ gs_status gs_stream_ctx_create(gs_stream_ctx **out, int64_t chunk_elems, int slo
     *out = c;
     return GS_OK;
 }
+
+int gs_stream_ctx_copies_overlap(const gs_stream_ctx *c) { return c ? c->copies_overlap : -1; }
 
 gs_status gs_stream_ctx_sync(gs_stream_ctx *c)
 {

@@ -99,6 +99,8 @@ _lib.gs_stream_ctx_create_inplace.argtypes = [ctypes.POINTER(_vp), ctypes.c_int]
 _lib.gs_stream_ctx_create.argtypes = [ctypes.POINTER(_vp), _i64, ctypes.c_int]
 _lib.gs_stream_ctx_create.restype = ctypes.c_int
 _lib.gs_stream_ctx_create_inplace.restype = ctypes.c_int
+_lib.gs_stream_ctx_copies_overlap.argtypes = [_vp]
+_lib.gs_stream_ctx_copies_overlap.restype = ctypes.c_int
 _lib.gs_stream_ctx_destroy.argtypes = [_vp]
 _lib.gs_stream_ctx_destroy.restype = ctypes.c_int
 _lib.gs_stream_ctx_sync.argtypes = [_vp]
@@ -331,6 +333,10 @@ def gs_stream_ctx_create(chunk_elems: int, slots: int = 3, check: bool = True):
         _check(st, "gs_stream_ctx_create", True)
         return out.value
     return st, out.value
+
+
+def gs_stream_ctx_copies_overlap(ctx) -> int:
+    return int(_lib.gs_stream_ctx_copies_overlap(ctx))
 
 
 def gs_stream_ctx_destroy(ctx, check: bool = True) -> int:
