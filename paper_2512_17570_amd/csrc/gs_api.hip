@@ -168,13 +168,43 @@ static float clip_coefficient_host(double sqnorm_total, float max_norm)
     return c < 1.0f ? c : 1.0f;
 }
 
-static bool alias_ok(const float *in, const float *out, int64_t end)
+// Byte range of elements [begin,end) of an array.
+struct ByteRange {
+    uintptr_t lo, hi;
+};
+static ByteRange range_of(const void *base, int64_t begin, int64_t end, size_t elem)
 {
-    // an output may be its own input, or must not overlap it at all
-    if (in == out) return true;
-    const uintptr_t a = reinterpret_cast<uintptr_t>(in), b = reinterpret_cast<uintptr_t>(out);
-    const uintptr_t bytes = (uintptr_t)end * sizeof(float);
-    return a + bytes <= b || b + bytes <= a;
+    const uintptr_t a = reinterpret_cast<uintptr_t>(base);
+    return {a + (uintptr_t)begin * elem, a + (uintptr_t)end * elem};
+}
+static bool overlap(const ByteRange &x, const ByteRange &y) { return x.lo < y.hi && y.lo < x.hi; }
+
+// Every output (p_out, m_out, v_out, w) against every input and every other output: an output may
+// be exactly its own input (the in-place entry points), anything else that overlaps is rejected --
+// a wave would read elements another wave has already overwritten.
+static bool aliasing_ok(const float *p, const float *m, const float *v, const float *po, const float *mo,
+                        const float *vo, const uint16_t *w, const uint16_t *const *grads, int k, const float *acc,
+                        int64_t begin, int64_t end)
+{
+    const ByteRange out[4] = {range_of(po, begin, end, 4), range_of(mo, begin, end, 4), range_of(vo, begin, end, 4),
+                              range_of(w, begin, end, 2)};
+    const void *own_in[4] = {p, m, v, nullptr};
+    const void *out_ptr[4] = {po, mo, vo, w};
+    for (int a = 0; a < 4; ++a)
+        for (int b = a + 1; b < 4; ++b)
+            if (overlap(out[a], out[b])) return false;
+    const void *in_ptr[3] = {p, m, v};
+    for (int o = 0; o < 4; ++o) {
+        for (int i = 0; i < 3; ++i) {
+            if (in_ptr[i] == out_ptr[o] && own_in[o] == in_ptr[i]) continue;      // in place
+            if (overlap(out[o], range_of(in_ptr[i], begin, end, 4))) return false;
+        }
+        if (acc && overlap(out[o], range_of(acc, begin, end, 4))) return false;
+        if (!acc)
+            for (int j = 0; j < k; ++j)
+                if (overlap(out[o], range_of(grads[j], begin, end, 2))) return false;
+    }
+    return true;
 }
 
 // spec_norm_out != nullptr: speculative pass (c = 1, squared norm reduced into *spec_norm_out)
@@ -194,7 +224,7 @@ static gs_status adamw_impl(const float *p, const float *m, const float *v, floa
         if (sg != GS_OK) return sg;
     }
     if (begin < 0 || end < begin) return GS_ERR_INVALID_ARG;
-    if (!alias_ok(p, po, end) || !alias_ok(m, mo, end) || !alias_ok(v, vo, end)) return GS_ERR_INVALID_ARG;
+    if (!aliasing_ok(p, m, v, po, mo, vo, w_bf16, grads, k, acc, begin, end)) return GS_ERR_INVALID_ARG;
     gs_status st = validate_hparams(hp);
     if (st != GS_OK) return st;
     if (d_sqnorm && (reinterpret_cast<uintptr_t>(d_sqnorm) & 7u)) return GS_ERR_INVALID_ARG;

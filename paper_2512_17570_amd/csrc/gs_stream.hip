@@ -4,19 +4,20 @@
 // optimizer states, step, write them back (Sec. 2.2), pipelined against the surrounding work
 // (Sec. 4.3).  There the slow link is SSD<->host; here it is host<->HBM over PCIe.  Two ways:
 //
-// In place (the default).  The step kernel runs on the pinned host arrays themselves, so every
+// In place (gs_stream_ctx_create_inplace).  The step kernel runs on the pinned host arrays themselves, so every
 // wave loads its tile of p/m/v over the link, updates it and stores it back, thousands of waves
 // at different stages at any time.  Nothing is staged in HBM and no copy engine is involved.
 // Measured on MI355X (GPT-65B-shaped layers, k = 8): 44-45 GB/s each way at once, the same on a
 // stream confined to 16 of the 256 CUs, and the same whatever copy traffic the process ran
 // before.
 //
-// Staged.  Chunk c+1 is uploaded by hipMemcpyAsync into one of `slots` staging slots in HBM while
+// Staged (gs_stream_ctx_create).  Chunk c+1 is uploaded by hipMemcpyAsync into one of `slots` staging slots in HBM while
 // the kernel updates chunk c there and chunk c-1 is copied back: three streams, events per slot.
 // It costs no CU time beyond the 0.5 ms kernel per chunk and reached 48 GB/s each way at its
 // best, but its rate is in the runtime's hands: which copy path a copy takes (under the file
 // tier's load its device-to-host copies were seen on the DMA engine at 12.8 GB/s) and which
-// hardware queue a stream lands on (upload and download on one queue: 28 GB/s each way).
+// hardware queue a stream lands on (upload and download on one queue: 28 GB/s each way; the
+// context checks for that when it is created and swaps the download stream until the two overlap).
 //
 // Either way the kernel is the resident one, handed base pointers such that base[i] is element i
 // of the layer (staged: chunk [b,e) sits at offset (b mod 8) of its slot), so its 4-element

@@ -12,6 +12,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "gs.h")
 
 FAKE = 0x10000          # non-null, 16-byte aligned; never dereferenced by a rejected call
+# distinct, far-apart fake arrays (p, m, v, w, two gradient buffers, staged sum): a valid call must not alias
+FP, FM, FV, FW, FG0, FG1, FACC = (FAKE + i * (1 << 24) for i in range(1, 8))
 GOOD_HP = gs.HParams(step=3)
 
 
@@ -57,7 +59,7 @@ def test_strerror_and_workspace():
 
 
 def _adamw(**kw):
-    a = dict(p=FAKE, m=FAKE, v=FAKE, w_bf16=FAKE, grads=[FAKE, FAKE], begin=0, end=100, hp=GOOD_HP,
+    a = dict(p=FP, m=FM, v=FV, w_bf16=FW, grads=[FG0, FG1], begin=0, end=100, hp=GOOD_HP,
              d_sqnorm=None, stream=0, check=False)
     a.update(kw)
     return gs.gs_accum_adamw(**a)
@@ -65,7 +67,7 @@ def _adamw(**kw):
 
 @pytest.mark.parametrize("kw", [
     dict(p=None), dict(m=None), dict(v=None), dict(w_bf16=None),
-    dict(p=FAKE + 4), dict(w_bf16=FAKE + 2), dict(m=FAKE + 8),
+    dict(p=FP + 4), dict(w_bf16=FW + 2), dict(m=FM + 8),
     dict(grads=None, k=2), dict(grads=[FAKE], k=0), dict(grads=[FAKE] * 33),
     dict(grads=[FAKE, None]), dict(grads=[FAKE, FAKE + 2]),
     dict(begin=-1), dict(begin=10, end=9),
@@ -80,6 +82,15 @@ def _adamw(**kw):
 ])
 def test_accum_adamw_rejects(kw):
     assert _adamw(**kw) == gs.GS_ERR_INVALID_ARG
+
+
+def test_baseline_arguments_of_the_rejection_tests_are_valid():
+    """The calls the rejection tests start from pass every check: without a GPU they get as far as
+    the launch and come back as GS_ERR_HIP, so each rejection above is caused by the one argument
+    that test changed."""
+    assert _adamw() == gs.GS_ERR_HIP
+    assert _sqnorm() == gs.GS_ERR_HIP
+    assert gs.gs_last_hip_error() != ""
 
 
 def test_accum_adamw_empty_range_is_ok_without_gpu():
@@ -194,9 +205,9 @@ def test_staged_variant_rejects_without_gpu():
                      (dict(workspace_bytes=8), gs.GS_ERR_WORKSPACE), (dict(d_sqnorm=None), gs.GS_ERR_INVALID_ARG)):
         assert gs.gs_grad_accum_sqnorm(**{**ok, **kw}) == want
     assert gs.gs_grad_accum_sqnorm(**{**ok, "begin": 5, "end": 5, "accumulate": True}) == gs.GS_OK
-    ok2 = dict(p=FAKE, m=FAKE, v=FAKE, w_bf16=FAKE, acc_f32=FAKE, begin=0, end=64, hp=GOOD_HP, d_sqnorm=None,
+    ok2 = dict(p=FP, m=FM, v=FV, w_bf16=FW, acc_f32=FACC, begin=0, end=64, hp=GOOD_HP, d_sqnorm=None,
                stream=0, check=False)
-    for kw in (dict(acc_f32=None), dict(acc_f32=FAKE + 8), dict(p=None), dict(hp=gs.HParams(step=0)),
+    for kw in (dict(acc_f32=None), dict(acc_f32=FACC + 8), dict(p=None), dict(hp=gs.HParams(step=0)),
                dict(begin=-1), dict(d_sqnorm=FAKE + 4)):
         assert gs.gs_adamw_from_acc(**{**ok2, **kw}) == gs.GS_ERR_INVALID_ARG
     assert gs.gs_adamw_from_acc(**{**ok2, "begin": 7, "end": 7}) == gs.GS_OK
@@ -204,21 +215,53 @@ def test_staged_variant_rejects_without_gpu():
 
 def test_speculative_and_oop_reject_without_gpu():
     ws = gs.gs_sqnorm_workspace_bytes()
-    F2 = FAKE + (1 << 20)
-    oop = dict(p=FAKE, m=FAKE, v=FAKE, p_out=F2, m_out=F2, v_out=F2, w_bf16=FAKE, grads=[FAKE], begin=0, end=64,
+    PO, MO, VO = (FACC + i * (1 << 24) for i in range(1, 4))
+    oop = dict(p=FP, m=FM, v=FV, p_out=PO, m_out=MO, v_out=VO, w_bf16=FW, grads=[FG0], begin=0, end=64,
                hp=GOOD_HP, d_sqnorm=None, stream=0, check=False)
     assert gs.gs_accum_adamw_oop(**{**oop, "begin": 4, "end": 4}) == gs.GS_OK
-    for kw in (dict(p_out=None), dict(m_out=FAKE + 4), dict(p_out=FAKE + 64),       # partial overlap with p
-               dict(v_out=FAKE - 128), dict(grads=[FAKE] * 33), dict(hp=None), dict(begin=5, end=1)):
+    for kw in (dict(p_out=None), dict(m_out=FM + 4), dict(p_out=FP + 64),       # partial overlap with p
+               dict(v_out=FV - 128), dict(grads=[FG0] * 33), dict(hp=None), dict(begin=5, end=1)):
         assert gs.gs_accum_adamw_oop(**{**oop, **kw}) == gs.GS_ERR_INVALID_ARG, kw
-    assert gs.gs_accum_adamw_oop(**{**oop, "p_out": FAKE, "m_out": FAKE, "v_out": FAKE, "begin": 9, "end": 9}) == gs.GS_OK
-    spec = dict(p=FAKE, m=FAKE, v=FAKE, p_out=F2, m_out=F2, v_out=F2, w_bf16=FAKE, grads=[FAKE], begin=0, end=64,
+    assert gs.gs_accum_adamw_oop(**{**oop, "p_out": FP, "m_out": FM, "v_out": FV, "begin": 9, "end": 9}) == gs.GS_OK
+    spec = dict(p=FP, m=FM, v=FV, p_out=PO, m_out=MO, v_out=VO, w_bf16=FW, grads=[FG0], begin=0, end=64,
                 hp=GOOD_HP, d_sqnorm=FAKE, d_workspace=FAKE, workspace_bytes=ws, stream=0, check=False)
     for kw, want in ((dict(d_sqnorm=None), gs.GS_ERR_INVALID_ARG), (dict(d_sqnorm=FAKE + 4), gs.GS_ERR_INVALID_ARG),
                      (dict(d_workspace=None), gs.GS_ERR_WORKSPACE), (dict(workspace_bytes=64), gs.GS_ERR_WORKSPACE),
-                     (dict(p_out=FAKE + 16), gs.GS_ERR_INVALID_ARG), (dict(v=None), gs.GS_ERR_INVALID_ARG)):
+                     (dict(p_out=FP + 16), gs.GS_ERR_INVALID_ARG), (dict(v=None), gs.GS_ERR_INVALID_ARG)):
         assert gs.gs_accum_adamw_spec(**{**spec, **kw}) == want, kw
     assert gs.gs_accum_adamw_spec(**{**spec, "begin": 3, "end": 3, "accumulate": True}) == gs.GS_OK
+
+
+def test_overlapping_inputs_and_outputs_are_rejected():
+    """An output may be exactly its own input; any other overlap between an output and an input, or
+    between two outputs, over the bytes of [begin,end) is refused before anything is enqueued."""
+    n = 1000
+    A, B, C, W, G, X = (FAKE + i * (1 << 20) for i in range(6))
+    oop = dict(p=A, m=B, v=C, p_out=A, m_out=B, v_out=C, w_bf16=W, grads=[G], begin=0, end=n, hp=GOOD_HP,
+               d_sqnorm=None, stream=0, check=False)
+    ok_empty = {**oop, "begin": 5, "end": 5}
+    assert gs.gs_accum_adamw_oop(**ok_empty) == gs.GS_OK
+    bad = [dict(p_out=B),                     # p_out over m (an input that is not its own)
+           dict(m_out=A, p_out=X),            # m_out over p
+           dict(v_out=A + 64, p_out=X),       # v_out partly over p
+           dict(w_bf16=A),                    # w over p
+           dict(w_bf16=C + 2 * n),            # w over the upper half of v's bytes
+           dict(p_out=X, m_out=X),            # two outputs on one array
+           dict(p_out=X, w_bf16=X + 16),      # w inside p_out
+           dict(grads=[A]),                   # a gradient buffer that is also a state being written
+           dict(grads=[G, W]),                # a gradient buffer that is also w
+           dict(p_out=G)]                     # p_out over a gradient buffer
+    for kw in bad:
+        assert gs.gs_accum_adamw_oop(**{**oop, **kw}) == gs.GS_ERR_INVALID_ARG, kw
+        assert gs.gs_accum_adamw_oop(**{**oop, **kw, "begin": 5, "end": 5}) in (gs.GS_OK, gs.GS_ERR_INVALID_ARG)
+    # ranges that do not touch each other are fine even when the arrays as a whole would overlap
+    assert gs.gs_accum_adamw(p=A, m=A + 4 * n, v=A + 8 * n, w_bf16=A + 12 * n, grads=[G], begin=0, end=0, hp=GOOD_HP,
+                             d_sqnorm=None, stream=0, check=False) == gs.GS_OK
+    # in place through the plain entry point, and the staged one with acc over a state
+    assert _adamw(p=A, m=B, v=C, w_bf16=W, grads=[G, G + (1 << 19)], begin=3, end=3) == gs.GS_OK
+    assert _adamw(p=A, m=A, v=C, w_bf16=W, grads=[G], end=n) == gs.GS_ERR_INVALID_ARG
+    assert gs.gs_adamw_from_acc(p=A, m=B, v=C, w_bf16=W, acc_f32=B, begin=0, end=n, hp=GOOD_HP, d_sqnorm=None, stream=0,
+                                check=False) == gs.GS_ERR_INVALID_ARG
 
 
 def test_host_clip_coefficient_matches_oracle():
