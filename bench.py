@@ -122,6 +122,25 @@ def _base_record(wl, props, value, steps, warmup, ms_per_step, extra_cfg=None):
             "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic", "config": cfg}
 
 
+def runs_beside(torch, a, b, big=None):
+    """True if work on stream b overtakes a burst already running on stream a (different hardware queues)."""
+    own = big is None
+    if own:
+        big = torch.zeros(1 << 28, dtype=torch.float32, device="cuda:0")
+    small = torch.zeros(1 << 10, dtype=torch.float32, device="cuda:0")
+    torch.cuda.synchronize()
+    e_long, e_short = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(a):
+        for _ in range(8):
+            big.add_(1.0)
+        e_long.record(a)
+    with torch.cuda.stream(b):
+        small.add_(1.0)
+        e_short.record(b)
+    torch.cuda.synchronize()
+    return e_short.elapsed_time(e_long) >= 0.5
+
+
 def concurrent_streams(torch, count=2, tries=24):
     """`count` torch streams that the runtime really runs side by side.  HIP multiplexes a process's
     streams onto a few hardware queues (4 here), and two streams that land on one queue run their
@@ -161,7 +180,8 @@ def concurrent_streams(torch, count=2, tries=24):
     return chosen
 
 
-def _layer_sequence(args, wl, gs, torch, dev, tokens, ga, gb, gc, sa, sb, deferred, t_def, cus):
+def _layer_sequence(args, wl, gs, torch, dev, tokens, ga, gb, gc, sa, step_args, t_def, cus):
+    p, m, v, w, grads, s_pt, n, sq = step_args
     # A sequence of layers (Sec. 4.4: a layer's deferred update only has to be finished before that
     # layer's forward of the next iteration): the forward of layer i (its four bf16 GEMMs for
     # `tokens` tokens) waits for the event of layer i's deferred step; the deferred steps run in
@@ -181,33 +201,41 @@ def _layer_sequence(args, wl, gs, torch, dev, tokens, ga, gb, gc, sa, sb, deferr
         torch.matmul(ga, w1, out=o_1)
         torch.matmul(o_1, w2, out=gc)
 
-    def sequence(step_stream, overlap, reps):
+    def sequence(num_cus, overlap, reps):
+        """One iteration = the deferred steps of all layers handed to a gs_defer_ctx (its own stream, on a
+        budget of num_cus compute units if > 0) and the forwards on `sa`, each behind its layer's deadline
+        (overlap) or behind the last layer's (serial)."""
+        # a context whose stream really runs beside the forward's stream (see concurrent_streams)
+        rejected, ctx = [], None
+        for _ in range(8):
+            ctx = gs.gs_defer_ctx_create(seq_layers, num_cus)
+            if runs_beside(torch, sa, torch.cuda.ExternalStream(gs.gs_defer_ctx_stream(ctx))):
+                break
+            rejected.append(ctx)
+        for r in rejected:
+            gs.gs_defer_ctx_destroy(r)
+        hp = _hp_of(gs, wl)
+
         def once():
-            evs = []
-            with torch.cuda.stream(step_stream):
-                for _ in range(seq_layers):
-                    deferred(step_stream)
-                    ev = torch.cuda.Event()
-                    ev.record(step_stream)
-                    evs.append(ev)
+            for i in range(seq_layers):
+                gs.gs_defer_layer_step(ctx, i, p, m, v, w, grads, s_pt, n, hp, sq, producer_stream=sa)
             with torch.cuda.stream(sa):
                 if not overlap:
-                    sa.wait_event(evs[-1])
+                    gs.gs_defer_wait_layer(ctx, seq_layers - 1, sa)
                 for i in range(seq_layers):
                     if overlap:
-                        sa.wait_event(evs[i])
+                        gs.gs_defer_wait_layer(ctx, i, sa)
                     forward_layer()
-            # the next iteration's steps follow this iteration's forward
-            done = torch.cuda.Event()
-            done.record(sa)
-            step_stream.wait_event(done)
+            # the next iteration's steps follow this iteration's forward (producer_stream = sa)
         once()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(reps):
             once()
         torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / reps * 1e3
+        dt = (time.perf_counter() - t0) / reps * 1e3
+        gs.gs_defer_ctx_destroy(ctx)
+        return dt
 
     with torch.cuda.stream(sa):
         for _ in range(2):
@@ -225,16 +253,13 @@ def _layer_sequence(args, wl, gs, torch, dev, tokens, ga, gb, gc, sa, sb, deferr
     seq = {"layers": seq_layers, "forward_ms_per_layer_alone": t_fwd_layer,
            "forward_TFLOPs_alone": 2.0 * tokens * wl.h * 12 * wl.h / (t_fwd_layer * 1e-3) / 1e12,
            "deferred_ms_per_layer_alone": t_def,
-           "serial_ms": sequence(sb, False, seq_reps),
-           "overlapped_all_cus_ms": sequence(sb, True, seq_reps)}
+           "serial_ms": sequence(0, False, seq_reps),
+           "overlapped_all_cus_ms": sequence(0, True, seq_reps)}
     for ncu in (cus // 4, cus // 2):
-        raw = gs.gs_cu_stream_create(ncu)
-        sc = torch.cuda.ExternalStream(raw)
-        seq[f"overlapped_{ncu}_cus_ms"] = sequence(sc, True, seq_reps)
-        del sc
-        gs.gs_cu_stream_destroy(raw)
+        seq[f"overlapped_{ncu}_cus_ms"] = sequence(ncu, True, seq_reps)
     seq["bound_ms"] = t_def + seq_layers * t_fwd_layer      # first step exposed, everything else hidden
-    seq["note"] = ("forward of layer i waits for layer i's deferred step; steps run in layer order on their own stream. "
+    seq["note"] = ("gs_defer_ctx: forward of layer i waits for layer i's deadline (gs_defer_wait_layer); steps run in layer "
+                   "order on the context's stream. "
                    "bound = one exposed deferred step + the forwards at their solo speed")
 
     return seq
@@ -341,7 +366,7 @@ def bench_split(args, wl, brief=False):
         gs.gs_cu_stream_destroy(raw)
     seq = None
     if not brief:
-        seq = _layer_sequence(args, wl, gs, torch, dev, tokens, ga, gb, gc, sa, sb, deferred, t_def, cus)
+        seq = _layer_sequence(args, wl, gs, torch, dev, tokens, ga, gb, gc, sa, (p, m, v, w, grads, s_pt, n, sq), t_def, cus)
 
     bpp = 2 * k + 26
     rec = _base_record(wl, props, n / ((t_imm + t_def) * 1e-3), args.steps, args.warmup, t_imm + t_def,

@@ -271,6 +271,41 @@ float gs_clip_coefficient(double sqnorm_total, float max_grad_norm);
 gs_status gs_cu_stream_create(void **stream, int num_cus);
 gs_status gs_cu_stream_destroy(void *stream);
 
+/*
+ * The deferred part of each layer's step as a schedule with per-layer deadlines (Sec. 4.4: the
+ * delayed alpha share of a layer's update runs during the next iteration's forward pass and has to
+ * be finished before that layer executes).  A context owns one stream -- confined to `num_cus`
+ * compute units as from gs_cu_stream_create, or unconfined with num_cus = 0 -- on which the
+ * deferred ranges run in the order they are handed over, and one event per layer
+ * (0 <= layer < max_layers <= 65536).
+ *   gs_defer_layer_step   gs_accum_adamw over [begin,end) of the layer (same arguments, same bits),
+ *                         enqueued on the context's stream behind whatever `producer_stream` holds
+ *                         at the call (gradients, the norm scalar); then the layer's event is
+ *                         recorded.  The same hp (same t), d_sqnorm and gradient buffers as the
+ *                         immediate part; the buffers must stay untouched until the layer is done.
+ *   gs_defer_wait_layer   the deadline: work enqueued on `consumer_stream` after this call -- the
+ *                         layer's forward, or whatever overwrites its gradient buffers -- starts
+ *                         only when the layer's latest deferred step has finished.  A layer with
+ *                         nothing deferred costs nothing.  Device-side wait; the host does not block.
+ *   gs_defer_layer_done   1 if the layer's latest deferred step has finished (or none was enqueued),
+ *                         0 if it is still pending, -1 on error.  Never blocks.
+ *   gs_defer_ctx_sync     blocks until everything enqueued on the context has finished.
+ *   gs_defer_ctx_stream   the context's hipStream_t (owned by the context), e.g. for a caller that wants
+ *                         to check that it runs beside its own streams: the runtime multiplexes streams
+ *                         onto a few hardware queues, and two streams on one queue take turns.
+ * One calling thread at a time per context; all calls with the device current on which it was made.
+ */
+typedef struct gs_defer_ctx gs_defer_ctx;
+gs_status gs_defer_ctx_create(gs_defer_ctx **out, int max_layers, int num_cus);
+gs_status gs_defer_ctx_destroy(gs_defer_ctx *ctx); /* waits for pending work, frees everything */
+gs_status gs_defer_layer_step(gs_defer_ctx *ctx, int layer, float *p, float *m, float *v, uint16_t *w_bf16,
+                              const uint16_t *const *grads, int k, int64_t begin, int64_t end,
+                              const gs_adamw_hparams *hp, const double *d_sqnorm, void *producer_stream);
+gs_status gs_defer_wait_layer(gs_defer_ctx *ctx, int layer, void *consumer_stream);
+int gs_defer_layer_done(gs_defer_ctx *ctx, int layer);
+gs_status gs_defer_ctx_sync(gs_defer_ctx *ctx);
+void *gs_defer_ctx_stream(gs_defer_ctx *ctx);
+
 /* ------------------------------------------------------------------------------------------
  * Step for states that live in pinned host memory (Sec. 2.2: for each parameter chunk, load
  * gradients + master parameters + optimizer states, step, write back; Sec. 4.3 the optimizer

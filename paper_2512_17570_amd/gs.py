@@ -488,3 +488,64 @@ def pinned_f32_set(n: int, count: int = 3):
         for _, ptr in got:
             gs_pinned_free(ptr)
         return None
+
+
+_lib.gs_defer_ctx_create.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_int]
+_lib.gs_defer_ctx_create.restype = ctypes.c_int
+_lib.gs_defer_ctx_destroy.argtypes = [_vp]
+_lib.gs_defer_ctx_destroy.restype = ctypes.c_int
+_lib.gs_defer_ctx_sync.argtypes = [_vp]
+_lib.gs_defer_ctx_sync.restype = ctypes.c_int
+_lib.gs_defer_layer_step.argtypes = [_vp, ctypes.c_int, _vp, _vp, _vp, _vp, _pp, ctypes.c_int, _i64, _i64,
+                                     ctypes.POINTER(gs_adamw_hparams), _vp, _vp]
+_lib.gs_defer_layer_step.restype = ctypes.c_int
+_lib.gs_defer_wait_layer.argtypes = [_vp, ctypes.c_int, _vp]
+_lib.gs_defer_wait_layer.restype = ctypes.c_int
+_lib.gs_defer_layer_done.argtypes = [_vp, ctypes.c_int]
+_lib.gs_defer_layer_done.restype = ctypes.c_int
+
+
+def gs_defer_ctx_create(max_layers: int, num_cus: int = 0, check: bool = True):
+    out = ctypes.c_void_p()
+    st = _lib.gs_defer_ctx_create(ctypes.byref(out), max_layers, num_cus)
+    if check:
+        _check(st, "gs_defer_ctx_create", True)
+        return out.value
+    return st, out.value
+
+
+_lib.gs_defer_ctx_stream.argtypes = [_vp]
+_lib.gs_defer_ctx_stream.restype = _vp
+
+
+def gs_defer_ctx_stream(ctx) -> int | None:
+    """Raw hipStream_t of the context's stream (owned by the context)."""
+    return _lib.gs_defer_ctx_stream(ctx)
+
+
+def gs_defer_ctx_destroy(ctx, check: bool = True) -> int:
+    return _check(_lib.gs_defer_ctx_destroy(ctx), "gs_defer_ctx_destroy", check)
+
+
+def gs_defer_ctx_sync(ctx, check: bool = True) -> int:
+    return _check(_lib.gs_defer_ctx_sync(ctx), "gs_defer_ctx_sync", check)
+
+
+def gs_defer_layer_step(ctx, layer: int, p, m, v, w_bf16, grads, begin: int, end: int, hp, d_sqnorm=None,
+                        producer_stream=None, check: bool = True, k: int | None = None) -> int:
+    tab, kk = _table(grads) if grads is not None else (None, 0)
+    for j, g in enumerate(grads or ()):
+        _need(g, end, 2, f"grads[{j}]")
+    for x, eb, nm in ((p, 4, "p"), (m, 4, "m"), (v, 4, "v"), (w_bf16, 2, "w_bf16")):
+        _need(x, end, eb, nm)
+    st = _lib.gs_defer_layer_step(ctx, layer, _addr(p), _addr(m), _addr(v), _addr(w_bf16), tab, kk if k is None else k,
+                                  begin, end, _hp(hp), _addr(d_sqnorm), _stream(producer_stream))
+    return _check(st, "gs_defer_layer_step", check)
+
+
+def gs_defer_wait_layer(ctx, layer: int, consumer_stream=None, check: bool = True) -> int:
+    return _check(_lib.gs_defer_wait_layer(ctx, layer, _stream(consumer_stream)), "gs_defer_wait_layer", check)
+
+
+def gs_defer_layer_done(ctx, layer: int) -> int:
+    return int(_lib.gs_defer_layer_done(ctx, layer))

@@ -343,6 +343,12 @@ hipError_t hipStreamWaitEvent(hipStream_t s, hipEvent_t e, unsigned)
     return hipSuccess;
 }
 
+hipError_t hipEventQuery(hipEvent_t e)
+{
+    std::lock_guard<std::mutex> g(e->mu);
+    return e->completed >= e->recorded ? hipSuccess : hipErrorNotReady;
+}
+
 // the stand-in keeps no clock: every interval reads as zero ("too short to tell")
 hipError_t hipEventElapsedTime(float *ms, hipEvent_t, hipEvent_t)
 {

@@ -510,6 +510,74 @@ static void test_hip_failures(const std::string &dir)
     for (int a = 0; a < 3; ++a) gs_pinned_free(h[a]);
 }
 
+// The deferred part of each layer's step with its deadline: the immediate part [0,s) runs on the
+// caller's stream, the deferred part [s,n) on the context's stream behind late-produced gradients,
+// and a consumer stream (the layer's "forward") that waited for the layer must find every element of
+// the layer stepped exactly once.
+static void test_defer(int layers, int64_t n, int num_cus)
+{
+    gs_defer_ctx *ctx = nullptr;
+    CHECK(gs_defer_ctx_create(&ctx, layers, num_cus) == GS_OK, "defer create");
+    hipStream_t mainstream = nullptr, fwd = nullptr;
+    CHECK(hipStreamCreateWithFlags(&mainstream, hipStreamNonBlocking) == hipSuccess, "main stream");
+    CHECK(hipStreamCreateWithFlags(&fwd, hipStreamNonBlocking) == hipSuccess, "forward stream");
+    std::vector<Layer *> Ls;
+    std::vector<std::vector<float>> P, M, V;
+    std::vector<std::atomic<int>> bad_seen(layers);
+    const int64_t s = n * 2 / 5 + 3;
+    for (int l = 0; l < layers; ++l) {
+        Ls.push_back(new Layer(n, 100 + l));
+        P.push_back(Ls[l]->p0); M.push_back(Ls[l]->m0); V.push_back(Ls[l]->v0);
+        bad_seen[l].store(-1);
+    }
+    CHECK(gs_defer_layer_done(ctx, 0) == 1 && gs_defer_layer_done(ctx, layers) == -1, "done before any step");
+    CHECK(gs_defer_wait_layer(ctx, 1, fwd) == GS_OK, "wait on a layer with nothing deferred");
+    for (int l = 0; l < layers; ++l) {
+        std::vector<uint16_t> *g = &Ls[l]->g;
+        std::vector<uint16_t> real = *g;
+        std::fill(g->begin(), g->end(), (uint16_t)0x7777);
+        hipmock_enqueue(mainstream, [g, real] {
+            std::this_thread::sleep_for(std::chrono::milliseconds(15));
+            *g = real;
+        });
+        const uint16_t *gt[1] = {g->data()};
+        CHECK(gs_accum_adamw(P[l].data(), M[l].data(), V[l].data(), Ls[l]->w.data(), gt, 1, 0, s, &HP, nullptr, mainstream) == GS_OK,
+              "immediate part");
+        CHECK(gs_defer_layer_step(ctx, l, P[l].data(), M[l].data(), V[l].data(), Ls[l]->w.data(), gt, 1, s, n, &HP, nullptr,
+                                  mainstream) == GS_OK, "deferred part");
+    }
+    // the forward of layer l: waits for the immediate part (an event on the caller's stream) and for the
+    // layer's deadline, then looks at the whole layer.  Last layer first: its deferred step is the last to
+    // finish, so a deadline tied to the wrong layer's event lets this forward run early.
+    for (int l = layers - 1; l >= 0; --l) {
+        hipEvent_t imm = nullptr;
+        CHECK(hipEventCreateWithFlags(&imm, hipEventDisableTiming) == hipSuccess, "event");
+        CHECK(hipEventRecord(imm, mainstream) == hipSuccess && hipStreamWaitEvent(fwd, imm, 0) == hipSuccess, "immediate done");
+        CHECK(gs_defer_wait_layer(ctx, l, fwd) == GS_OK, "deadline");
+        Layer *L = Ls[l];
+        const float *p = P[l].data(), *m = M[l].data(), *v = V[l].data();
+        std::atomic<int> *out = &bad_seen[l];
+        hipmock_enqueue(fwd, [L, p, m, v, out, n] {
+            int bad = 0;
+            for (int64_t i = 0; i < n; ++i) {
+                if (p[i] != L->p0[i] + 1.0f || m[i] != L->m0[i] * 2.0f || v[i] != L->v0[i] + (float)L->g[i]) ++bad;
+                if (L->w[i] != (uint16_t)((i + 1) & 0xffff)) ++bad;
+            }
+            out->store(bad);
+        });
+        CHECK(hipStreamSynchronize(fwd) == hipSuccess, "forward sync");
+        CHECK(hipEventDestroy(imm) == hipSuccess, "event destroy");
+        CHECK(bad_seen[l].load() == 0, "forward of layer %d saw %d elements not stepped exactly once", l, bad_seen[l].load());
+    }
+    CHECK(gs_defer_ctx_sync(ctx) == GS_OK, "defer sync");
+    for (int l = 0; l < layers; ++l) CHECK(gs_defer_layer_done(ctx, l) == 1, "layer %d done after sync", l);
+    CHECK(gs_defer_layer_step(ctx, layers, P[0].data(), M[0].data(), V[0].data(), Ls[0]->w.data(), nullptr, 1, 0, 1, &HP, nullptr,
+                              mainstream) == GS_ERR_INVALID_ARG, "layer out of range");
+    CHECK(gs_defer_ctx_destroy(ctx) == GS_OK, "defer destroy");
+    CHECK(hipStreamDestroy(mainstream) == hipSuccess && hipStreamDestroy(fwd) == hipSuccess, "streams");
+    for (Layer *L : Ls) delete L;
+}
+
 int main(int argc, char **argv)
 {
     if (argc < 2) {
@@ -532,6 +600,8 @@ int main(int argc, char **argv)
     test_tier_call_does_not_wait(dir);
     test_tier_failures(dir);
     test_hip_failures(dir);
+    test_defer(4, 5000, 0);
+    test_defer(3, 777, 64);
     printf(g_fail ? "FAILED (%d)\n" : "PIPELINE OK\n", g_fail);
     return g_fail ? 1 : 0;
 }

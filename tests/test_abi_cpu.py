@@ -288,6 +288,18 @@ def test_cu_stream_rejects_without_gpu():
     assert gs.gs_cu_stream_destroy(None, check=False) == gs.GS_ERR_INVALID_ARG
 
 
+def test_defer_api_rejects_without_gpu():
+    for layers, cus in ((0, 0), (-3, 0), (65537, 0), (4, -1)):
+        st, ctx = gs.gs_defer_ctx_create(layers, cus, check=False)
+        assert st == gs.GS_ERR_INVALID_ARG and not ctx
+    assert gs.gs_defer_ctx_sync(None, check=False) == gs.GS_ERR_INVALID_ARG
+    assert gs.gs_defer_ctx_destroy(None, check=False) == gs.GS_ERR_INVALID_ARG
+    assert gs.gs_defer_wait_layer(None, 0, 0, check=False) == gs.GS_ERR_INVALID_ARG
+    assert gs.gs_defer_layer_done(None, 0) == -1
+    assert gs.gs_defer_layer_step(None, 0, FP, FM, FV, FW, [FG0], 0, 10, GOOD_HP, producer_stream=0,
+                                  check=False) == gs.GS_ERR_INVALID_ARG
+
+
 def test_error_raises_through_binding():
     with pytest.raises(gs.GsError) as ei:
         _adamw(begin=3, end=2, check=True)

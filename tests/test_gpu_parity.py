@@ -1181,6 +1181,62 @@ def test_random_sweep_of_host_resident_and_tiered_layouts(tmp_path):
                 gs.gs_pinned_free(ptr)
 
 
+# ----------------------------------------------------------------------------- deferred schedule
+@pytest.mark.parametrize("num_cus", [0, 64])
+def test_deferred_schedule_equals_full_step_and_keeps_the_deadline(num_cus):
+    """Sec. 4.4 as a library object: per layer, the immediate part on the caller's stream, the deferred
+    part through a gs_defer_ctx (its own stream, optionally on a CU budget).  A consumer stream that
+    waited for a layer's deadline reads that layer's working weights: they have to be the full step's,
+    bit for bit; so are p, m, v after the context is synced, and they match the oracle."""
+    layers, n, k = 3, 2048 * 300 + 17, 4
+    s_pt = int(0.4 * n) + 1
+    cases = [DeviceCase(n, k, seed=40 + l) for l in range(layers)]
+    sq = torch.zeros(1, dtype=torch.float64, device=DEV)
+    ws = cases[0].ws
+    for l, c in enumerate(cases):
+        gs.gs_grad_sqnorm(c.grads, 0, n, sq, ws, accumulate=(l > 0))
+    torch.cuda.synchronize()
+    S = float(sq.item())
+    ref = []
+    for c in cases:
+        p, m, v, w = c.clone_states()
+        gs.gs_accum_adamw(p, m, v, w, c.grads, 0, n, HP, sq)
+        ref.append((p, m, v, w))
+    torch.cuda.synchronize()
+    ctx = gs.gs_defer_ctx_create(layers, num_cus)
+    assert gs.gs_defer_layer_done(ctx, 0) == 1 and gs.gs_defer_layer_done(ctx, layers) == -1
+    fwd = torch.cuda.Stream()
+    got = [c.clone_states() for c in cases]
+    snaps = []
+    try:
+        for l, c in enumerate(cases):
+            p, m, v, w = got[l]
+            gs.gs_accum_adamw(p, m, v, w, c.grads, 0, s_pt, HP, sq)                       # immediate, caller's stream
+            gs.gs_defer_layer_step(ctx, l, p, m, v, w, c.grads, s_pt, n, HP, sq)          # deferred, context's stream
+        for l in range(layers):
+            ev = torch.cuda.Event()
+            ev.record()
+            fwd.wait_event(ev)                                                            # immediate parts
+            gs.gs_defer_wait_layer(ctx, l, fwd)                                           # the deadline
+            with torch.cuda.stream(fwd):
+                snaps.append(got[l][3].clone())                                           # the "forward" reads w
+        fwd.synchronize()
+        for l in range(layers):
+            assert torch.equal(snaps[l].view(torch.int16), ref[l][3].view(torch.int16)), f"layer {l}: forward saw stale weights"
+        gs.gs_defer_ctx_sync(ctx)
+        assert all(gs.gs_defer_layer_done(ctx, l) == 1 for l in range(layers))
+        st = gs.gs_defer_layer_step(ctx, layers, *got[0], cases[0].grads, 0, n, HP, sq, check=False)
+        assert st == gs.GS_ERR_INVALID_ARG
+    finally:
+        gs.gs_defer_ctx_destroy(ctx)
+    c_clip = O.clip_coef(S, HP.max_grad_norm)
+    for l, c in enumerate(cases):
+        for a, b, nm in zip(got[l], ref[l], "pmvw"):
+            assert torch.equal(a.view(torch.int32 if a.dtype == torch.float32 else torch.int16),
+                               b.view(torch.int32 if b.dtype == torch.float32 else torch.int16)), f"layer {l} {nm}: deferred != full"
+        compare_states(got[l], c.oracle_step(HP, c_clip), f"deferred layer {l}")
+
+
 # ----------------------------------------------------------------------------- the ABI from plain C
 def _c_demo():
     import sys

@@ -19,7 +19,7 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 CSRC = os.path.join(ROOT, "paper_2512_17570_amd", "csrc")
 MOCK = os.path.join(ROOT, "tests", "hipmock")
-HOST_SOURCES = ["gs_api.hip", "gs_stream.hip", "gs_tier.hip"]
+HOST_SOURCES = ["gs_api.hip", "gs_stream.hip", "gs_tier.hip", "gs_defer.hip"]
 
 
 def _build(src_dir: str, out: str, tsan: bool, sanitize: str = "thread") -> None:
@@ -113,6 +113,13 @@ def test_c_program_sequence_completes_under_null_stream_orderings(tmp_path, tsan
 
 
 MUTANTS = [
+    ("deferred_deadline_not_waited_for", "gs_defer.hip",
+     '    hipError_t e = hipStreamWaitEvent(static_cast<hipStream_t>(consumer_stream), c->done[layer], 0);\n',
+     '    hipError_t e = hipSuccess;\n'),
+    ("deferred_step_ignores_producer", "gs_defer.hip",
+     '    if ((e = hipStreamWaitEvent(c->stream, c->ev_producer, 0)) != hipSuccess)\n        return hip_fail(e, "hipStreamWaitEvent(producer)");\n', ""),
+    ("deferred_layer_event_on_wrong_layer", "gs_defer.hip",
+     'hipEventRecord(c->done[layer], c->stream)', 'hipEventRecord(c->done[0], c->stream)'),
     ("kernel_ignores_producer", "gs_stream.hip",
      '    GS_TRY(hipStreamWaitEvent(c->s_comp, c->ev_producer, 0), "hipStreamWaitEvent(producer)");\n', ""),
     ("staged_upload_ignores_pending_download", "gs_stream.hip",
