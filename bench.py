@@ -37,7 +37,7 @@ HEADLINE = "gpt65b_layer_h8192_k16"
 # HBM bytes per gs_accum_adamw launch on the headline workload from rocprofv3 --pmc runs
 # (FETCH_SIZE and WRITE_SIZE, each scaled by the same counter's reading on a plain copy kernel
 # of known size); see profiles/.  None until measured for the workload being run.
-MEASURED_TRAFFIC_BYTES = {"gpt65b_layer_h8192_k16": 46_712_699_261,    # profiles/gs_step_gpt65b_layer_h8192_k16.txt
+MEASURED_TRAFFIC_BYTES = {"gpt65b_layer_h8192_k16": 46_712_867_821,    # profiles/gs_step_gpt65b_layer_h8192_k16.txt
                           "gpt_h4096_k8": 8_458_116_813}               # profiles/gs_step_gpt_h4096_k8.txt
 
 
