@@ -330,13 +330,15 @@ typedef struct gs_stream_ctx gs_stream_ctx;
 gs_status gs_stream_ctx_create(gs_stream_ctx **out, int64_t chunk_elems, int slots);
 
 /*
- * What a staged context found when it was created.  The pipeline of Sec. 4.3 only pays if uploads
- * and downloads run at the same time, but the runtime may put the two copy streams on one
- * hardware queue, where they take turns (half the rate).  gs_stream_ctx_create therefore times a
- * short burst of copies each way, alone and together, and swaps the download stream for a fresh
- * one (up to six times) while the two still take turns.  Returns 1 if the copies ran side by side
- * in the end, 0 if they still took turns, -1 if the check was skipped (slots under 1 MB, in-place
- * context) or ctx is NULL.  No HIP call.
+ * What a staged context found when it was created.  The pipeline of Sec. 4.3 only pays if upload,
+ * kernel and download run at the same time, but the runtime may put two of the context's three
+ * streams on one hardware queue, where they take turns (upload and download on one queue, or the
+ * kernel's wait for the next upload holding back the previous download: half the rate either way).
+ * gs_stream_ctx_create therefore checks each pair -- a burst of copies on one stream, a 4 KB copy
+ * on the other that has to finish while the burst is still running -- and swaps a colliding stream
+ * for a fresh one (up to nine times).  Returns 1 if all three ran side by side in the end, 0 if a
+ * pair still took turns, -1 if the check was skipped (slots under 1 MB, in-place context) or ctx
+ * is NULL.  No HIP call.
  */
 int gs_stream_ctx_copies_overlap(const gs_stream_ctx *ctx);
 

@@ -179,65 +179,66 @@ static gs_status staged_chunk(gs_stream_ctx *c, StepArgs &A, float *host_p, floa
 
 }  // namespace gs
 
-// Staged mode lives on its upload and download copies running at the same time.  HIP multiplexes a
-// process's streams onto a few hardware queues, and when the two copy streams share one, the two
-// directions take turns: half the rate, with nothing else to show for it.  Which queue a new stream
-// gets depends on the streams the process already has, so the context checks: a burst of uploads
-// and a burst of downloads of `bytes` each, timed one after the other and then together (the
-// download stream released by an event on the upload stream).  Together in clearly less than the
-// sum means side by side.  Returns 1 (side by side), 0 (in turns) or -1 (a HIP call failed; the
-// error text is set).
-static int copies_run_side_by_side(hipStream_t up, hipStream_t down, float *dev, float *host, size_t bytes)
+// Staged mode lives on three streams that really run side by side.  HIP multiplexes a process's
+// streams onto a few hardware queues, and a hardware queue takes its work in order: when the upload
+// and the download stream share one, the two directions take turns; when the compute stream shares
+// one with a copy stream, its wait for the next chunk's upload also holds back the previous chunk's
+// download queued behind it.  Either way the pipeline runs at half its rate with nothing else to
+// show for it.  Which queue a new stream gets depends on the streams the process already has, so
+// the context checks each pair: `busy` is given a burst of copies of `bytes` each, and `other`,
+// released by an event at the start of the burst, a 4 KB copy the other way.  If the small copy is
+// done in under half the burst's time, the two streams run side by side.  Returns 1 (side by
+// side, or too short to tell), 0 (in turns) or -1 (a HIP call failed; the error text is set).
+static int overtakes(hipStream_t busy, hipStream_t other, bool busy_uploads, float *dev, float *host, size_t bytes)
 {
-    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
     int verdict = -1;
-    float t_up = 0.f, t_down = 0.f, t_a = 0.f, t_b = 0.f;
+    float t_burst = 0.f, t_small = 0.f;
     char *d = reinterpret_cast<char *>(dev), *h = reinterpret_cast<char *>(host);
-    const int reps = 2;
-    auto fail = [&](hipError_t e, const char *what) {
+    const size_t small = 4096;
+    const hipMemcpyKind burst_kind = busy_uploads ? hipMemcpyHostToDevice : hipMemcpyDeviceToHost;
+    const hipMemcpyKind small_kind = busy_uploads ? hipMemcpyDeviceToHost : hipMemcpyHostToDevice;
+    void *burst_dst = busy_uploads ? static_cast<void *>(d) : static_cast<void *>(h);
+    const void *burst_src = busy_uploads ? static_cast<const void *>(h) : static_cast<const void *>(d);
+    void *small_dst = busy_uploads ? static_cast<void *>(h + bytes) : static_cast<void *>(d + bytes);
+    const void *small_src = busy_uploads ? static_cast<const void *>(d + bytes) : static_cast<const void *>(h + bytes);
+    hipError_t e = hipSuccess;
+    auto fail = [&](const char *what) {
         hip_fail(e, what);
         return -1;
     };
-    hipError_t e = hipSuccess;
     for (auto &x : ev)
         if ((e = hipEventCreateWithFlags(&x, 0)) != hipSuccess) {
             x = nullptr;
-            verdict = fail(e, "hipEventCreateWithFlags(copy check)");
+            verdict = fail("hipEventCreateWithFlags(stream check)");
             goto done;
         }
-    // warm both paths, then each direction alone
-    if ((e = hipMemcpyAsync(d, h, bytes, hipMemcpyHostToDevice, up)) != hipSuccess ||
-        (e = hipMemcpyAsync(h + bytes, d + bytes, bytes, hipMemcpyDeviceToHost, down)) != hipSuccess ||
-        (e = hipStreamSynchronize(up)) != hipSuccess || (e = hipStreamSynchronize(down)) != hipSuccess) {
-        verdict = fail(e, "copy check (warm-up)");
+    // warm both paths
+    if ((e = hipMemcpyAsync(burst_dst, burst_src, bytes, burst_kind, busy)) != hipSuccess ||
+        (e = hipMemcpyAsync(small_dst, small_src, small, small_kind, other)) != hipSuccess ||
+        (e = hipStreamSynchronize(busy)) != hipSuccess || (e = hipStreamSynchronize(other)) != hipSuccess) {
+        verdict = fail("stream check (warm-up)");
         goto done;
     }
-    if ((e = hipEventRecord(ev[0], up)) != hipSuccess) { verdict = fail(e, "hipEventRecord(copy check)"); goto done; }
-    for (int r = 0; r < reps; ++r)
-        if ((e = hipMemcpyAsync(d, h, bytes, hipMemcpyHostToDevice, up)) != hipSuccess) { verdict = fail(e, "hipMemcpyAsync(copy check)"); goto done; }
-    if ((e = hipEventRecord(ev[1], up)) != hipSuccess || (e = hipStreamSynchronize(up)) != hipSuccess ||
-        (e = hipEventElapsedTime(&t_up, ev[0], ev[1])) != hipSuccess) { verdict = fail(e, "copy check (upload alone)"); goto done; }
-    if ((e = hipEventRecord(ev[2], down)) != hipSuccess) { verdict = fail(e, "hipEventRecord(copy check)"); goto done; }
-    for (int r = 0; r < reps; ++r)
-        if ((e = hipMemcpyAsync(h + bytes, d + bytes, bytes, hipMemcpyDeviceToHost, down)) != hipSuccess) { verdict = fail(e, "hipMemcpyAsync(copy check)"); goto done; }
-    if ((e = hipEventRecord(ev[3], down)) != hipSuccess || (e = hipStreamSynchronize(down)) != hipSuccess ||
-        (e = hipEventElapsedTime(&t_down, ev[2], ev[3])) != hipSuccess) { verdict = fail(e, "copy check (download alone)"); goto done; }
-    // both at once
-    if ((e = hipEventRecord(ev[0], up)) != hipSuccess || (e = hipStreamWaitEvent(down, ev[0], 0)) != hipSuccess) { verdict = fail(e, "copy check (start)"); goto done; }
-    for (int r = 0; r < reps; ++r)
-        if ((e = hipMemcpyAsync(d, h, bytes, hipMemcpyHostToDevice, up)) != hipSuccess ||
-            (e = hipMemcpyAsync(h + bytes, d + bytes, bytes, hipMemcpyDeviceToHost, down)) != hipSuccess) { verdict = fail(e, "hipMemcpyAsync(copy check)"); goto done; }
-    if ((e = hipEventRecord(ev[1], up)) != hipSuccess || (e = hipEventRecord(ev[3], down)) != hipSuccess ||
-        (e = hipStreamSynchronize(up)) != hipSuccess || (e = hipStreamSynchronize(down)) != hipSuccess ||
-        (e = hipEventElapsedTime(&t_a, ev[0], ev[1])) != hipSuccess || (e = hipEventElapsedTime(&t_b, ev[0], ev[3])) != hipSuccess) {
-        verdict = fail(e, "copy check (both)");
+    if ((e = hipEventRecord(ev[0], busy)) != hipSuccess || (e = hipStreamWaitEvent(other, ev[0], 0)) != hipSuccess) {
+        verdict = fail("stream check (start)");
         goto done;
     }
-    {
-        const float both = t_a > t_b ? t_a : t_b;
-        // too short to tell (a runtime without a clock, tiny slots): take the streams as they are
-        verdict = (t_up + t_down < 0.05f) ? 1 : (both < 0.8f * (t_up + t_down) ? 1 : 0);
+    for (int r = 0; r < 2; ++r)
+        if ((e = hipMemcpyAsync(burst_dst, burst_src, bytes, burst_kind, busy)) != hipSuccess) {
+            verdict = fail("hipMemcpyAsync(stream check)");
+            goto done;
+        }
+    if ((e = hipEventRecord(ev[1], busy)) != hipSuccess ||
+        (e = hipMemcpyAsync(small_dst, small_src, small, small_kind, other)) != hipSuccess ||
+        (e = hipEventRecord(ev[2], other)) != hipSuccess || (e = hipStreamSynchronize(busy)) != hipSuccess ||
+        (e = hipStreamSynchronize(other)) != hipSuccess || (e = hipEventElapsedTime(&t_burst, ev[0], ev[1])) != hipSuccess ||
+        (e = hipEventElapsedTime(&t_small, ev[0], ev[2])) != hipSuccess) {
+        verdict = fail("stream check (burst)");
+        goto done;
     }
+    // a burst too short to time (a runtime without a clock): take the streams as they are
+    verdict = (t_burst < 0.05f) ? 1 : (t_small < 0.5f * t_burst ? 1 : 0);
 done:
     for (auto x : ev)
         if (x) (void)hipEventDestroy(x);
@@ -340,31 +341,42 @@ gs_status gs_stream_ctx_create(gs_stream_ctx **out, int64_t chunk_elems, int slo
         destroy_partial(c);
         return GS_ERR_NOMEM;
     }
-    // Make sure upload and download really overlap; if they take turns, try further download streams
-    // (the rejected ones stay alive meanwhile, so each new one is handed another hardware queue).
-    const size_t probe_bytes = std::min<size_t>((size_t)64 << 20, bytes / 2) & ~(size_t)255;
+    // Make sure the three streams really run side by side; while a pair takes turns, swap one of the
+    // two for a fresh stream (the rejected ones stay alive meanwhile, so each new one is handed another
+    // hardware queue).
+    const size_t probe_bytes = std::min<size_t>((size_t)64 << 20, bytes / 2) & ~(size_t)4095;
     if (probe_bytes >= ((size_t)1 << 20)) {
         void *host = nullptr;
-        e = hipHostMalloc(&host, 2 * probe_bytes, hipHostMallocDefault);
+        e = hipHostMalloc(&host, probe_bytes + 8192, hipHostMallocDefault);
         if (e != hipSuccess) {
-            hip_fail(e, "hipHostMalloc(copy check)");
+            hip_fail(e, "hipHostMalloc(stream check)");
             (void)hipGetLastError();
             destroy_partial(c);
             return GS_ERR_NOMEM;
         }
-        memset(host, 0, 2 * probe_bytes);
+        memset(host, 0, probe_bytes + 8192);
+        float *hbuf = static_cast<float *>(host);
         std::vector<hipStream_t> rejected;
-        int verdict = copies_run_side_by_side(c->s_h2d, c->s_d2h, c->pool, static_cast<float *>(host), probe_bytes);
-        for (int attempt = 0; verdict == 0 && attempt < 6; ++attempt) {
+        int verdict = 0;
+        for (int attempt = 0; attempt < 10; ++attempt) {
+            const int ud = overtakes(c->s_h2d, c->s_d2h, true, c->pool, hbuf, probe_bytes);
+            const int uc = ud < 0 ? -1 : overtakes(c->s_h2d, c->s_comp, true, c->pool, hbuf, probe_bytes);
+            const int dc = uc < 0 ? -1 : overtakes(c->s_d2h, c->s_comp, false, c->pool, hbuf, probe_bytes);
+            if (ud < 0 || uc < 0 || dc < 0) {
+                verdict = -1;
+                break;
+            }
+            verdict = (ud && uc && dc) ? 1 : 0;
+            if (verdict == 1 || attempt == 9) break;
             hipStream_t cand = nullptr;
             if ((e = hipStreamCreateWithFlags(&cand, hipStreamNonBlocking)) != hipSuccess) {
                 hip_fail(e, "hipStreamCreateWithFlags");
                 verdict = -1;
                 break;
             }
-            rejected.push_back(c->s_d2h);
-            c->s_d2h = cand;
-            verdict = copies_run_side_by_side(c->s_h2d, c->s_d2h, c->pool, static_cast<float *>(host), probe_bytes);
+            hipStream_t &victim = !ud ? c->s_d2h : c->s_comp;      // the compute stream if it is the one that collides
+            rejected.push_back(victim);
+            victim = cand;
         }
         for (hipStream_t r : rejected) (void)hipStreamDestroy(r);
         (void)hipHostFree(host);

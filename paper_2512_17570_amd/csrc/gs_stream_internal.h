@@ -26,7 +26,7 @@ struct gs_stream_ctx {
     std::vector<hipEvent_t> ev_h2d, ev_comp, ev_d2h;
     std::vector<char> used;                 // ev_d2h[slot] has been recorded at least once
     int64_t next_chunk = 0;                 // running chunk counter across calls -> slot rotation
-    int copies_overlap = -1;                // creation-time check: 1 uploads and downloads ran side by side, 0 they
+    int copies_overlap = -1;                // creation-time check: 1 the three streams ran side by side, 0 a pair
                                             // still took turns after every retry, -1 not checked (tiny slots)
 };
 
