@@ -51,6 +51,9 @@ def parse():
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="headline workload only: skip the short runs of the other configurations")
     ap.add_argument("--no-ceiling", action="store_true", help="skip the no-arithmetic stream-mix probe kernels")
+    ap.add_argument("--k-sweep", action="store_true",
+                    help="instead of the step benchmark: gs_accum_adamw and gs_grad_sqnorm on the workload's layer for "
+                         "k = 1..32 gradient buffers (bytes per parameter 2k+26 and 2k), one JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise copy of 2^28 floats (1 GiB in, 1 GiB out) three times before the "
                          "timed region, as the known-size reference for rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
@@ -1003,6 +1006,55 @@ def bench_resident(args, wl, full=True):
     return out
 
 
+def bench_k_sweep(args, wl):
+    """The two kernels on one resident layer of the workload's shape as the number of bf16 gradient
+    buffers goes from 1 to 32: how the achieved bandwidth moves with the share of gradient reads
+    (2k of 2k+26 bytes) and with the kernel shapes chosen per k."""
+    import torch
+
+    from paper_2512_17570_amd import gs
+    from paper_2512_17570_amd import inputs as I
+
+    dev = "cuda:0"
+    props = torch.cuda.get_device_properties(0)
+    n = I.layer_numel(wl.h)
+    ks = (1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, 15, 16, 20, 24, 32)
+    p, m, v = I.make_states(n, wl.seed, dev)
+    grads = I.make_grads(n, max(ks), wl.grad_sigma, wl.seed, dev)
+    w = torch.zeros(n, dtype=torch.bfloat16, device=dev)
+    sq = torch.zeros(1, dtype=torch.float64, device=dev)
+    ws = torch.empty(gs.gs_sqnorm_workspace_bytes(), dtype=torch.uint8, device=dev)
+    rows = {}
+    for k in ks:
+        g = grads[:k]
+        hp = gs.HParams(wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay, wl.max_grad_norm, wl.step)
+        for _ in range(max(2, args.warmup)):
+            gs.gs_grad_sqnorm(g, 0, n, sq, ws)
+            gs.gs_accum_adamw(p, m, v, w, g, 0, n, hp, sq)
+        torch.cuda.synchronize()
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+        for i in range(args.steps):
+            ev[i][0].record()
+            gs.gs_grad_sqnorm(g, 0, n, sq, ws)
+            ev[i][1].record()
+            gs.gs_accum_adamw(p, m, v, w, g, 0, n, hp, sq)
+            ev[i][2].record()
+        torch.cuda.synchronize()
+        rows[str(k)] = {"gs_accum_adamw": _kernel_entry([e[1].elapsed_time(e[2]) for e in ev], 2 * k + 26, n),
+                        "gs_grad_sqnorm": _kernel_entry([e[0].elapsed_time(e[1]) for e in ev], 2 * k, n),
+                        "read_share_of_step_bytes": (2 * k + 12) / (2 * k + 26)}
+    best = max(rows, key=lambda kk: rows[kk]["gs_accum_adamw"]["frac"])
+    rec = _base_record(wl, props, n / (rows[str(wl.k)]["gs_accum_adamw"]["avg_ms"] * 1e-3) if str(wl.k) in rows else 0.0,
+                       args.steps, args.warmup, rows[str(wl.k)]["gs_accum_adamw"]["avg_ms"] if str(wl.k) in rows else 0.0,
+                       {"n_params": n, "layers": 1, "sweep": "k_grad_buffers 1..32"})
+    rec["metric"] = "params/s, gs_accum_adamw alone at the workload's k (k sweep)"
+    rec["k_sweep"] = rows
+    rec["best_k_for_step_frac"] = int(best)
+    rec["roofline"] = None
+    rec["cpu_baseline"] = None
+    return rec
+
+
 def _brief(rec, keys):
     return {k: rec[k] for k in keys if k in rec}
 
@@ -1106,6 +1158,9 @@ def main():
         sys.exit(2)
     wl = I.WORKLOADS[args.workload]
     torch.cuda.set_device(0)
+    if args.k_sweep:
+        print(json.dumps(bench_k_sweep(args, wl)))
+        return
     if "immediate_frac" in wl.extra:
         rec = bench_split(args, wl)
     elif "host_share" in wl.extra:
