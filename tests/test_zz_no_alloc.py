@@ -57,3 +57,37 @@ def test_noalloc_norm_on_a_side_stream_and_too_large_is_refused():
     assert st == gs.GS_ERR_TOO_LARGE
     torch.cuda.synchronize()
     assert float(sq.item()) == -1.0
+
+
+def test_noalloc_norm_and_step_replay_from_a_hip_graph():
+    """What the entry point is for: under stream capture nothing may allocate.  After one call outside
+    capture (which looks up the array's address), the no-allocation norm and the step are captured
+    once and replayed three times with eager work between the replays; every replay has to equal
+    the eager run with the workspace entry point, bit for bit."""
+    from test_gpu_parity import HP, compare_states
+    n = 2048 * 150 + 9
+    case = DeviceCase(n, 8, seed=172)
+    p, m, v, w = case.clone_states()
+    sq_g = torch.zeros(1, dtype=torch.float64, device=DEV)
+    gs.gs_grad_sqnorm_noalloc(case.grads, 0, n, sq_g)                # first call on the device: outside capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        gs.gs_grad_sqnorm_noalloc(case.grads, 0, n, sq_g)
+        gs.gs_accum_adamw(p, m, v, w, case.grads, 0, n, HP, sq_g)
+    torch.cuda.synchronize()
+    eager = case.clone_states()
+    first = None
+    for it in range(3):
+        g.replay()
+        torch.cuda.synchronize()
+        gs.gs_grad_sqnorm(case.grads, 0, n, case.sq, case.ws)        # eager work between replays, workspace variant
+        gs.gs_accum_adamw(*eager, case.grads, 0, n, HP, case.sq)
+        torch.cuda.synchronize()
+        assert float(sq_g.item()) == float(case.sq.item())
+        for a, b in zip((p, m, v, w), eager):
+            assert torch.equal(a, b), f"replay {it}"
+        if it == 0:
+            first = [t.clone() for t in (p, m, v, w)]
+    c = O.clip_coef(O.grad_sqnorm(case.h_g), HP.max_grad_norm)
+    compare_states(first, case.oracle_step(HP, c), "no-alloc graph, first replay")
