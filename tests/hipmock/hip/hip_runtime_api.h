@@ -77,5 +77,9 @@ extern "C" void hipmock_set_copy_delay_us(int us);
 /* the nth call from now of the named API (hipEventRecord, hipStreamWaitEvent, hipLaunchHostFunc,
  * hipMemcpyAsync) returns hipErrorUnknown and does nothing; api == NULL disarms */
 extern "C" void hipmock_fail_nth(const char *api, int nth);
+/* the next `count` calls of hipEventElapsedTime return these values (then zero again) */
+extern "C" void hipmock_script_elapsed_ms(const float *values, int count);
+/* streams created and not yet destroyed */
+extern "C" int hipmock_live_streams(void);
 #endif
 #endif

@@ -349,11 +349,30 @@ hipError_t hipEventQuery(hipEvent_t e)
     return e->completed >= e->recorded ? hipSuccess : hipErrorNotReady;
 }
 
-// the stand-in keeps no clock: every interval reads as zero ("too short to tell")
+// The stand-in keeps no clock: an interval reads as zero ("too short to tell") unless a test has
+// scripted the next readings with hipmock_script_elapsed_ms.
+static std::mutex g_elapsed_mu;
+static std::deque<float> g_elapsed_script;
 hipError_t hipEventElapsedTime(float *ms, hipEvent_t, hipEvent_t)
 {
-    *ms = 0.0f;
+    std::lock_guard<std::mutex> g(g_elapsed_mu);
+    if (g_elapsed_script.empty()) {
+        *ms = 0.0f;
+    } else {
+        *ms = g_elapsed_script.front();
+        g_elapsed_script.pop_front();
+    }
     return hipSuccess;
+}
+void hipmock_script_elapsed_ms(const float *values, int count)
+{
+    std::lock_guard<std::mutex> g(g_elapsed_mu);
+    g_elapsed_script.assign(values, values + count);
+}
+int hipmock_live_streams(void)
+{
+    std::lock_guard<std::mutex> g(g_streams_mu);
+    return (int)g_all_streams.size();
 }
 
 hipError_t hipEventSynchronize(hipEvent_t e)

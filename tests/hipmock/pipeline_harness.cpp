@@ -510,6 +510,45 @@ static void test_hip_failures(const std::string &dir)
     for (int a = 0; a < 3; ++a) gs_pinned_free(h[a]);
 }
 
+// The staged context's creation-time check that its three streams run side by side, driven by scripted
+// clock readings: a pair that takes turns has its colliding stream swapped for a fresh one (and the
+// rejected stream destroyed), a context whose streams never get apart still works and says so.
+static void test_stream_check(bool ever_apart)
+{
+    const int before = hipmock_live_streams();
+    std::vector<float> script;
+    auto pair = [&](bool apart) { script.push_back(2.0f); script.push_back(apart ? 0.1f : 1.9f); };
+    if (ever_apart) {
+        pair(true); pair(false); pair(true);      // attempt 1: upload/compute collide -> the compute stream is swapped
+        pair(false); pair(true); pair(true);      // attempt 2: upload/download collide -> the download stream is swapped
+        pair(true); pair(true); pair(true);       // attempt 3: all three side by side
+    } else {
+        for (int i = 0; i < 40; ++i) pair(false);
+    }
+    hipmock_script_elapsed_ms(script.data(), (int)script.size());
+    gs_stream_ctx *ctx = nullptr;
+    CHECK(gs_stream_ctx_create(&ctx, 200000, 2) == GS_OK, "create staged (stream check)");
+    hipmock_script_elapsed_ms(nullptr, 0);
+    CHECK(gs_stream_ctx_copies_overlap(ctx) == (ever_apart ? 1 : 0), "copies_overlap = %d", gs_stream_ctx_copies_overlap(ctx));
+    CHECK(hipmock_live_streams() == before + 3, "%d streams alive beside the context's three", hipmock_live_streams() - before - 3);
+    Layer A(300000, 7);
+    float *h[3];
+    const std::vector<float> *src[3] = {&A.p0, &A.m0, &A.v0};
+    for (int a = 0; a < 3; ++a) {
+        h[a] = (float *)gs_pinned_alloc((size_t)A.n * 4);
+        memcpy(h[a], src[a]->data(), (size_t)A.n * 4);
+    }
+    const uint16_t *gt[1] = {A.g.data()};
+    CHECK(gs_stream_layer_step(ctx, h[0], h[1], h[2], A.w.data(), gt, 1, A.n, &HP, nullptr, nullptr) == GS_OK, "step");
+    CHECK(gs_stream_ctx_sync(ctx) == GS_OK, "sync");
+    A.check(h[0], h[1], h[2], 0, A.n, 0, 1, "after the stream check");
+    A.check_w(1, "after the stream check");
+    CHECK(gs_stream_ctx_destroy(ctx) == GS_OK, "destroy");
+    CHECK(hipmock_live_streams() == before, "streams leaked: %d", hipmock_live_streams() - before);
+    for (int a = 0; a < 3; ++a) gs_pinned_free(h[a]);
+    CHECK(gs_stream_ctx_copies_overlap(nullptr) == -1, "copies_overlap(NULL)");
+}
+
 // The deferred part of each layer's step with its deadline: the immediate part [0,s) runs on the
 // caller's stream, the deferred part [s,n) on the context's stream behind late-produced gradients,
 // and a consumer stream (the layer's "forward") that waited for the layer must find every element of
@@ -600,6 +639,8 @@ int main(int argc, char **argv)
     test_tier_call_does_not_wait(dir);
     test_tier_failures(dir);
     test_hip_failures(dir);
+    test_stream_check(true);
+    test_stream_check(false);
     test_defer(4, 5000, 0);
     test_defer(3, 777, 64);
     printf(g_fail ? "FAILED (%d)\n" : "PIPELINE OK\n", g_fail);

@@ -113,6 +113,10 @@ def test_c_program_sequence_completes_under_null_stream_orderings(tmp_path, tsan
 
 
 MUTANTS = [
+    ("stream_check_never_swaps_the_colliding_stream", "gs_stream.hip",
+     "            if (verdict == 1 || attempt == 9) break;\n", "            break;\n"),
+    ("stream_check_leaks_rejected_streams", "gs_stream.hip",
+     "        for (hipStream_t r : rejected) (void)hipStreamDestroy(r);\n", ""),
     ("deferred_deadline_not_waited_for", "gs_defer.hip",
      '    hipError_t e = hipStreamWaitEvent(static_cast<hipStream_t>(consumer_stream), c->done[layer], 0);\n',
      '    hipError_t e = hipSuccess;\n'),
