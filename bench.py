@@ -331,6 +331,20 @@ def bench_split(args, wl, brief=False):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps
 
+    # split == full, bit for bit, on the tensors being timed: the full step on the states, the immediate and
+    # the deferred part (two streams) on a copy of them, same hyper-parameters and norm
+    p2, m2, v2, w2 = p.clone(), m.clone(), v.clone(), torch.zeros_like(w)
+    torch.cuda.synchronize()
+    gs.gs_accum_adamw(p, m, v, w, grads, 0, n, hp, sq)
+    torch.cuda.synchronize()
+    gs.gs_accum_adamw(p2, m2, v2, w2, grads, 0, s_pt, hp, sq, stream=sa)
+    gs.gs_accum_adamw(p2, m2, v2, w2, grads, s_pt, n, hp, sq, stream=sb)
+    torch.cuda.synchronize()
+    split_equals_full = all(torch.equal(a.view(torch.int32 if a.dtype == torch.float32 else torch.int16),
+                                        b.view(torch.int32 if b.dtype == torch.float32 else torch.int16))
+                            for a, b in ((p, p2), (m, m2), (v, v2), (w, w2)))
+    del p2, m2, v2, w2
+
     t_full = alone(full, sb, args.steps)
     t_imm = alone(immediate, sb, args.steps)
     t_def = alone(deferred, sb, args.steps)
@@ -386,6 +400,7 @@ def bench_split(args, wl, brief=False):
                        "traffic": None, "algorithmic_bytes_per_launch": n * bpp, "avg_launch_ms": t_full}
     gemm_flop = 2.0 * tokens * wl.h * wl.h
     rec["split"] = {
+        "split_equals_full_bitwise": bool(split_equals_full),
         "full_ms": t_full, "immediate_ms": t_imm, "deferred_alone_ms": t_def,
         "deferred_alone_GBps": (n - s_pt) * bpp / (t_def * 1e-3) / 1e9,
         "gemm_alone_ms": t_gemm, "gemm_alone_TFLOPs": gemm_flop / (t_gemm * 1e-3) / 1e12,
@@ -1148,6 +1163,7 @@ def other_workloads(args):
         "full_ms": sp["full_ms"], "immediate_ms": sp["immediate_ms"], "deferred_alone_ms": sp["deferred_alone_ms"],
         "full_GBps": r["roofline"]["achieved"], "full_frac": r["roofline"]["frac"],
         "split_vs_full": (sp["immediate_ms"] + sp["deferred_alone_ms"]) / sp["full_ms"],
+        "split_equals_full_bitwise": sp["split_equals_full_bitwise"],
         "gemm": r["config"]["gemm"], "gemms_per_deferred_step": r["config"]["gemms_per_deferred_step"],
         "gemm_alone_ms": sp["gemm_alone_ms"], "gemm_alone_TFLOPs": sp["gemm_alone_TFLOPs"],
         "deferred_beside_gemm_ms": sp["deferred_concurrent_ms"], "gemm_beside_deferred_ms": sp["gemm_concurrent_ms"],
