@@ -1181,6 +1181,48 @@ def test_random_sweep_of_host_resident_and_tiered_layouts(tmp_path):
                 gs.gs_pinned_free(ptr)
 
 
+# ----------------------------------------------------------------------------- staged context: stream check
+def test_staged_context_reports_its_stream_check():
+    """A staged context with slots large enough to time (>= 1 MB) checks at creation that its three
+    streams run side by side and reports 1; tiny slots and in-place contexts skip the check (-1).
+    Contexts created while other streams are alive still come out side by side, and step correctly."""
+    others = [torch.cuda.Stream() for _ in range(5)]
+    x = torch.zeros(1 << 16, device=DEV)
+    for s_ in others:
+        with torch.cuda.stream(s_):
+            x.add_(1.0)
+    torch.cuda.synchronize()
+    tiny = gs.gs_stream_ctx_create(4096, 2)
+    assert gs.gs_stream_ctx_copies_overlap(tiny) == -1
+    gs.gs_stream_ctx_destroy(tiny)
+    inplace = gs.gs_stream_ctx_create_inplace(0)
+    assert gs.gs_stream_ctx_copies_overlap(inplace) == -1
+    gs.gs_stream_ctx_destroy(inplace)
+    assert gs.gs_stream_ctx_copies_overlap(None) == -1
+    n, k = (1 << 21) + 4099, 3
+    case = DeviceCase(n, k, seed=61)
+    case.gpu_sqnorm()
+    ref = run_gpu_step(case, HP)
+    for _ in range(2):
+        ctx = gs.gs_stream_ctx_create(1 << 20, 3)                     # 3 x 3 x 4 MB of slots: the check runs
+        assert gs.gs_stream_ctx_copies_overlap(ctx) == 1
+        bufs = gs.pinned_f32_set(n, 3)
+        assert bufs is not None
+        try:
+            for (t, _), src in zip(bufs, (case.p, case.m, case.v)):
+                t.copy_(src)
+            w = torch.zeros(n, dtype=torch.bfloat16, device=DEV)
+            gs.gs_stream_layer_step(ctx, bufs[0][1], bufs[1][1], bufs[2][1], w, case.grads, n, HP, case.sq)
+            gs.gs_stream_ctx_sync(ctx)
+            for (t, _), want in zip(bufs, ref[:3]):
+                assert torch.equal(t.to(DEV), want)
+            assert torch.equal(w, ref[3])
+        finally:
+            gs.gs_stream_ctx_destroy(ctx)
+            for _, ptr in bufs:
+                gs.gs_pinned_free(ptr)
+
+
 # ----------------------------------------------------------------------------- deferred schedule
 @pytest.mark.parametrize("num_cus", [0, 64])
 def test_deferred_schedule_equals_full_step_and_keeps_the_deadline(num_cus):
